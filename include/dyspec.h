@@ -1,0 +1,181 @@
+/*
+ * dyspec.h -- C ABI of the MI355X (gfx950) library for one DySpec speculative step
+ * (arXiv 2410.11744): greedy token-tree construction, tree-masked attention and
+ * multi-candidate tree verification.
+ *
+ * Conventions shared by every entry point
+ *  - Pointers marked DEVICE address HBM of the current HIP device; pointers marked HOST
+ *    address ordinary host memory that is read before the call returns.  The caller owns
+ *    every buffer; the library allocates nothing and keeps no state between calls.
+ *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
+ *    stream); calls return without synchronising.  Two calls that write the same buffers
+ *    race unless ordered by the stream.
+ *  - Errors are return codes (< 0).  Arguments are validated on the host before anything
+ *    is launched; a call that returns an error has launched nothing.
+ *  - A batch holds n_seq independent sequences packed back to back.  Sequence s owns tree
+ *    rows [node_offset[s], node_offset[s+1]) of every per-node array and prefix rows
+ *    [kv_offset[s], kv_offset[s] + prefix_len[s]) of k_prefix / v_prefix.  Row 0 of each
+ *    tree is the root: the last committed token, whose logits open the tree
+ *    (Section 4.2, first paragraph).  Node indices stored in the arrays (parent, links,
+ *    accepted_nodes, mask bits) are LOCAL to the sequence.
+ *  - Uniform random numbers come from Philox4x32-10 (Salmon et al., SC'11) with key =
+ *    seed and a counter that names each draw by the path of sibling ranks from the root,
+ *    so results do not depend on node numbering or on which kernel makes the draw.
+ */
+#ifndef DYSPEC_H
+#define DYSPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t dyspec_status;
+enum {
+    DYSPEC_OK = 0,
+    DYSPEC_BAD_ARG = -1,             /* null pointer, non-positive size, temperature <= 0 ... */
+    DYSPEC_BAD_SHAPE = -2,           /* offsets not increasing, heads not divisible, ...      */
+    DYSPEC_UNSUPPORTED = -3,         /* dtype / head_dim / vocabulary outside the built kernels */
+    DYSPEC_WORKSPACE_TOO_SMALL = -4,
+    DYSPEC_HIP_ERROR = -5            /* a HIP call failed; hipGetLastError() still holds it   */
+};
+
+/* Tensor element types of dyspec_tree_attn.  DYSPEC_BF16_WAVE: bf16 storage handled by the
+ * one-wavefront-per-row kernel (fp32 arithmetic, any head_dim <= 256) instead of the
+ * matrix-core kernel. */
+enum { DYSPEC_F32 = 0, DYSPEC_BF16 = 1, DYSPEC_BF16_WAVE = 0x101 };
+
+#define DYSPEC_MAX_SEQ 64            /* sequences per call                                */
+#define DYSPEC_MAX_NODES 1024        /* tree rows per sequence, root included             */
+#define DYSPEC_MAX_VOCAB 32768       /* vocabulary handled by the build / verify kernels  */
+
+/* Ragged batch description; all three arrays are HOST memory. */
+typedef struct {
+    int32_t n_seq;                   /* 1 .. DYSPEC_MAX_SEQ                               */
+    const int32_t* node_offset;      /* [n_seq+1] increasing, node_offset[0] = 0          */
+    const int32_t* prefix_len;       /* [n_seq]   >= 0                                    */
+    const int64_t* kv_offset;        /* [n_seq+1] first prefix row of each sequence       */
+} dyspec_batch;
+
+/* A packed batch of token trees; every array is DEVICE memory of length node_offset[n_seq].
+ * Children of a node are linked in the order they were sampled, which is the order
+ * verification must try them (Algorithm 3, loop over CurrentNode.branches). */
+typedef struct {
+    int32_t* parent;                 /* -1 for the root and for rows that were not built  */
+    int32_t* token;                  /* -1 for the root                                   */
+    int32_t* sib_rank;               /* 0 for a first child, 1 for the next sampling ...  */
+    int32_t* first_child;            /* -1 = leaf                                         */
+    int32_t* next_sibling;           /* -1 = last sampled child                           */
+    int32_t* depth;                  /* 0 for the root                                    */
+} dyspec_tree;
+
+/* Words per row of the ancestor bitmask for this batch: ceil(max_s N_s / 64). */
+int32_t dyspec_mask_words(const dyspec_batch* batch);
+
+/* Bytes of DEVICE workspace the named call needs for this batch (0 = none). */
+enum { DYSPEC_WS_BUILD_TREE = 0, DYSPEC_WS_TREE_ATTN = 1, DYSPEC_WS_VERIFY = 2 };
+size_t dyspec_workspace_bytes(int32_t which, const dyspec_batch* batch, int32_t vocab,
+                              int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim);
+
+const char* dyspec_status_string(dyspec_status s);
+
+/*
+ * dyspec_build_tree -- greedy fixed-budget construction of the draft token tree
+ * (Algorithm 1; Section 4.2; Appendix A.1) plus the tree-attention mask (Section 2).
+ *
+ * For each sequence, N = node_offset[s+1]-node_offset[s] rows are built, the root
+ * included.  Starting from the single slot (parent = root, value 1), the slot with the
+ * largest estimated value v is taken (earliest-opened slot on a tie); a token y is drawn
+ * from the parent's draft distribution with the parent's earlier children removed and the
+ * rest renormalised (R); the node is appended; the slots "next sampling at the same
+ * position" with value v*(1-R[y]) and "first child of the new node" with value v*R[y] are
+ * opened (slots of value 0 are not).  Draft distributions are softmax(draft_logits[i]/T_d),
+ * where row i is the distribution that FOLLOWS node i (creation index): the table stands in
+ * for the draft model call of Algorithm 1.  Arithmetic on values and distributions is fp64.
+ * y is the smallest index whose cumulative residual weight exceeds u * (total weight),
+ * u in [0,1) with 24 random bits.
+ *
+ *   draft_logits  DEVICE [sum N, vocab] fp32, row-major
+ *   draft_temp    HOST   [n_seq] > 0
+ *   tree          DEVICE outputs (all six arrays)
+ *   est_value     DEVICE [sum N] fp32: v of the slot each node was drawn from (root: 1)
+ *   anc_mask      DEVICE [sum N, mask_words] u64: bit i of row j set iff local node i is an
+ *                 ancestor of local node j or i == j
+ *   n_built       DEVICE [n_seq]: rows actually built (< N only if no slot of positive
+ *                 value is left); later rows keep parent = token = -1 and their own mask bit
+ *   workspace     DEVICE, dyspec_workspace_bytes(DYSPEC_WS_BUILD_TREE, ...) bytes
+ * vocab <= DYSPEC_MAX_VOCAB, N <= DYSPEC_MAX_NODES.
+ */
+dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab,
+                                const dyspec_batch* batch, const float* draft_temp,
+                                uint64_t seed, const dyspec_tree* tree, float* est_value,
+                                uint64_t* anc_mask, int32_t* n_built,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * dyspec_tree_attn -- one layer of tree attention (Section 2, "Tree Attention";
+ * Appendix C for the block-sparse treatment of the tree part).
+ *
+ * For every tree row j and query head h:
+ *   out[j,h,:] = softmax_k( scale * <q[j,h,:], K[k, h/G, :]> ) . V[k, h/G, :]
+ * over all prefix keys of the sequence and over the tree keys i whose bit is set in
+ * anc_mask row j; G = n_q_heads / n_kv_heads.
+ *
+ *   q, out            DEVICE [sum N, n_q_heads, head_dim]
+ *   k_prefix,v_prefix DEVICE [kv rows, n_kv_heads, head_dim]
+ *   k_tree, v_tree    DEVICE [sum N, n_kv_heads, head_dim]
+ *   anc_mask          DEVICE [sum N, mask_words] as written by dyspec_build_tree
+ *   dtype             DYSPEC_F32 (any head_dim <= 256, multiple of 4) or DYSPEC_BF16
+ *                     (head_dim 64 or 128; matrix-core path, fp32 accumulation)
+ * All tensors are dense row-major and 16-byte aligned.  workspace may be NULL when
+ * dyspec_workspace_bytes(DYSPEC_WS_TREE_ATTN, ...) is 0.
+ */
+dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* v_prefix,
+                               const void* k_tree, const void* v_tree,
+                               const uint64_t* anc_mask, const dyspec_batch* batch,
+                               int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                               int32_t dtype, float softmax_scale, void* out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * dyspec_verify -- vocabulary softmax of every tree row and multi-candidate tree
+ * rejection sampling (Algorithm 3; Appendix A.3; Section 2 for the one-candidate rule).
+ *
+ * Data-parallel part, one workgroup per tree row p: D = softmax(draft_logits[p]/T_d),
+ * R = softmax(target_logits[p]/T_t); for each child n of p in sampling order, with token y:
+ * accept_ratio[n] = R[y]/D[y]; then R <- norm(max(R-D,0)), D[y] <- 0, D <- norm(D)
+ * (scan of p's children ends early when D is empty: the remaining children get ratio -1).
+ * resid_token[p] = draw from the R left after all children (for a leaf: from the target
+ * row itself when emit_bonus != 0, else -1).  These are exactly the quantities the serial
+ * algorithm would compute on reaching p, so the walk below reproduces it.
+ * Walk, one thread per sequence: from the root, try the children in order; child n is
+ * accepted iff c < accept_ratio[n] (equivalently c*D[y] < R[y]), c uniform in [0,1); move to
+ * the accepted child; when none is accepted, or the node is a leaf, emit resid_token and stop.
+ *
+ *   draft_logits, target_logits DEVICE [sum N, vocab] fp32 (row i = distribution after node i)
+ *   draft_temp, target_temp     HOST [n_seq] > 0
+ *   tree                        DEVICE inputs (token, sib_rank, parent, first_child,
+ *                               next_sibling are read; parents must precede children)
+ *   row_stats    DEVICE [sum N,4] fp32: max and sum-exp of draft/T_d, then of target/T_t
+ *   accept_ratio DEVICE [sum N] fp32 (root: 0)
+ *   resid_token  DEVICE [sum N] i32
+ *   accepted_nodes DEVICE [sum N] i32: per sequence, from its node_offset, the accepted
+ *                  local node indices in order (root excluded); n_accepted [n_seq]
+ *   final_token  DEVICE [n_seq]: token emitted where the walk stopped (-1 if none)
+ *   min_margin   DEVICE [n_seq] fp32: smallest |c - accept_ratio| over tested children
+ * Arithmetic is fp32.  vocab <= DYSPEC_MAX_VOCAB.
+ */
+dyspec_status dyspec_verify(const float* draft_logits, const float* target_logits,
+                            int32_t vocab, const dyspec_batch* batch, const dyspec_tree* tree,
+                            const float* draft_temp, const float* target_temp, uint64_t seed,
+                            int32_t emit_bonus, float* row_stats, float* accept_ratio,
+                            int32_t* resid_token, int32_t* accepted_nodes,
+                            int32_t* n_accepted, int32_t* final_token, float* min_margin,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYSPEC_H */

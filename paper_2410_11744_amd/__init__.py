@@ -1,0 +1,9 @@
+"""MI355X-native (gfx950) hot path of one DySpec speculative step (arXiv 2410.11744):
+``build_tree`` (Algorithm 1 + ancestor mask), ``tree_attn`` (tree-masked attention) and
+``verify`` (Algorithm 3).  The work is done by hand-written HIP kernels behind the C ABI
+in ``include/dyspec.h``; this package only marshals arguments."""
+from .binding import (BF16, BF16_WAVE, F32, Batch, BuiltTrees, DyspecError, Tree, VerifyOutput,
+                      build_tree, load_library, status_string, tree_attn, verify)
+
+__all__ = ["BF16", "BF16_WAVE", "F32", "Batch", "BuiltTrees", "DyspecError", "Tree", "VerifyOutput",
+           "build_tree", "load_library", "status_string", "tree_attn", "verify"]

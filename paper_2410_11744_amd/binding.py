@@ -1,0 +1,264 @@
+"""Thin ctypes binding over libdyspec.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in
+``include/dyspec.h``; torch is used for device memory and the current stream.  There is no
+CPU fallback: if the library is missing or fails to load, importing callers get an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+from . import build as _build
+
+F32, BF16, BF16_WAVE = 0, 1, 0x101
+MAX_SEQ, MAX_NODES, MAX_VOCAB = 64, 1024, 32768
+EXPORTS = ("dyspec_mask_words", "dyspec_workspace_bytes", "dyspec_status_string",
+           "dyspec_build_tree", "dyspec_tree_attn", "dyspec_verify")
+
+
+class DyspecError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+class _Batch(ctypes.Structure):
+    _fields_ = [("n_seq", ctypes.c_int32),
+                ("node_offset", ctypes.POINTER(ctypes.c_int32)),
+                ("prefix_len", ctypes.POINTER(ctypes.c_int32)),
+                ("kv_offset", ctypes.POINTER(ctypes.c_int64))]
+
+
+class _Tree(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("parent", "token", "sib_rank", "first_child", "next_sibling", "depth")]
+
+
+_lib = None
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load libdyspec.so (building it first only when nothing is built)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or _build.LIB
+    if not os.path.exists(p):
+        _build.build(force=True)
+    lib = ctypes.CDLL(p)
+    V, I32, U64, SZ, F = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint64, ctypes.c_size_t, ctypes.c_float
+    PB, PT = ctypes.POINTER(_Batch), ctypes.POINTER(_Tree)
+    lib.dyspec_mask_words.restype = I32
+    lib.dyspec_mask_words.argtypes = [PB]
+    lib.dyspec_workspace_bytes.restype = SZ
+    lib.dyspec_workspace_bytes.argtypes = [I32, PB, I32, I32, I32, I32]
+    lib.dyspec_status_string.restype = ctypes.c_char_p
+    lib.dyspec_status_string.argtypes = [I32]
+    lib.dyspec_build_tree.restype = I32
+    lib.dyspec_build_tree.argtypes = [V, I32, PB, ctypes.POINTER(F), U64, PT, V, V, V, V, SZ, V]
+    lib.dyspec_tree_attn.restype = I32
+    lib.dyspec_tree_attn.argtypes = [V, V, V, V, V, V, PB, I32, I32, I32, I32, F, V, V, SZ, V]
+    lib.dyspec_verify.restype = I32
+    lib.dyspec_verify.argtypes = [V, V, I32, PB, PT, ctypes.POINTER(F), ctypes.POINTER(F), U64, I32,
+                                  V, V, V, V, V, V, V, V, SZ, V]
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().dyspec_status_string(status).decode()
+
+
+@dataclass
+class Batch:
+    """Host description of a ragged batch (see dyspec_batch in include/dyspec.h)."""
+    node_offset: np.ndarray      # int32 [n_seq+1]
+    prefix_len: np.ndarray       # int32 [n_seq]
+    kv_offset: np.ndarray        # int64 [n_seq+1]
+
+    @staticmethod
+    def from_sizes(n_nodes: Sequence[int], prefix_len: Optional[Sequence[int]] = None) -> "Batch":
+        n_nodes = list(n_nodes)
+        prefix_len = [0] * len(n_nodes) if prefix_len is None else list(prefix_len)
+        no = np.zeros(len(n_nodes) + 1, dtype=np.int32)
+        no[1:] = np.cumsum(n_nodes)
+        kv = np.zeros(len(n_nodes) + 1, dtype=np.int64)
+        kv[1:] = np.cumsum(prefix_len)
+        return Batch(no, np.asarray(prefix_len, dtype=np.int32), kv)
+
+    @property
+    def n_seq(self) -> int:
+        return int(self.prefix_len.shape[0])
+
+    @property
+    def total_nodes(self) -> int:
+        return int(self.node_offset[-1])
+
+    @property
+    def total_prefix(self) -> int:
+        return int(self.kv_offset[-1])
+
+    def _c(self) -> _Batch:
+        self.node_offset = np.ascontiguousarray(self.node_offset, dtype=np.int32)
+        self.prefix_len = np.ascontiguousarray(self.prefix_len, dtype=np.int32)
+        self.kv_offset = np.ascontiguousarray(self.kv_offset, dtype=np.int64)
+        return _Batch(self.n_seq,
+                      self.node_offset.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                      self.prefix_len.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                      self.kv_offset.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)))
+
+    @property
+    def mask_words(self) -> int:
+        c = self._c()
+        return int(load_library().dyspec_mask_words(ctypes.byref(c)))
+
+
+@dataclass
+class Tree:
+    """Device-resident packed token trees (see dyspec_tree in include/dyspec.h)."""
+    parent: "torch.Tensor"
+    token: "torch.Tensor"
+    sib_rank: "torch.Tensor"
+    first_child: "torch.Tensor"
+    next_sibling: "torch.Tensor"
+    depth: "torch.Tensor"
+
+    def _c(self) -> _Tree:
+        return _Tree(*[_ptr(getattr(self, n), "int32") for n in
+                       ("parent", "token", "sib_rank", "first_child", "next_sibling", "depth")])
+
+    @staticmethod
+    def empty(total_nodes: int, device) -> "Tree":
+        import torch
+        return Tree(*[torch.empty(total_nodes, dtype=torch.int32, device=device) for _ in range(6)])
+
+
+def _ptr(t, want: Optional[str] = None) -> int:
+    if t is None:
+        return 0
+    if not t.is_cuda:
+        raise ValueError("device tensor required")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor required")
+    if want is not None and str(t.dtype) != "torch." + want:
+        raise ValueError(f"expected {want}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream=None) -> int:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _temps(x, n_seq: int):
+    a = np.ascontiguousarray(np.broadcast_to(np.asarray(x, dtype=np.float32), (n_seq,)))
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise DyspecError(status, where)
+
+
+@dataclass
+class BuiltTrees:
+    tree: Tree
+    est_value: "torch.Tensor"      # fp32 [sum N]
+    anc_mask: "torch.Tensor"       # int64 view of u64 [sum N, mask_words]
+    n_built: "torch.Tensor"        # int32 [n_seq]
+
+
+def build_tree(draft_logits, batch: Batch, draft_temp, seed: int, stream=None) -> BuiltTrees:
+    """dyspec_build_tree: greedy token-tree construction (Algorithm 1) + ancestor mask."""
+    import torch
+    lib = load_library()
+    dev = draft_logits.device
+    total, V = batch.total_nodes, int(draft_logits.shape[1])
+    if draft_logits.shape[0] != total:
+        raise ValueError("draft_logits needs one row per tree node")
+    tree = Tree.empty(total, dev)
+    est = torch.empty(total, dtype=torch.float32, device=dev)
+    mask = torch.empty((total, batch.mask_words), dtype=torch.int64, device=dev)
+    nb = torch.empty(batch.n_seq, dtype=torch.int32, device=dev)
+    cb, ct = batch._c(), tree._c()
+    tarr, tptr = _temps(draft_temp, batch.n_seq)
+    st = lib.dyspec_build_tree(_ptr(draft_logits, "float32"), V, ctypes.byref(cb), tptr, ctypes.c_uint64(seed),
+                               ctypes.byref(ct), _ptr(est), _ptr(mask), _ptr(nb), None, 0, _stream(stream))
+    _check(st, "dyspec_build_tree")
+    return BuiltTrees(tree, est, mask, nb)
+
+
+def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, softmax_scale: float,
+              out=None, dtype: Optional[int] = None, stream=None):
+    """dyspec_tree_attn: one layer of tree-masked attention.  q/out [sum N, Hq, d]."""
+    import torch
+    lib = load_library()
+    total, Hq, d = q.shape
+    Hkv = int(k_tree.shape[1])
+    if dtype is None:
+        dtype = {torch.float32: F32, torch.bfloat16: BF16}[q.dtype]
+    if total != batch.total_nodes or k_tree.shape[0] != total or v_tree.shape != k_tree.shape:
+        raise ValueError("q / k_tree / v_tree need one row per tree node")
+    if batch.total_prefix > 0 and (k_prefix.shape[0] < batch.total_prefix or k_prefix.shape[1] != Hkv
+                                   or k_prefix.shape[2] != d or v_prefix.shape != k_prefix.shape):
+        raise ValueError("prefix K/V shape does not match the batch")
+    if anc_mask.shape[0] != total or anc_mask.shape[1] != batch.mask_words:
+        raise ValueError("ancestor mask shape does not match the batch")
+    for t in (k_prefix, v_prefix, k_tree, v_tree):
+        if t is not None and t.dtype != q.dtype:
+            raise ValueError("q, k, v must share a dtype")
+    if out is None:
+        out = torch.empty_like(q)
+    cb = batch._c()
+    st = lib.dyspec_tree_attn(_ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree),
+                              _ptr(anc_mask, "int64"), ctypes.byref(cb), int(Hq), Hkv, int(d), int(dtype),
+                              ctypes.c_float(softmax_scale), _ptr(out), None, 0, _stream(stream))
+    _check(st, "dyspec_tree_attn")
+    return out
+
+
+@dataclass
+class VerifyOutput:
+    row_stats: "torch.Tensor"        # fp32 [sum N, 4]
+    accept_ratio: "torch.Tensor"     # fp32 [sum N]
+    resid_token: "torch.Tensor"      # int32 [sum N]
+    accepted_nodes: "torch.Tensor"   # int32 [sum N]
+    n_accepted: "torch.Tensor"       # int32 [n_seq]
+    final_token: "torch.Tensor"      # int32 [n_seq]
+    min_margin: "torch.Tensor"       # fp32 [n_seq]
+
+    @staticmethod
+    def empty(batch: Batch, device) -> "VerifyOutput":
+        import torch
+        t, s = batch.total_nodes, batch.n_seq
+        f = lambda *sh: torch.empty(sh, dtype=torch.float32, device=device)
+        i = lambda *sh: torch.empty(sh, dtype=torch.int32, device=device)
+        return VerifyOutput(f(t, 4), f(t), i(t), i(t), i(s), i(s), f(s))
+
+
+def verify(draft_logits, target_logits, batch: Batch, tree: Tree, draft_temp, target_temp, seed: int,
+           emit_bonus: bool = True, out: Optional[VerifyOutput] = None, stream=None) -> VerifyOutput:
+    """dyspec_verify: per-row vocabulary softmax + tree rejection sampling (Algorithm 3)."""
+    lib = load_library()
+    total, V = batch.total_nodes, int(draft_logits.shape[1])
+    if draft_logits.shape[0] != total or target_logits.shape != draft_logits.shape:
+        raise ValueError("logit tables need one row per tree node")
+    if out is None:
+        out = VerifyOutput.empty(batch, draft_logits.device)
+    cb, ct = batch._c(), tree._c()
+    da, dp = _temps(draft_temp, batch.n_seq)
+    ta, tp = _temps(target_temp, batch.n_seq)
+    st = lib.dyspec_verify(_ptr(draft_logits, "float32"), _ptr(target_logits, "float32"), V, ctypes.byref(cb),
+                           ctypes.byref(ct), dp, tp, ctypes.c_uint64(seed), int(bool(emit_bonus)),
+                           _ptr(out.row_stats), _ptr(out.accept_ratio), _ptr(out.resid_token),
+                           _ptr(out.accepted_nodes), _ptr(out.n_accepted), _ptr(out.final_token),
+                           _ptr(out.min_margin), None, 0, _stream(stream))
+    _check(st, "dyspec_verify")
+    return out

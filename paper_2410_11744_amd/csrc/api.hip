@@ -1,0 +1,156 @@
+// extern "C" boundary: host-side validation, then kernel launches.  See include/dyspec.h
+// for the contract of every entry point.
+#include "dyspec_device.h"
+
+namespace dyspec {
+
+static dyspec_status check_batch(const dyspec_batch* b, bool need_prefix, SeqArgs* sa)
+{
+    if (!b || !b->node_offset) return DYSPEC_BAD_ARG;
+    if (b->n_seq < 1 || b->n_seq > DYSPEC_MAX_SEQ) return DYSPEC_BAD_SHAPE;
+    if (need_prefix && (!b->prefix_len || !b->kv_offset)) return DYSPEC_BAD_ARG;
+    if (b->node_offset[0] != 0) return DYSPEC_BAD_SHAPE;
+    sa->n_seq = b->n_seq;
+    for (int s = 0; s < b->n_seq; ++s) {
+        const int n = b->node_offset[s + 1] - b->node_offset[s];
+        if (n < 1 || n > DYSPEC_MAX_NODES) return DYSPEC_BAD_SHAPE;
+        sa->node_off[s] = b->node_offset[s];
+        sa->prefix_len[s] = 0;
+        sa->kv_off[s] = 0;
+        sa->temp_d[s] = sa->temp_t[s] = 1.0f;
+        if (need_prefix) {
+            if (b->prefix_len[s] < 0 || b->kv_offset[s] < 0) return DYSPEC_BAD_SHAPE;
+            if (b->kv_offset[s + 1] < b->kv_offset[s] + b->prefix_len[s]) return DYSPEC_BAD_SHAPE;
+            sa->prefix_len[s] = b->prefix_len[s];
+            sa->kv_off[s] = b->kv_offset[s];
+        }
+    }
+    sa->node_off[b->n_seq] = b->node_offset[b->n_seq];
+    return DYSPEC_OK;
+}
+
+static bool tree_ok(const dyspec_tree* t)
+{
+    return t && t->parent && t->token && t->sib_rank && t->first_child && t->next_sibling && t->depth;
+}
+
+static int mask_words_of(const dyspec_batch* b)
+{
+    int mx = 1;
+    for (int s = 0; s < b->n_seq; ++s) mx = max(mx, b->node_offset[s + 1] - b->node_offset[s]);
+    return (mx + 63) / 64;
+}
+
+}  // namespace dyspec
+
+using namespace dyspec;
+
+extern "C" {
+
+int32_t dyspec_mask_words(const dyspec_batch* batch)
+{
+    SeqArgs sa;
+    if (check_batch(batch, false, &sa) != DYSPEC_OK) return 0;
+    return mask_words_of(batch);
+}
+
+size_t dyspec_workspace_bytes(int32_t, const dyspec_batch*, int32_t, int32_t, int32_t, int32_t)
+{
+    return 0;   // every kernel keeps its scratch in registers and LDS
+}
+
+const char* dyspec_status_string(dyspec_status s)
+{
+    switch (s) {
+        case DYSPEC_OK: return "ok";
+        case DYSPEC_BAD_ARG: return "bad argument";
+        case DYSPEC_BAD_SHAPE: return "bad shape";
+        case DYSPEC_UNSUPPORTED: return "unsupported dtype, head_dim or vocabulary";
+        case DYSPEC_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case DYSPEC_HIP_ERROR: return "HIP error";
+        default: return "unknown status";
+    }
+}
+
+dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab, const dyspec_batch* batch,
+                                const float* draft_temp, uint64_t seed, const dyspec_tree* tree,
+                                float* est_value, uint64_t* anc_mask, int32_t* n_built,
+                                void*, size_t, void* hip_stream)
+{
+    SeqArgs sa;
+    const dyspec_status st = check_batch(batch, false, &sa);
+    if (st != DYSPEC_OK) return st;
+    if (!draft_logits || !draft_temp || !tree_ok(tree) || !est_value || !anc_mask || !n_built) return DYSPEC_BAD_ARG;
+    if (vocab < 1) return DYSPEC_BAD_ARG;
+    if (vocab > DYSPEC_MAX_VOCAB) return DYSPEC_UNSUPPORTED;
+    for (int s = 0; s < sa.n_seq; ++s) {
+        if (!(draft_temp[s] > 0.0f)) return DYSPEC_BAD_ARG;
+        sa.temp_d[s] = draft_temp[s];
+    }
+    const hipError_t e = launch_build_tree(draft_logits, vocab, sa, seed, *tree, est_value, anc_mask,
+                                           mask_words_of(batch), n_built, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
+}
+
+dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* v_prefix,
+                               const void* k_tree, const void* v_tree, const uint64_t* anc_mask,
+                               const dyspec_batch* batch, int32_t n_q_heads, int32_t n_kv_heads,
+                               int32_t head_dim, int32_t dtype, float softmax_scale, void* out,
+                               void*, size_t, void* hip_stream)
+{
+    SeqArgs sa;
+    const dyspec_status st = check_batch(batch, true, &sa);
+    if (st != DYSPEC_OK) return st;
+    if (!q || !k_tree || !v_tree || !anc_mask || !out) return DYSPEC_BAD_ARG;
+    bool any_prefix = false;
+    for (int s = 0; s < sa.n_seq; ++s) any_prefix |= sa.prefix_len[s] > 0;
+    if (any_prefix && (!k_prefix || !v_prefix)) return DYSPEC_BAD_ARG;
+    if (n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads != 0) return DYSPEC_BAD_SHAPE;
+    if (!(softmax_scale > 0.0f)) return DYSPEC_BAD_ARG;
+    bool force_simple = false;
+    if (dtype == DYSPEC_BF16 || dtype == DYSPEC_BF16_WAVE) {
+        force_simple = dtype == DYSPEC_BF16_WAVE;
+        dtype = DYSPEC_BF16;
+        if (!force_simple && head_dim != 64 && head_dim != 128) return DYSPEC_UNSUPPORTED;
+        if (force_simple && (head_dim < 1 || head_dim > 256)) return DYSPEC_UNSUPPORTED;
+    } else if (dtype == DYSPEC_F32) {
+        if (head_dim < 1 || head_dim > 256) return DYSPEC_UNSUPPORTED;
+    } else {
+        return DYSPEC_UNSUPPORTED;
+    }
+    AttnArgs a;
+    a.q = q; a.kp = k_prefix; a.vp = v_prefix; a.kt = k_tree; a.vt = v_tree;
+    a.mask = anc_mask; a.out = out;
+    a.mask_words = mask_words_of(batch);
+    a.Hq = n_q_heads; a.Hkv = n_kv_heads; a.d = head_dim; a.scale = softmax_scale;
+    const hipError_t e = launch_tree_attn(a, sa, dtype, force_simple, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
+}
+
+dyspec_status dyspec_verify(const float* draft_logits, const float* target_logits, int32_t vocab,
+                            const dyspec_batch* batch, const dyspec_tree* tree, const float* draft_temp,
+                            const float* target_temp, uint64_t seed, int32_t emit_bonus,
+                            float* row_stats, float* accept_ratio, int32_t* resid_token,
+                            int32_t* accepted_nodes, int32_t* n_accepted, int32_t* final_token,
+                            float* min_margin, void*, size_t, void* hip_stream)
+{
+    SeqArgs sa;
+    const dyspec_status st = check_batch(batch, false, &sa);
+    if (st != DYSPEC_OK) return st;
+    if (!draft_logits || !target_logits || !tree_ok(tree) || !draft_temp || !target_temp || !row_stats ||
+        !accept_ratio || !resid_token || !accepted_nodes || !n_accepted || !final_token || !min_margin)
+        return DYSPEC_BAD_ARG;
+    if (vocab < 1) return DYSPEC_BAD_ARG;
+    if (vocab > DYSPEC_MAX_VOCAB) return DYSPEC_UNSUPPORTED;
+    for (int s = 0; s < sa.n_seq; ++s) {
+        if (!(draft_temp[s] > 0.0f) || !(target_temp[s] > 0.0f)) return DYSPEC_BAD_ARG;
+        sa.temp_d[s] = draft_temp[s];
+        sa.temp_t[s] = target_temp[s];
+    }
+    const hipError_t e = launch_verify(draft_logits, target_logits, vocab, sa, *tree, seed, emit_bonus != 0,
+                                       row_stats, accept_ratio, resid_token, accepted_nodes, n_accepted,
+                                       final_token, min_margin, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
+}
+
+}  // extern "C"

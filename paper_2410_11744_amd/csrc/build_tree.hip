@@ -1,0 +1,171 @@
+// Greedy fixed-budget token-tree construction (Algorithm 1, Section 4.2, Appendix A.1)
+// and the ancestor bitmask of tree attention (Section 2) for gfx950.
+//
+// One 1024-thread workgroup builds one sequence's tree without leaving the GPU.  The
+// paper keeps the expandable slots in a heap on the host; here the frontier (at most two
+// new slots per node) lives in LDS and the pop is a workgroup arg-max, which costs less
+// than a heap's pointer chasing at these sizes.  Each expansion is one pass over the
+// parent's draft row held in registers: fp64 softmax weights, workgroup sum and scan for
+// the inverse-CDF draw.  fp64 keeps every discrete decision (which slot, which token) equal
+// to an fp64 evaluation of the algorithm except at relative margins near 1e-13.
+#include "vocab_common.h"
+
+namespace dyspec {
+
+constexpr int kMaxSlots = 2 * DYSPEC_MAX_NODES + 2;
+
+struct BuildShared {
+    double slot_value[kMaxSlots];       // < 0: closed
+    int slot_parent[kMaxSlots];
+    int n_children[DYSPEC_MAX_NODES];
+    int last_child[DYSPEC_MAX_NODES];
+    int token[DYSPEC_MAX_NODES];
+    int first_child[DYSPEC_MAX_NODES];
+    int next_sibling[DYSPEC_MAX_NODES];
+    int depth[DYSPEC_MAX_NODES];
+    uint2 pk[DYSPEC_MAX_NODES];
+    CdfScratch cdf;
+    double best_v[kWaves];
+    int best_i[kWaves];
+    float fred[kWaves];
+    int n_slots;
+    int pick;
+};
+
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void build_tree_kernel(
+    const float* __restrict__ draft_logits, int V, SeqArgs sa, uint64_t seed,
+    dyspec_tree tree, float* __restrict__ est_value, uint64_t* __restrict__ anc_mask,
+    int mask_words, int* __restrict__ n_built)
+{
+    __shared__ BuildShared sh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int seq = blockIdx.x;
+    const int base = sa.node_off[seq];
+    const int N = sa.node_off[seq + 1] - base;
+    const double temp = (double)sa.temp_d[seq];
+
+    // ---- initial state: every row unbuilt, root slot open
+    for (int i = tid; i < N; i += kBlock) {
+        sh.n_children[i] = 0; sh.last_child[i] = -1; sh.token[i] = -1;
+        sh.first_child[i] = -1; sh.next_sibling[i] = -1; sh.depth[i] = 0;
+        tree.parent[base + i] = -1; tree.token[base + i] = -1; tree.sib_rank[base + i] = 0;
+        tree.first_child[base + i] = -1; tree.next_sibling[base + i] = -1; tree.depth[base + i] = 0;
+        est_value[base + i] = (i == 0) ? 1.0f : 0.0f;
+        for (int w = 0; w < mask_words; ++w)
+            anc_mask[(size_t)(base + i) * mask_words + w] = (w == i / 64) ? (1ull << (i % 64)) : 0ull;
+    }
+    for (int s = tid; s < kMaxSlots; s += kBlock) sh.slot_value[s] = -1.0;
+    __syncthreads();
+    if (tid == 0) {
+        sh.slot_value[0] = 1.0; sh.slot_parent[0] = 0; sh.n_slots = 1;
+        sh.pk[0] = root_key((uint32_t)seq);
+    }
+    __syncthreads();
+
+    int n = 1;
+    while (n < N) {
+        // ---- pop: open slot of largest value, earliest-opened on ties
+        const int n_slots = sh.n_slots;
+        double bv = -1.0; int bi = 0x7fffffff;
+        for (int s = tid; s < n_slots; s += kBlock) {
+            const double v = sh.slot_value[s];
+            if (v > bv) { bv = v; bi = s; }           // s ascends: ties keep the earlier slot
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double ov = __shfl_xor(bv, o, kWave);
+            const int oi = __shfl_xor(bi, o, kWave);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        if (lane == 0) { sh.best_v[wave] = bv; sh.best_i[wave] = bi; }
+        __syncthreads();
+        if (tid == 0) {
+            double v = sh.best_v[0]; int i = sh.best_i[0];
+            for (int w = 1; w < kWaves; ++w)
+                if (sh.best_v[w] > v || (sh.best_v[w] == v && sh.best_i[w] < i)) { v = sh.best_v[w]; i = sh.best_i[w]; }
+            sh.pick = (v > 0.0) ? i : -1;
+        }
+        __syncthreads();
+        const int pick = sh.pick;
+        if (pick < 0) break;                           // frontier is empty
+        const int p = sh.slot_parent[pick];
+        const double v = sh.slot_value[pick];
+        const int rank = sh.n_children[p];
+
+        // ---- residual draft distribution of p: softmax weights, earlier children removed
+        float x[kMaxSeg][4];
+        load_row<VEC>(draft_logits + (size_t)(base + p) * V, V, x);
+        float mx[1] = { -INFINITY };
+#pragma unroll
+        for (int j = 0; j < kMaxSeg; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mx[0] = fmaxf(mx[0], x[j][e]);
+        block_max<1>(mx, sh.fred);
+        const double m = (double)mx[0] / temp;
+        double w[kMaxSeg][4];
+#pragma unroll
+        for (int j = 0; j < kMaxSeg; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                w[j][e] = (tok_index(j, e) < V) ? exp((double)x[j][e] / temp - m) : 0.0;
+        for (int c = sh.first_child[p]; c >= 0; c = sh.next_sibling[c]) {
+            const int y = sh.token[c];
+            if (((y % kSeg) >> 2) == tid) {
+#pragma unroll
+                for (int j = 0; j < kMaxSeg; ++j)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (j == y / kSeg && e == (y & 3)) w[j][e] = 0.0;
+            }
+        }
+
+        // ---- draw the token
+        const double u = (double)u01(seed, sh.pk[p], (uint32_t)rank, KIND_BUILD);
+        double W, wy;
+        const int y = block_inverse_cdf<double>(w, u, &sh.cdf, &W, &wy);
+        if (y < 0) break;                              // nothing left to sample under p
+
+        // ---- append node n, open its two slots
+        const int i = n;
+        if (tid == 0) {
+            const double Ry = wy / W;
+            sh.slot_value[pick] = -1.0;
+            sh.token[i] = y; sh.depth[i] = sh.depth[p] + 1;
+            if (sh.last_child[p] < 0) { sh.first_child[p] = i; tree.first_child[base + p] = i; }
+            else { sh.next_sibling[sh.last_child[p]] = i; tree.next_sibling[base + sh.last_child[p]] = i; }
+            sh.last_child[p] = i; sh.n_children[p] = rank + 1;
+            sh.pk[i] = child_key(seed, sh.pk[p], (uint32_t)rank);
+            tree.parent[base + i] = p; tree.token[base + i] = y; tree.sib_rank[base + i] = rank;
+            tree.depth[base + i] = sh.depth[i];
+            est_value[base + i] = (float)v;
+            const double v0 = v * Ry, v1 = v * (1.0 - Ry);
+            int ns = sh.n_slots;
+            if (v1 > 0.0) { sh.slot_value[ns] = v1; sh.slot_parent[ns] = p; ++ns; }   // next sampling at this position
+            if (v0 > 0.0) { sh.slot_value[ns] = v0; sh.slot_parent[ns] = i; ++ns; }   // first child of the new node
+            sh.n_slots = ns;
+        }
+        if (tid < mask_words) {
+            const uint64_t up = anc_mask[(size_t)(base + p) * mask_words + tid];
+            anc_mask[(size_t)(base + i) * mask_words + tid] = up | ((tid == i / 64) ? (1ull << (i % 64)) : 0ull);
+        }
+        ++n;
+        __syncthreads();
+    }
+    if (tid == 0) n_built[seq] = n;
+}
+
+hipError_t launch_build_tree(const float* draft_logits, int V, const SeqArgs& sa, uint64_t seed,
+                             const dyspec_tree& tree, float* est_value, uint64_t* anc_mask,
+                             int mask_words, int* n_built, hipStream_t stream)
+{
+    if (V % 4 == 0)
+        build_tree_kernel<true><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
+                                                                 anc_mask, mask_words, n_built);
+    else
+        build_tree_kernel<false><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
+                                                                  anc_mask, mask_words, n_built);
+    return hipGetLastError();
+}
+
+}  // namespace dyspec

@@ -1,0 +1,136 @@
+"""GPU parity: dyspec_build_tree and dyspec_verify against the CPU oracle (through the C ABI)."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import compare_trees, compare_verify, oracle_trees
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def dy():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2410_11744_amd as m
+    m.load_library()
+    return m
+
+
+def logits(n, V, sigma, tsigma, seed):
+    rng = np.random.default_rng(seed)
+    d = (rng.standard_normal((n, V)) * sigma).astype(np.float32)
+    t = (d + rng.standard_normal((n, V)) * tsigma).astype(np.float32)
+    return d, t
+
+
+CASES = [
+    # (nodes per seq, V, sigma, target sigma, temps, seed)
+    ((32,), 1000, 2.0, 0.5, (1.0,), 0),                     # tiny config
+    ((13,), 3, 1.0, 1.0, (1.0,), 1),                        # V not a multiple of 4, tiny vocabulary
+    ((40,), 130, 2.0, 1.0, (0.7,), 2),                      # scalar-load path, ragged last segment
+    ((128,), 32000, 3.0, 1.0, (0.6,), 3),                   # 7B-shaped logits
+    ((1,), 64, 1.0, 1.0, (1.0,), 4),                        # root only
+    ((2,), 8, 1.0, 1.0, (0.9,), 5),                         # single child
+    ((64, 7, 200, 1), 5000, 3.0, 1.5, (0.6, 1.0, 0.8, 1.0), 6),   # ragged batch, V spans two segments
+    ((300,), 32768, 3.0, 0.8, (0.6,), 7),                   # largest vocabulary, several mask words
+]
+
+
+@pytest.mark.parametrize("nodes,V,sigma,tsigma,temps,seed", CASES)
+def test_build_and_verify_match_oracle(dy, nodes, V, sigma, tsigma, temps, seed):
+    print(f"case nodes={nodes} V={V} seed={seed}", flush=True)
+    batch = dy.Batch.from_sizes(nodes)
+    d, t = logits(sum(nodes), V, sigma, tsigma, 100 + seed)
+    dd, tt = torch.from_numpy(d).cuda(), torch.from_numpy(t).cuda()
+    built = dy.build_tree(dd, batch, temps, seed)
+    torch.cuda.synchronize()
+    trees = oracle_trees(d, nodes, temps, seed)
+    full = compare_trees(built, batch, trees)
+    assert full == len(nodes), "an oracle decision had a margin below 1e-9: pick another seed"
+    for bonus in (True, False):
+        out = dy.verify(dd, tt, batch, built.tree, temps, temps, seed, emit_bonus=bonus)
+        torch.cuda.synchronize()
+        compared, skipped = compare_verify(out, batch, trees, d, t, temps, temps, seed, emit_bonus=bonus)
+        assert compared + skipped == len(nodes)
+        assert compared >= 1
+
+
+def test_verify_many_seeds_accept_paths(dy):
+    """Same tree, many Philox seeds: accepted path and final token agree wherever the
+    oracle's decision margins are not tiny; the skipped fraction stays small."""
+    nodes, V = (48,), 2000
+    batch = dy.Batch.from_sizes(nodes)
+    d, t = logits(48, V, 3.0, 1.0, 77)
+    dd, tt = torch.from_numpy(d).cuda(), torch.from_numpy(t).cuda()
+    total = skipped = 0
+    for seed in range(40):
+        built = dy.build_tree(dd, batch, (0.6,), seed)
+        trees = oracle_trees(d, nodes, (0.6,), seed)
+        assert compare_trees(built, batch, trees) == 1
+        out = dy.verify(dd, tt, batch, built.tree, (0.6,), (0.8,), seed)
+        c, s = compare_verify(out, batch, trees, d, t, (0.6,), (0.8,), seed)
+        total += c
+        skipped += s
+    assert total >= 36
+
+
+def _hand_tree(dy, token, parent):
+    fc, ns, dep = oracle.links_from_parent(parent)
+    rank = np.zeros(len(parent), np.int32)
+    cnt = {}
+    for i, p in enumerate(parent):
+        if p >= 0:
+            rank[i] = cnt.get(p, 0)
+            cnt[p] = rank[i] + 1
+    mk = lambda a: torch.from_numpy(np.asarray(a, dtype=np.int32)).cuda()
+    tree = dy.Tree(mk(parent), mk(token), mk(rank), mk(fc), mk(ns), mk(dep))
+    return tree, (np.asarray(token, np.int32), fc, ns)
+
+
+def test_verify_hand_built_edge_cases(dy):
+    """Draft exhausted after a reject (ratio -1 for later siblings), zero-probability drafts,
+    V = 2 and V = 1 vocabularies, identical draft and target."""
+    cases = []
+    # draft one-hot on token 1, target one-hot on token 0: reject, then D is empty
+    cases.append((np.array([[-3000.0, 0.0]] * 3, np.float32), np.array([[0.0, -3000.0]] * 3, np.float32),
+                  [-1, 1, 0], [-1, 0, 0]))
+    # V = 2, children (1, 0) with a real residual update
+    cases.append((np.log(np.array([[0.5, 0.5]] * 3)).astype(np.float32),
+                  np.log(np.array([[0.8, 0.2]] * 3)).astype(np.float32), [-1, 1, 0], [-1, 0, 0]))
+    # V = 1 chain
+    cases.append((np.zeros((3, 1), np.float32), np.zeros((3, 1), np.float32), [-1, 0, 0], [-1, 0, 1]))
+    # identical distributions, branching tree, V = 4
+    same = np.log(np.array([[0.4, 0.3, 0.2, 0.1]] * 5)).astype(np.float32)
+    cases.append((same, same.copy(), [-1, 2, 0, 3, 1], [-1, 0, 0, 1, 1]))
+    for k, (d, t, token, parent) in enumerate(cases):
+        print(f"hand case {k}", flush=True)
+        n = len(token)
+        batch = dy.Batch.from_sizes([n])
+        tree, otree = _hand_tree(dy, token, parent)
+        dd, tt = torch.from_numpy(d).cuda(), torch.from_numpy(t).cuda()
+        for seed in range(6):
+            out = dy.verify(dd, tt, batch, tree, (1.0,), (1.0,), seed)
+            torch.cuda.synchronize()
+            compare_verify(out, batch, [otree], d, t, (1.0,), (1.0,), seed)
+    # first case: the second child must carry the "not tried" marker
+    d, t, token, parent = cases[0]
+    tree, _ = _hand_tree(dy, token, parent)
+    out = dy.verify(torch.from_numpy(d).cuda(), torch.from_numpy(t).cuda(), dy.Batch.from_sizes([3]), tree,
+                    (1.0,), (1.0,), 0)
+    assert out.accept_ratio.cpu().numpy()[2] == -1.0
+    assert out.n_accepted.item() == 0 and out.final_token.item() == 0
+
+
+def test_bad_arguments_are_rejected(dy):
+    batch = dy.Batch.from_sizes([4])
+    d = torch.zeros((4, 16), device="cuda")
+    with pytest.raises(dy.DyspecError) as e:
+        dy.build_tree(d, batch, (0.0,), 0)                       # temperature must be positive
+    assert e.value.status == -1
+    big = dy.Batch.from_sizes([2000])
+    with pytest.raises(dy.DyspecError) as e:
+        dy.build_tree(torch.zeros((2000, 16), device="cuda"), big, (1.0,), 0)
+    assert e.value.status == -2

@@ -1,0 +1,113 @@
+"""GPU parity: dyspec_tree_attn against the fp64 oracle (through the C ABI)."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import ATTN_TOL, oracle_attention_rows
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def dy():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2410_11744_amd as m
+    m.load_library()
+    return m
+
+
+def random_parents(n, rng, chain=False):
+    if chain:
+        return np.arange(-1, n - 1, dtype=np.int32)
+    par = np.full(n, -1, np.int32)
+    for i in range(1, n):
+        par[i] = int(rng.integers(max(0, i - 12), i)) if rng.random() < 0.7 else int(rng.integers(0, i))
+    return par
+
+
+def make_case(nodes, prefix, Hq, Hkv, d, dtype, seed, chain=False):
+    rng = np.random.default_rng(seed)
+    g = torch.Generator().manual_seed(seed)
+    dt = torch.float32 if dtype == "f32" else torch.bfloat16
+    tn, tp = sum(nodes), sum(prefix)
+    mk = lambda *sh: torch.randn(sh, generator=g, dtype=torch.float32).to(dt)
+    q, kp, vp, kt, vt = mk(tn, Hq, d), mk(tp, Hkv, d), mk(tp, Hkv, d), mk(tn, Hkv, d), mk(tn, Hkv, d)
+    words = (max(nodes) + 63) // 64
+    mask = np.zeros((tn, words), np.uint64)
+    off = 0
+    for n in nodes:
+        m = oracle.ancestor_mask(random_parents(n, rng, chain))
+        mask[off:off + n, :m.shape[1]] = m
+        off += n
+    return q, kp, vp, kt, vt, mask
+
+
+def run_and_compare(dy, nodes, prefix, Hq, Hkv, d, dtype, seed, chain=False, api_dtype=None, max_rows=4000):
+    print(f"attn case nodes={nodes} prefix={prefix} H={Hq}/{Hkv} d={d} {dtype} seed={seed}", flush=True)
+    batch = dy.Batch.from_sizes(nodes, prefix)
+    q, kp, vp, kt, vt, mask = make_case(nodes, prefix, Hq, Hkv, d, dtype, seed, chain)
+    scale = 1.0 / math.sqrt(d)
+    dev = lambda t: t.cuda() if t.numel() else torch.empty(t.shape, dtype=t.dtype, device="cuda")
+    mask_dev = torch.from_numpy(mask.view(np.int64)).cuda()
+    out = dy.tree_attn(dev(q), dev(kp), dev(vp), dev(kt), dev(vt), mask_dev, batch, scale, dtype=api_dtype)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    host = [t.float().numpy() for t in (q, kp, vp, kt, vt)]
+    rng = np.random.default_rng(seed + 1)
+    worst = 0.0
+    for s, n in enumerate(nodes):
+        total = n * Hq
+        if total <= max_rows:
+            rj, rh = np.divmod(np.arange(total), Hq)
+        else:
+            pick = rng.choice(total, max_rows, replace=False)
+            rj, rh = np.divmod(pick, Hq)
+        want = oracle_attention_rows(*host, mask, batch, s, scale, rj, rh)
+        a = int(batch.node_offset[s])
+        err = np.abs(got[a + rj, rh] - want).max()
+        worst = max(worst, float(err))
+    assert np.isfinite(got).all()
+    assert worst <= ATTN_TOL[dtype], f"max abs error {worst}"
+    return worst
+
+
+def test_tiny_fp32_config(dy):
+    run_and_compare(dy, (32,), (128,), 8, 8, 64, "f32", 0)
+
+
+@pytest.mark.parametrize("nodes,prefix,Hq,Hkv,d,seed", [
+    ((32,), (128,), 8, 8, 64, 1),            # one 128-row tile per 4 heads... G=1, partial tiles
+    ((128,), (1024,), 4, 4, 128, 2),         # 7B-shaped slice (4 of 32 heads)
+    ((100,), (1000,), 8, 2, 128, 3),         # GQA 4, ragged prefix tile and ragged tree tile
+    ((512,), (333,), 16, 2, 128, 4),         # 70B-shaped GQA 8, many row tiles, odd prefix
+    ((70,), (0,), 4, 2, 128, 5),             # no prefix at all
+    ((1,), (65,), 8, 8, 128, 6),             # root only
+    ((64, 7, 200, 1), (100, 1, 513, 64), 8, 2, 128, 7),   # ragged batch
+    ((300,), (64,), 6, 2, 64, 8),            # head_dim 64, G = 3 (rows of a node split across blocks)
+    ((768,), (129,), 8, 1, 128, 9),          # widest supported tree slice: 12 mask words
+])
+def test_bf16_matrix_core_kernel(dy, nodes, prefix, Hq, Hkv, d, seed):
+    run_and_compare(dy, nodes, prefix, Hq, Hkv, d, "bf16", seed)
+
+
+def test_bf16_chain_tree_is_causal(dy):
+    run_and_compare(dy, (130,), (70,), 4, 2, 128, "bf16", 11, chain=True)
+
+
+@pytest.mark.parametrize("dtype,api", [("f32", None), ("bf16", 0x101)])
+def test_per_wave_kernel_odd_head_dim(dy, dtype, api):
+    run_and_compare(dy, (40, 9), (77, 3), 6, 3, 80, dtype, 12, api_dtype=api)
+
+
+def test_unsupported_head_dim_is_rejected(dy):
+    batch = dy.Batch.from_sizes([4], [4])
+    z = lambda *sh: torch.zeros(sh, dtype=torch.bfloat16, device="cuda")
+    mask = torch.zeros((4, 1), dtype=torch.int64, device="cuda")
+    with pytest.raises(dy.DyspecError) as e:
+        dy.tree_attn(z(4, 2, 96), z(4, 2, 96), z(4, 2, 96), z(4, 2, 96), z(4, 2, 96), mask, batch, 0.1)
+    assert e.value.status == -3
