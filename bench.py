@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the DySpec verification hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input: tree attention for
+every layer of the model shape (dyspec_tree_attn, L launches) followed by the vocabulary
+softmax + tree rejection sampling (dyspec_verify).  The token tree is built once, before
+the timed region, by dyspec_build_tree from the same draft logits.  Every input is already
+resident in HBM when timing starts.
+
+Prints ONE JSON line: verified tree tokens/s, the roofline position of the dominant kernel
+(the matrix-core tree-attention kernel) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "verified tree tokens/s (tree-attn + verify), 70B shape, 1 GPU; % of HBM peak"
+PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+# HBM bytes per tree-attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
+# copy kernel of known size (see profiles/); None until measured for this workload.
+TRAFFIC_BYTES_PER_LAUNCH = {"llama2_70b": None}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama2_70b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding or collectives); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2410_11744_amd as dy
+    from paper_2410_11744_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dy.load_library()
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS[args.workload]
+    batch = dy.Batch.from_sizes(cfg.n_nodes, cfg.prefix_len)
+    n_tokens = batch.total_nodes
+    scale = 1.0 / math.sqrt(cfg.head_dim)
+
+    # ---- inputs (resident in HBM before timing)
+    draft_h, target_h = synth.make_logits(cfg)
+    draft, target = torch.from_numpy(draft_h).to(dev), torch.from_numpy(target_h).to(dev)
+    built = dy.build_tree(draft, batch, cfg.temps, cfg.seed)
+    layers = [synth.make_attention_inputs(cfg, l, device=dev) for l in range(cfg.layers)]
+    outs = [torch.empty_like(layers[l][0]) for l in range(cfg.layers)]
+    vout = dy.VerifyOutput.empty(batch, dev)
+    torch.cuda.synchronize()
+    depth = built.tree.depth.cpu().numpy().astype(np.int64)
+    n_built = built.n_built.cpu().numpy()
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        for l in range(cfg.layers):
+            q, kp, vp, kt, vt = layers[l]
+            dy.tree_attn(q, kp, vp, kt, vt, built.anc_mask, batch, scale, out=outs[l])
+        if ev:
+            ev[1].record()
+        dy.verify(draft, target, batch, built.tree, cfg.temps, cfg.temps, cfg.seed, out=vout)
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    attn_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    verify_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    value = n_tokens / (ms_per_step * 1e-3)
+
+    # ---- roofline of the dominant kernel (tree attention, one launch = one layer)
+    # Algorithmic work per launch: every row scores and accumulates over all prefix keys and
+    # over its ancestors-or-self in the tree: 4*d flops per (row, visible key).
+    visible = sum(int(cfg.prefix_len[s]) * int(cfg.n_nodes[s]) for s in range(batch.n_seq)) + int((depth + 1).sum())
+    flops_per_launch = 4.0 * cfg.n_q_heads * cfg.head_dim * visible
+    launch_ms = attn_ms / cfg.layers
+    achieved_tflops = flops_per_launch / (launch_ms * 1e-3) / 1e12
+    elt = 4 if cfg.dtype == "f32" else 2
+    bytes_attn_launch = elt * cfg.head_dim * (2 * cfg.n_kv_heads * (batch.total_prefix + n_tokens)
+                                              + 2 * cfg.n_q_heads * n_tokens)
+    bytes_step = bytes_attn_launch * cfg.layers + 8.0 * n_tokens * cfg.vocab
+    hbm_gbs = bytes_step / (ms_per_step * 1e-3) / 1e9
+    roofline = {"kernel": "tree_attn_mfma_kernel<128>", "bound": "mfma", "achieved": round(achieved_tflops, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
+                "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+                "launch_us": round(launch_ms * 1e3, 2), "flops_per_launch": flops_per_launch,
+                "algorithmic_bytes_per_launch": bytes_attn_launch}
+
+    # ---- CPU oracle on a bounded sample of the same workload (reported baseline, not a target)
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        q, kp, vp, kt, vt = [t.float().cpu().numpy() for t in layers[0]]
+        mask = built.anc_mask.cpu().numpy().view(np.uint64)
+        rng = np.random.default_rng(0)
+        total_rows = n_tokens * cfg.n_q_heads
+        N0, P0 = int(cfg.n_nodes[0]), int(cfg.prefix_len[0])      # sample rows from sequence 0
+        words0 = (N0 + 63) // 64
+        m0 = np.ascontiguousarray(mask[:N0, :words0])
+
+        def run(n_rows):
+            pick = rng.choice(N0 * cfg.n_q_heads, n_rows, replace=False)
+            rj, rh = np.divmod(pick, cfg.n_q_heads)
+            t = time.perf_counter()
+            oracle.tree_attn_rows(q[:N0], kp[:P0], vp[:P0], kt[:N0], vt[:N0], m0, scale, rj, rh)
+            return time.perf_counter() - t
+        t_probe = run(256)
+        n_rows = int(min(N0 * cfg.n_q_heads, max(256, 256 * args.cpu_seconds / max(t_probe, 1e-4))))
+        t_rows = run(n_rows)
+        # rows of sequence 0 see P0 + ancestors keys; scale to the whole batch by visible keys
+        vis0 = P0 * N0 + int((depth[:N0] + 1).sum())
+        t_attn_step = t_rows / n_rows * (N0 * cfg.n_q_heads) * (visible / vis0) * cfg.layers
+        t = time.perf_counter()
+        off = 0
+        for s, n in enumerate(cfg.n_nodes):
+            tr = {k: getattr(built.tree, k).cpu().numpy()[off:off + n] for k in ("token", "first_child", "next_sibling")}
+            oracle.verify(draft_h[off:off + n], target_h[off:off + n], tr["token"], tr["first_child"],
+                          tr["next_sibling"], float(np.float32(cfg.temps[s])), float(np.float32(cfg.temps[s])),
+                          cfg.seed, seq=s)
+            off += n
+        t_verify = time.perf_counter() - t
+        cpu = {"value": round(n_tokens / (t_attn_step + t_verify), 3), "unit": "tokens/s",
+               "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"tree attention: {n_rows} of {total_rows * cfg.layers} (row, head, layer) rows of layer 0 "
+                         f"in {t_rows:.2f} s, scaled by row count; verification walk in full ({t_verify * 1e3:.1f} ms)"}
+
+    line = {
+        "metric": METRIC, "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype if cfg.dtype != "f32" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.layers} layers, {cfg.n_q_heads}q/{cfg.n_kv_heads}kv heads, "
+                               f"head_dim {cfg.head_dim}, prefix {list(cfg.prefix_len)}, tree rows {list(cfg.n_nodes)}, "
+                               f"vocab {cfg.vocab}, batch {batch.n_seq}",
+                   "tree_rows_built": [int(x) for x in n_built], "max_depth": int(depth.max())},
+        "attn_ms_per_step": round(attn_ms, 4), "verify_ms_per_step": round(verify_ms, 4),
+        "pct_hbm_peak": round(100.0 * hbm_gbs / PEAK_HBM_GBS, 2), "algorithmic_gbs": round(hbm_gbs, 1),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -45,6 +45,11 @@ def _L():
     return _lib
 
 
+def num_threads() -> int:
+    """Threads the attention routines use (OpenMP over independent rows)."""
+    return int(_L().oracle_num_threads())
+
+
 def _p(a, ct):
     return a.ctypes.data_as(ctypes.POINTER(ct))
 

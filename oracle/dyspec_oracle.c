@@ -35,6 +35,20 @@
 #include <stdlib.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Threads the attention routines spread independent rows over. */
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
 /* ------------------------------------------------------------------ Philox4x32-10 */
 
 static void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
