@@ -43,6 +43,7 @@ hipError_t launch_verify(const float* draft_logits, const float* target_logits, 
                          int* accepted_nodes, int* n_accepted, int* final_token,
                          float* min_margin, hipStream_t stream);
 hipError_t launch_tree_attn(AttnArgs a, const SeqArgs& sa, int dtype, bool per_wave, hipStream_t stream);
+hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, hipStream_t stream);
 
 enum : uint32_t { KIND_PATH = 0, KIND_BUILD = 1, KIND_ACCEPT = 2, KIND_RESID = 3 };
 
