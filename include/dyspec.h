@@ -143,24 +143,24 @@ dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* 
  * dyspec_verify -- vocabulary softmax of every tree row and multi-candidate tree
  * rejection sampling (Algorithm 3; Appendix A.3; Section 2 for the one-candidate rule).
  *
- * Data-parallel part, one workgroup per tree row p: D = softmax(draft_logits[p]/T_d),
- * R = softmax(target_logits[p]/T_t); for each child n of p in sampling order, with token y:
- * accept_ratio[n] = R[y]/D[y]; then R <- norm(max(R-D,0)), D[y] <- 0, D <- norm(D)
- * (scan of p's children ends early when D is empty: the remaining children get ratio -1).
- * resid_token[p] = draw from the R left after all children (for a leaf: from the target
- * row itself when emit_bonus != 0, else -1).  These are exactly the quantities the serial
- * algorithm would compute on reaching p, so the walk below reproduces it.
- * Walk, one thread per sequence: from the root, try the children in order; child n is
- * accepted iff c < accept_ratio[n] (equivalently c*D[y] < R[y]), c uniform in [0,1); move to
- * the accepted child; when none is accepted, or the node is a leaf, emit resid_token and stop.
+ * Data-parallel part, one workgroup per tree row p: the maximum and the sum of exponentials
+ * of draft_logits[p]/T_d and of target_logits[p]/T_t (row_stats), i.e. the normalisers of
+ * D = softmax(draft_logits[p]/T_d) and R = softmax(target_logits[p]/T_t).
+ * Walk, one workgroup per sequence, from the root: for each child n of the current node in
+ * sampling order, with token y: draw c uniform in [0,1); accept iff c < R[y]/D[y]
+ * (equivalently c*D[y] < R[y]); on a reject R <- norm(max(R-D,0)) with D as it stands, then
+ * D[y] <- 0 and D <- norm(D); the scan of the children ends early when D is empty.  Move to
+ * the accepted child; when none is accepted sample the step's last token from R; when the
+ * walk reaches a leaf sample it from the leaf's target row if emit_bonus != 0 (the printed
+ * algorithm returns without it: final_token = -1).  The final token is the smallest index
+ * whose cumulative probability exceeds u * (total), u in [0,1) with 24 random bits.
  *
  *   draft_logits, target_logits DEVICE [sum N, vocab] fp32 (row i = distribution after node i)
  *   draft_temp, target_temp     HOST [n_seq] > 0
- *   tree                        DEVICE inputs (token, sib_rank, parent, first_child,
- *                               next_sibling are read; parents must precede children)
+ *   tree                        DEVICE inputs (token, first_child, next_sibling are read)
  *   row_stats    DEVICE [sum N,4] fp32: max and sum-exp of draft/T_d, then of target/T_t
- *   accept_ratio DEVICE [sum N] fp32 (root: 0)
- *   resid_token  DEVICE [sum N] i32
+ *   accept_ratio DEVICE [sum N] fp32: R[y]/D[y] seen by every child the walk tested (root: 0;
+ *                -1: not tried because the draft distribution was exhausted; -2: never reached)
  *   accepted_nodes DEVICE [sum N] i32: per sequence, from its node_offset, the accepted
  *                  local node indices in order (root excluded); n_accepted [n_seq]
  *   final_token  DEVICE [n_seq]: token emitted where the walk stopped (-1 if none)
@@ -171,9 +171,9 @@ dyspec_status dyspec_verify(const float* draft_logits, const float* target_logit
                             int32_t vocab, const dyspec_batch* batch, const dyspec_tree* tree,
                             const float* draft_temp, const float* target_temp, uint64_t seed,
                             int32_t emit_bonus, float* row_stats, float* accept_ratio,
-                            int32_t* resid_token, int32_t* accepted_nodes,
-                            int32_t* n_accepted, int32_t* final_token, float* min_margin,
-                            void* workspace, size_t workspace_bytes, void* hip_stream);
+                            int32_t* accepted_nodes, int32_t* n_accepted, int32_t* final_token,
+                            float* min_margin, void* workspace, size_t workspace_bytes,
+                            void* hip_stream);
 
 #ifdef __cplusplus
 }

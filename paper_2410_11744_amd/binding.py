@@ -65,7 +65,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.dyspec_tree_attn.argtypes = [V, V, V, V, V, V, PB, I32, I32, I32, I32, F, V, V, SZ, V]
     lib.dyspec_verify.restype = I32
     lib.dyspec_verify.argtypes = [V, V, I32, PB, PT, ctypes.POINTER(F), ctypes.POINTER(F), U64, I32,
-                                  V, V, V, V, V, V, V, V, SZ, V]
+                                  V, V, V, V, V, V, V, SZ, V]
     if path is None:
         _lib = lib
     return lib
@@ -227,8 +227,7 @@ def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, sof
 @dataclass
 class VerifyOutput:
     row_stats: "torch.Tensor"        # fp32 [sum N, 4]
-    accept_ratio: "torch.Tensor"     # fp32 [sum N]
-    resid_token: "torch.Tensor"      # int32 [sum N]
+    accept_ratio: "torch.Tensor"     # fp32 [sum N]; -1 / -2 mark children the walk did not test
     accepted_nodes: "torch.Tensor"   # int32 [sum N]
     n_accepted: "torch.Tensor"       # int32 [n_seq]
     final_token: "torch.Tensor"      # int32 [n_seq]
@@ -240,7 +239,7 @@ class VerifyOutput:
         t, s = batch.total_nodes, batch.n_seq
         f = lambda *sh: torch.empty(sh, dtype=torch.float32, device=device)
         i = lambda *sh: torch.empty(sh, dtype=torch.int32, device=device)
-        return VerifyOutput(f(t, 4), f(t), i(t), i(t), i(s), i(s), f(s))
+        return VerifyOutput(f(t, 4), f(t), i(t), i(s), i(s), f(s))
 
 
 def verify(draft_logits, target_logits, batch: Batch, tree: Tree, draft_temp, target_temp, seed: int,
@@ -257,8 +256,7 @@ def verify(draft_logits, target_logits, batch: Batch, tree: Tree, draft_temp, ta
     ta, tp = _temps(target_temp, batch.n_seq)
     st = lib.dyspec_verify(_ptr(draft_logits, "float32"), _ptr(target_logits, "float32"), V, ctypes.byref(cb),
                            ctypes.byref(ct), dp, tp, ctypes.c_uint64(seed), int(bool(emit_bonus)),
-                           _ptr(out.row_stats), _ptr(out.accept_ratio), _ptr(out.resid_token),
-                           _ptr(out.accepted_nodes), _ptr(out.n_accepted), _ptr(out.final_token),
+                           _ptr(out.row_stats), _ptr(out.accept_ratio), _ptr(out.accepted_nodes), _ptr(out.n_accepted), _ptr(out.final_token),
                            _ptr(out.min_margin), None, 0, _stream(stream))
     _check(st, "dyspec_verify")
     return out

@@ -130,15 +130,15 @@ dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* 
 dyspec_status dyspec_verify(const float* draft_logits, const float* target_logits, int32_t vocab,
                             const dyspec_batch* batch, const dyspec_tree* tree, const float* draft_temp,
                             const float* target_temp, uint64_t seed, int32_t emit_bonus,
-                            float* row_stats, float* accept_ratio, int32_t* resid_token,
-                            int32_t* accepted_nodes, int32_t* n_accepted, int32_t* final_token,
-                            float* min_margin, void*, size_t, void* hip_stream)
+                            float* row_stats, float* accept_ratio, int32_t* accepted_nodes,
+                            int32_t* n_accepted, int32_t* final_token, float* min_margin,
+                            void*, size_t, void* hip_stream)
 {
     SeqArgs sa;
     const dyspec_status st = check_batch(batch, false, &sa);
     if (st != DYSPEC_OK) return st;
     if (!draft_logits || !target_logits || !tree_ok(tree) || !draft_temp || !target_temp || !row_stats ||
-        !accept_ratio || !resid_token || !accepted_nodes || !n_accepted || !final_token || !min_margin)
+        !accept_ratio || !accepted_nodes || !n_accepted || !final_token || !min_margin)
         return DYSPEC_BAD_ARG;
     if (vocab < 1) return DYSPEC_BAD_ARG;
     if (vocab > DYSPEC_MAX_VOCAB) return DYSPEC_UNSUPPORTED;
@@ -148,8 +148,8 @@ dyspec_status dyspec_verify(const float* draft_logits, const float* target_logit
         sa.temp_t[s] = target_temp[s];
     }
     const hipError_t e = launch_verify(draft_logits, target_logits, vocab, sa, *tree, seed, emit_bonus != 0,
-                                       row_stats, accept_ratio, resid_token, accepted_nodes, n_accepted,
-                                       final_token, min_margin, static_cast<hipStream_t>(hip_stream));
+                                       row_stats, accept_ratio, accepted_nodes, n_accepted, final_token,
+                                       min_margin, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
 }
 

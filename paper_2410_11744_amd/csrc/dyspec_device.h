@@ -39,9 +39,8 @@ hipError_t launch_build_tree(const float* draft_logits, int V, const SeqArgs& sa
                              int mask_words, int* n_built, hipStream_t stream);
 hipError_t launch_verify(const float* draft_logits, const float* target_logits, int V,
                          const SeqArgs& sa, const dyspec_tree& tree, uint64_t seed, int emit_bonus,
-                         float* row_stats, float* accept_ratio, int* resid_token,
-                         int* accepted_nodes, int* n_accepted, int* final_token,
-                         float* min_margin, hipStream_t stream);
+                         float* row_stats, float* accept_ratio, int* accepted_nodes, int* n_accepted,
+                         int* final_token, float* min_margin, hipStream_t stream);
 hipError_t launch_tree_attn(AttnArgs a, const SeqArgs& sa, int dtype, bool per_wave, hipStream_t stream);
 hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, hipStream_t stream);
 
