@@ -26,9 +26,9 @@ if ROOT not in sys.path:
 METRIC = "verified tree tokens/s (tree-attn + verify), 70B shape, 1 GPU; % of HBM peak"
 PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
-# HBM bytes per tree-attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
-# copy kernel of known size (see profiles/); None until measured for this workload.
-TRAFFIC_BYTES_PER_LAUNCH = {"llama2_70b": None}
+# HBM bytes per tree-attention launch from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each
+# scaled by what the same counter reads for a 1 GiB device copy (profiles/bench_llama2_70b_rocprofv3.md).
+TRAFFIC_BYTES_PER_LAUNCH = {"llama2_70b": 36204124}
 
 
 def main() -> int:
@@ -39,6 +39,8 @@ def main() -> int:
     ap.add_argument("--workload", default="llama2_70b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain 1 GiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding or collectives); use --gpus 1",
@@ -84,6 +86,12 @@ def main() -> int:
         if ev:
             ev[2].record()
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

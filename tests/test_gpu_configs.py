@@ -1,0 +1,79 @@
+"""GPU parity at the five benchmark configurations, in the launch configuration bench.py
+times: tree build, one layer of tree attention (sampled rows against the fp64 oracle, which
+computes any single row independently) and verification, all through the C ABI."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import ATTN_TOL, compare_trees, compare_verify, oracle_attention_rows, oracle_trees
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def dy():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2410_11744_amd as m
+    m.load_library()
+    return m
+
+
+@pytest.mark.parametrize("name,layer,rows_per_seq", [
+    ("tiny_f32", 0, 256),
+    ("llama2_7b", 31, 512),
+    ("llama2_13b", 7, 512),
+    ("llama2_70b", 79, 1024),
+    ("llama2_70b_ragged8", 40, 256),
+])
+def test_config(dy, name, layer, rows_per_seq):
+    from paper_2410_11744_amd import synth
+    cfg = synth.CONFIGS[name]
+    print(f"config {name}: nodes={cfg.n_nodes} prefix={cfg.prefix_len}", flush=True)
+    dev = torch.device("cuda:0")
+    batch = dy.Batch.from_sizes(cfg.n_nodes, cfg.prefix_len)
+    draft_h, target_h = synth.make_logits(cfg)
+    draft, target = torch.from_numpy(draft_h).to(dev), torch.from_numpy(target_h).to(dev)
+
+    # ---- tree
+    built = dy.build_tree(draft, batch, cfg.temps, cfg.seed)
+    torch.cuda.synchronize()
+    trees = oracle_trees(draft_h, cfg.n_nodes, cfg.temps, cfg.seed)
+    full = compare_trees(built, batch, trees)
+    assert full == batch.n_seq, "an oracle build decision had a margin below 1e-9"
+    print(f"  trees match ({batch.total_nodes} nodes, max depth {max(int(t.depth.max()) for t in trees)})", flush=True)
+
+    # ---- attention, one layer, sampled rows
+    q, kp, vp, kt, vt = synth.make_attention_inputs(cfg, layer, device=dev)
+    scale = 1.0 / math.sqrt(cfg.head_dim)
+    out = dy.tree_attn(q, kp, vp, kt, vt, built.anc_mask, batch, scale)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    host = [t.float().cpu().numpy() for t in (q, kp, vp, kt, vt)]
+    mask = built.anc_mask.cpu().numpy().view(np.uint64)
+    rng = np.random.default_rng(cfg.seed)
+    worst = 0.0
+    for s, n in enumerate(cfg.n_nodes):
+        total = n * cfg.n_q_heads
+        pick = np.arange(total) if total <= rows_per_seq else rng.choice(total, rows_per_seq, replace=False)
+        # always include the first and last node (tile edges, deepest mask rows)
+        pick = np.unique(np.concatenate([pick, np.arange(cfg.n_q_heads), total - 1 - np.arange(cfg.n_q_heads)]))
+        rj, rh = np.divmod(pick, cfg.n_q_heads)
+        want = oracle_attention_rows(*host, mask, batch, s, scale, rj, rh)
+        a = int(batch.node_offset[s])
+        worst = max(worst, float(np.abs(got[a + rj, rh] - want).max()))
+    print(f"  attention max abs error {worst:.2e}", flush=True)
+    assert worst <= ATTN_TOL[cfg.dtype]
+
+    # ---- verification
+    vout = dy.verify(draft, target, batch, built.tree, cfg.temps, cfg.temps, cfg.seed)
+    torch.cuda.synchronize()
+    compared, skipped = compare_verify(vout, batch, trees, draft_h, target_h, cfg.temps, cfg.temps, cfg.seed)
+    print(f"  verify: paths compared {compared}, skipped for small margins {skipped}, "
+          f"accepted {vout.n_accepted.cpu().tolist()}", flush=True)
+    assert compared + skipped == batch.n_seq and compared >= max(1, batch.n_seq - 2)
