@@ -47,10 +47,15 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(1))) const void* global_ptr;
 typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4v* lds_short4;
 
 constexpr int kRowsPerWG = 128;
 constexpr int kKeysPerTile = 64;
-constexpr int kAttnThreads = 256;
+#ifndef DYSPEC_ATTN_QB
+#define DYSPEC_ATTN_QB 1
+#endif
+constexpr int kQB = DYSPEC_ATTN_QB;   // 32-row query blocks per wave (see the kernel)
 constexpr float kLazy = 8.0f;        // accumulators are rescaled only when exp2 would pass 2^kLazy
 
 // v_exp_f32 without the denormal-range fix-up: inputs below -126 give 0, which is what the
@@ -71,8 +76,13 @@ __device__ __forceinline__ uint32_t lds_address(const void* p)
     return (uint32_t)(size_t)(lds_ptr)(p);
 }
 
-__device__ __forceinline__ uint32_t pack_lo(uint32_t w0, uint32_t w1) { return __builtin_amdgcn_perm(w1, w0, 0x05040100u); }
-__device__ __forceinline__ uint32_t pack_hi(uint32_t w0, uint32_t w1) { return __builtin_amdgcn_perm(w1, w0, 0x07060302u); }
+// max of three without the NaN-quieting moves fmaxf would add in front
+__device__ __forceinline__ float max3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
 
 template <int D> struct Geo {
     static constexpr int kRowBytes = 2 * D;
@@ -84,21 +94,26 @@ template <int D> struct Geo {
     static constexpr int kLoadsPerMat = kKeysPerTile / kRowsPerLoad;
     // chunk c of K row r sits at chunk position c ^ swz_k(r); of V row r at c ^ swz_v(r)
     __device__ static __forceinline__ int swz_k(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
-    __device__ static __forceinline__ int swz_v(int r) { return D == 128 ? (((r >> 2) & 1) << 3) : 0; }
+    __device__ static __forceinline__ int swz_v(int r) { return D == 128 ? ((r & 3) << 2) : 0; }
 };
 
-template <int D>
-__global__ __launch_bounds__(kAttnThreads) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs sa)
+// QB = 32-row query blocks per wave.  QB = 2: 4 waves, one per SIMD, 512 registers each.
+// QB = 1: 8 waves, two per SIMD with 256 registers each, so the matrix work of one wave hides
+// behind the vector work of the other; every K/V byte is then read from LDS by four waves.
+template <int D, int QB>
+__global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs sa)
 {
     using L = Geo<D>;
+    constexpr int NWQ = 4 / QB;                  // waves along the row dimension
+    constexpr int NW = 2 * NWQ;                  // waves per workgroup
     constexpr int KK = D / 16;                   // k-steps of the QK^T product
-    constexpr int DG = D / 64;                   // 64-wide groups of the head dimension
+    constexpr int DB = D / 32;                   // 32-wide blocks of the head dimension
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, g = lane >> 5;
-    const int wq = wave & 1, wk = wave >> 1;
+    const int wq = wave % NWQ, wk = wave / NWQ;
 
     // ---- which tile
     const int kvh = blockIdx.x % a.Hkv;
@@ -125,12 +140,12 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_mfma_kernel(AttnArgs a
     const char* vt = static_cast<const char*>(a.vt) + (size_t)node_base * kv_row_bytes + (size_t)kvh * D * 2;
 
     // ---- Q fragments (B operand: lane holds query n, head-dim slice 16*kk + 8*g .. +7)
-    bf16x8 qf[2][KK];
-    int rq[2];
-    const uint64_t* mrow[2];
+    bf16x8 qf[QB][KK];
+    int rq[QB];
+    const uint64_t* mrow[QB];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const int r = r0 + 64 * wq + 32 * qb + n;
+    for (int qb = 0; qb < QB; ++qb) {
+        const int r = r0 + 32 * QB * wq + 32 * qb + n;
         rq[qb] = r;
         const int rc = min(r, rows - 1);
         const int j = rc / G, h = kvh * G + rc % G;
@@ -141,24 +156,27 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_mfma_kernel(AttnArgs a
             qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * g);
     }
 
-    floatx16 acc[DG][2][2];                      // [d group][even/odd d][query block]
+    floatx16 acc[DB][QB];                        // O^T: [32-wide head-dim block][query block]
 #pragma unroll
-    for (int dg = 0; dg < DG; ++dg)
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int par = 0; par < 2; ++par)
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
+            for (int i = 0; i < 16; ++i) acc[db][qb][i] = 0.0f;
+    float m_run[QB], l_run[QB];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[dg][par][qb][i] = 0.0f;
-    float m_run[2] = { -1e30f, -1e30f }, l_run[2] = { 0.0f, 0.0f };
+    for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -1e30f; l_run[qb] = 0.0f; }
     const float c2 = a.scale * 1.4426950408889634f;     // scores are used as exp2(c2 * s)
 
-    // ---- direct-load plan: wave w fills matrix w of every stage (0: K of the even tile, 1: V
-    //      of the even tile, 2: K odd, 3: V odd) with kLoadsPerMat loads of kRowsPerLoad rows.
-    //      Lane i of load x writes row position R = kRowsPerLoad*x + i/kChunks, chunk position
-    //      i % kChunks, so it must fetch chunk (i % kChunks) ^ swz(R) of that key row.  With
-    //      these swizzles swz(R) = (lane part) ^ (part that depends on x mod 4 only).
-    const bool ld_is_v = wave & 1;
+    // ---- direct-load plan: a stage holds four matrices (0: K of the even tile, 1: V of the
+    //      even tile, 2: K odd, 3: V odd) of kLoadsPerMat wave-wide loads each; wave w fills
+    //      loads [LPW*part, LPW*part + LPW) of matrix w / (NW/4).  Lane i of load x writes row
+    //      position R = kRowsPerLoad*x + i/kChunks, chunk position i % kChunks, so it must fetch
+    //      chunk (i % kChunks) ^ swz(R) of that key row; with these swizzles the lane's byte
+    //      offset depends on x mod 4 only.
+    constexpr int LPW = L::kLoadsPerMat / (NW / 4);
+    const int ld_mm = wave / (NW / 4), ld_x0 = (wave % (NW / 4)) * LPW;
+    const bool ld_is_v = ld_mm & 1;
     const int ld_lrow = lane / L::kChunks, ld_cpos = lane % L::kChunks;
     int ld_voff[4];                               // byte offset of the lane's chunk for x mod 4
 #pragma unroll
@@ -169,11 +187,11 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_mfma_kernel(AttnArgs a
     }
     const char* const st_prefix = ld_is_v ? vp : kp;
     const char* const st_tree = ld_is_v ? vt : kt;
-    unsigned char* const st_dst = lds + wave * L::kMatBytes;
+    unsigned char* const st_dst = lds + ld_mm * L::kMatBytes + ld_x0 * 1024;
     // (captures by value: a conditional between variables captured by reference would be a
     //  conditional between addresses and force them into scratch memory)
     auto issue_stage = [=](int it) {
-        const int t = 2 * it + (wave >> 1);                      // the tile this wave stages
+        const int t = 2 * it + (ld_mm >> 1);                     // the tile this wave stages
         if (t >= nT) return;                                     // odd tile past the end: nobody reads it
         unsigned char* dst0 = st_dst + (it & 1) * L::kStageBytes;
         const bool prefix = t < nTp;
@@ -181,8 +199,8 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_mfma_kernel(AttnArgs a
         const int key0 = (prefix ? t : t - nTp) * kKeysPerTile;
         const int limit = prefix ? P : N;
         if (key0 + kKeysPerTile <= limit) {                      // whole tile in range: uniform base + lane offset
-            const char* base = region + (size_t)key0 * kv_row_bytes;
-            static_for<L::kLoadsPerMat>([=](auto xc) {
+            const char* base = region + (size_t)(key0 + L::kRowsPerLoad * ld_x0) * kv_row_bytes;
+            static_for<LPW>([=](auto xc) {
                 constexpr int x = decltype(xc)::value;
                 direct_load_16(base + (size_t)(L::kRowsPerLoad * x) * kv_row_bytes, (uint32_t)ld_voff[x & 3],
                                lds_address(dst0) + x * 1024);
@@ -190,10 +208,11 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_mfma_kernel(AttnArgs a
         } else {
             // rows past the end read row 0 of the region (a key every query may see, so its
             // values are as finite as the result itself); their scores are masked out
-            static_for<L::kLoadsPerMat>([=](auto xc) {
+            static_for<LPW>([=](auto xc) {
                 constexpr int x = decltype(xc)::value;
-                const int key = key0 + L::kRowsPerLoad * x + ld_lrow;
-                const uint32_t off = (key < limit) ? (uint32_t)(key0 + L::kRowsPerLoad * x) * (uint32_t)kv_row_bytes + (uint32_t)ld_voff[x & 3]
+                const int rowx = L::kRowsPerLoad * (ld_x0 + x);
+                const int key = key0 + rowx + ld_lrow;
+                const uint32_t off = (key < limit) ? (uint32_t)(key0 + rowx) * (uint32_t)kv_row_bytes + (uint32_t)ld_voff[x & 3]
                                                    : (uint32_t)(ld_voff[x & 3] - ld_lrow * (int)kv_row_bytes);
                 direct_load_16(region, off, lds_address(dst0) + x * 1024);
             });
@@ -207,33 +226,47 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_mfma_kernel(AttnArgs a
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) k_off[kk] = n * L::kRowBytes + (((2 * kk) ^ h) << 4);
     }
-    int v_off[DG];                               // V word (d = 64*dg + 2n, +1) of key row 4*g (+ more rows)
+    // V^T fragments come from the LDS transpose read (ds_read_b64_tr_b16).  Measured lane
+    // layout of that instruction, per group of 16 lanes: lane i supplies the address of four
+    // consecutive 16-bit elements M_i[0..3] and receives { M_{4j + i/4}[i % 4] : j = 0..3 }.
+    // So lanes s = 4j + r of a group point at key row (base + j), columns 4r..4r+3 of a
+    // 16-column slab, and lane i of the group gets column i of that slab for the four keys:
+    // exactly four consecutive k-slots of an MFMA A operand whose row is head-dim index i.
+    // Groups 0/1 of a half-wave take columns 0-15 / 16-31 of the 32-wide block, half-waves
+    // (g) take key rows +0 / +4, matching the k-slot order of the P registers.
+    int v_off[DB];                               // byte offset of the lane's 8-byte piece for block db
+    {
+        const int sl = lane & 15, grp = (lane >> 4) & 1;
+        const int row = (sl >> 2) + 4 * g;       // + 8*(2*ts + half) + 32*ka rows added at the read
 #pragma unroll
-    for (int dg = 0; dg < DG; ++dg)
-        v_off[dg] = 4 * g * L::kRowBytes + (((8 * dg + (n >> 2)) ^ L::swz_v(4 * g)) << 4) + 4 * (n & 3);
+        for (int db = 0; db < DB; ++db) {
+            const int chunk = 4 * db + 2 * grp + ((sl & 3) >> 1);
+            v_off[db] = row * L::kRowBytes + ((chunk ^ L::swz_v(row)) << 4) + 8 * (sl & 1);
+        }
+    }
 
     // Visibility words of a tile's 64 keys for the lane's two queries: all ones inside the
     // prefix, the low bits for a ragged last prefix tile, the ancestor-mask word for a tree
     // tile.  They are fetched one iteration ahead, BEFORE that iteration's direct loads are
     // issued, so that the wait the compiler places at their first use finds nothing in flight.
-    uint64_t vis_next[2];
-    {
-        const int t = wk;
-        vis_next[0] = vis_next[1] = ~0ull;
-        if (t >= nTp && t < nT) { vis_next[0] = mrow[0][t - nTp]; vis_next[1] = mrow[1][t - nTp]; }
-    }
+    uint64_t vis_next[QB];
+    auto fetch_vis = [=](int t, uint64_t (&v)[QB]) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) v[qb] = (t >= nTp && t < nT) ? mrow[qb][t - nTp] : ~0ull;
+    };
+    fetch_vis(wk, vis_next);
     issue_stage(0);
     wait_direct_loads();
     __syncthreads();
 
     for (int it = 0; it < nIt; ++it) {
-        uint64_t vis[2] = { vis_next[0], vis_next[1] };
-        asm volatile("" : "+v"(vis[0]), "+v"(vis[1]));          // first use of the prefetched words
-        {
-            const int tn = 2 * (it + 1) + wk;
-            vis_next[0] = vis_next[1] = ~0ull;
-            if (tn >= nTp && tn < nT) { vis_next[0] = mrow[0][tn - nTp]; vis_next[1] = mrow[1][tn - nTp]; }
+        uint64_t vis[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            vis[qb] = vis_next[qb];
+            asm volatile("" : "+v"(vis[qb]));                     // first use of the prefetched words
         }
+        fetch_vis(2 * (it + 1) + wk, vis_next);
         if (it + 1 < nIt) issue_stage(it + 1);
 
         const int t = 2 * it + wk;
@@ -241,109 +274,104 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_mfma_kernel(AttnArgs a
             bool need_mask = t >= nTp;
             if (t < nTp && (t + 1) * kKeysPerTile > P) {
                 const int live = P - t * kKeysPerTile;              // 1..63
-                vis[0] = vis[1] = (1ull << live) - 1ull;
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) vis[qb] = (1ull << live) - 1ull;
                 need_mask = true;
             }
-            if (__any((vis[0] | vis[1]) != 0ull)) {
+            uint64_t vis_any = 0;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) vis_any |= vis[qb];
+            if (__any(vis_any != 0ull)) {
                 const unsigned char* Ks = lds + (it & 1) * L::kStageBytes + 2 * wk * L::kMatBytes;
                 const unsigned char* Vs = Ks + L::kMatBytes;
 
-                // S^T block ka = K[32*ka .. +31] Q^T
-                auto qk = [&](int ka, floatx16 (&S)[2]) {
+                // ---- S^T = K Q^T for the two 32-key blocks of the tile: independent
+                //      accumulation chains, so consecutive MFMAs never wait on each other
+                floatx16 S[2][QB];
+                const floatx16 zero16 = { 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0 };
 #pragma unroll
-                    for (int qb = 0; qb < 2; ++qb)
+                for (int kk = 0; kk < KK; ++kk) {
+                    bf16x8 kf[2];
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) S[qb][i] = 0.0f;
+                    for (int ka = 0; ka < 2; ++ka)
+                        kf[ka] = *reinterpret_cast<const bf16x8*>(Ks + 32 * ka * L::kRowBytes + k_off[kk]);
 #pragma unroll
-                    for (int kk = 0; kk < KK; ++kk) {
-                        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + 32 * ka * L::kRowBytes + k_off[kk]);
+                    for (int ka = 0; ka < 2; ++ka)
 #pragma unroll
-                        for (int qb = 0; qb < 2; ++qb)
-                            S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][kk], S[qb], 0, 0, 0);
-                    }
-                };
-                // mask + online softmax of block ka.  Register i of a 32x32 block holds key
-                // row 8*(i/4) + 4*g + i%4 of the block, query column n.
-                auto softmax = [&](int ka, floatx16 (&S)[2], bf16x8 (&pb)[2][2]) {
+                        for (int qb = 0; qb < QB; ++qb)
+                            S[ka][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ka], qf[qb][kk], kk == 0 ? zero16 : S[ka][qb], 0, 0, 0);
+                }
+
+                // ---- mask + online softmax.  Register i of a 32x32 block holds key row
+                //      8*(i/4) + 4*g + i%4 of the block, query column n.
+                bf16x8 pb[QB][2][2];                      // [query block][key block][16-key step]
 #pragma unroll
-                    for (int qb = 0; qb < 2; ++qb) {
-                        if (need_mask) {
+                for (int qb = 0; qb < QB; ++qb) {
+                    if (need_mask) {
+#pragma unroll
+                        for (int ka = 0; ka < 2; ++ka) {
                             const uint32_t v32 = (uint32_t)(vis[qb] >> (32 * ka + 4 * g));
 #pragma unroll
                             for (int i = 0; i < 16; ++i)
-                                if (!((v32 >> (8 * (i / 4) + (i % 4))) & 1u)) S[qb][i] = -INFINITY;
+                                if (!((v32 >> (8 * (i / 4) + (i % 4))) & 1u)) S[ka][qb][i] = -INFINITY;
                         }
-                        float mx = fmaxf(S[qb][0], S[qb][1]);
+                    }
+                    float mx = -INFINITY;
 #pragma unroll
-                        for (int i = 2; i < 16; ++i) mx = fmaxf(mx, S[qb][i]);
-                        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-                        // The reference maximum only has to keep exp2 in range, so it is raised
-                        // lazily: the accumulators (they sit in AGPRs, three instructions per
-                        // register to touch) are rescaled only when a score tops it by kLazy.
-                        if (__any(mx * c2 > m_run[qb] * c2 + kLazy)) {
-                            const float m_new = fmaxf(m_run[qb], mx);
-                            const float alpha = fast_exp2((m_run[qb] - m_new) * c2);
-                            m_run[qb] = m_new;
-                            l_run[qb] *= alpha;
-                            if (__any(alpha != 0.0f && alpha != 1.0f)) {   // alpha 0: accumulators still 0
+                    for (int ka = 0; ka < 2; ++ka)
 #pragma unroll
-                                for (int dg = 0; dg < DG; ++dg)
+                        for (int i = 0; i < 16; i += 2) mx = max3(mx, S[ka][qb][i], S[ka][qb][i + 1]);
+                    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+                    // The reference maximum only has to keep exp2 in range, so it is raised
+                    // lazily: the accumulators are rescaled only when a score tops it by kLazy.
+                    if (__any(mx * c2 > m_run[qb] * c2 + kLazy)) {
+                        const float m_new = fmaxf(m_run[qb], mx);
+                        const float alpha = fast_exp2((m_run[qb] - m_new) * c2);
+                        m_run[qb] = m_new;
+                        l_run[qb] *= alpha;
+                        if (__any(alpha != 0.0f && alpha != 1.0f)) {   // alpha 0: accumulators still 0
 #pragma unroll
-                                    for (int par = 0; par < 2; ++par)
+                            for (int db = 0; db < DB; ++db)
 #pragma unroll
-                                        for (int i = 0; i < 16; ++i) acc[dg][par][qb][i] *= alpha;
-                            }
+                                for (int i = 0; i < 16; ++i) acc[db][qb][i] *= alpha;
                         }
-                        const float mc = m_run[qb] * c2;
-                        float ls = 0.0f;
+                    }
+                    const float mc = m_run[qb] * c2;
+                    float ls = 0.0f;
+#pragma unroll
+                    for (int ka = 0; ka < 2; ++ka)
 #pragma unroll
                         for (int i = 0; i < 16; i += 2) {
-                            const float p0 = fast_exp2(fmaf(S[qb][i], c2, -mc));
-                            const float p1 = fast_exp2(fmaf(S[qb][i + 1], c2, -mc));
+                            const float p0 = fast_exp2(fmaf(S[ka][qb][i], c2, -mc));
+                            const float p1 = fast_exp2(fmaf(S[ka][qb][i + 1], c2, -mc));
                             ls += p0 + p1;
                             floatx2 pp = { p0, p1 };
                             const bf16x2 pc = __builtin_convertvector(pp, bf16x2);
-                            pb[qb][i / 8][i % 8] = pc[0];
-                            pb[qb][i / 8][i % 8 + 1] = pc[1];
+                            pb[qb][ka][i / 8][i % 8] = pc[0];
+                            pb[qb][ka][i / 8][i % 8 + 1] = pc[1];
                         }
-                        l_run[qb] += ls;
-                    }
-                };
-                // O^T += V^T P^T for key block ka.  k-slot (g, e) of 16-key step ts is key
-                // 32*ka + 8*(2*ts + e/4) + 4*g + e%4, as in the P registers.
-                auto pv = [&](int ka, bf16x8 (&pb)[2][2]) {
+                    l_run[qb] += ls;
+                }
+
+                // ---- O^T += V^T P^T.  k-slot (g, e) of step (ka, ts) is key
+                //      32*ka + 8*(2*ts + e/4) + 4*g + e%4, as in the P registers.
+#pragma unroll
+                for (int ka = 0; ka < 2; ++ka)
 #pragma unroll
                     for (int ts = 0; ts < 2; ++ts)
 #pragma unroll
-                        for (int dg = 0; dg < DG; ++dg) {
-                            uint32_t w[8];
+                        for (int db = 0; db < DB; ++db) {
+                            union { short4v h[2]; bf16x8 v; } f;
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) {
-                                const int krow = 32 * ka + 8 * (2 * ts + e / 4) + e % 4;      // + 4*g in v_off
-                                w[e] = *reinterpret_cast<const uint32_t*>(Vs + krow * L::kRowBytes + v_off[dg]);
-                            }
-                            union { uint32_t u[4]; bf16x8 v; } fe, fo;
-#pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                fe.u[j] = pack_lo(w[2 * j], w[2 * j + 1]);
-                                fo.u[j] = pack_hi(w[2 * j], w[2 * j + 1]);
+                            for (int half = 0; half < 2; ++half) {
+                                const int krow = 32 * ka + 8 * (2 * ts + half);      // + s/4 + 4*g in v_off
+                                f.h[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                    (lds_short4)(Vs + krow * L::kRowBytes + v_off[db]));
                             }
 #pragma unroll
-                            for (int qb = 0; qb < 2; ++qb) {
-                                acc[dg][0][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fe.v, pb[qb][ts], acc[dg][0][qb], 0, 0, 0);
-                                acc[dg][1][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo.v, pb[qb][ts], acc[dg][1][qb], 0, 0, 0);
-                            }
+                            for (int qb = 0; qb < QB; ++qb)
+                                acc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v, pb[qb][ka][ts], acc[db][qb], 0, 0, 0);
                         }
-                };
-
-#pragma unroll
-                for (int ka = 0; ka < 2; ++ka) {
-                    floatx16 S[2];
-                    bf16x8 Pb[2][2];
-                    qk(ka, S);
-                    softmax(ka, S, Pb);
-                    pv(ka, Pb);
-                }
             }
         }
         wait_direct_loads();
@@ -352,30 +380,30 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_mfma_kernel(AttnArgs a
 
     // ---- merge the two key halves of each row half through LDS, normalise, store
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) l_run[qb] += __shfl_xor(l_run[qb], 32, kWave);
+    for (int qb = 0; qb < QB; ++qb) l_run[qb] += __shfl_xor(l_run[qb], 32, kWave);
     float* xs = reinterpret_cast<float*>(lds);               // [wq][register][lane]
-    constexpr int NR = DG * 2 * 2 * 16 + 4;
+    constexpr int NR = DB * QB * 16 + 2 * QB;
     if (wk == 1) {
         float* dst = xs + (size_t)wq * NR * kWave + lane;
         int r = 0;
 #pragma unroll
-        for (int dg = 0; dg < DG; ++dg)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int par = 0; par < 2; ++par)
+            for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
+                for (int i = 0; i < 16; ++i) dst[(r++) * kWave] = acc[db][qb][i];
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) dst[(r++) * kWave] = acc[dg][par][qb][i];
-        dst[(r++) * kWave] = m_run[0]; dst[(r++) * kWave] = m_run[1];
-        dst[(r++) * kWave] = l_run[0]; dst[(r++) * kWave] = l_run[1];
+        for (int qb = 0; qb < QB; ++qb) dst[(r++) * kWave] = m_run[qb];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) dst[(r++) * kWave] = l_run[qb];
     }
     __syncthreads();
     if (wk == 0) {
         const float* src = xs + (size_t)wq * NR * kWave + lane;
-        float f0[2], f1[2], inv[2];
+        float f0[QB], f1[QB], inv[QB];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const float m1 = src[(NR - 4 + qb) * kWave], l1 = src[(NR - 2 + qb) * kWave];
+        for (int qb = 0; qb < QB; ++qb) {
+            const float m1 = src[(NR - 2 * QB + qb) * kWave], l1 = src[(NR - QB + qb) * kWave];
             const float m = fmaxf(m_run[qb], m1);
             f0[qb] = exp2f((m_run[qb] - m) * c2);
             f1[qb] = exp2f((m1 - m) * c2);
@@ -383,45 +411,43 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_mfma_kernel(AttnArgs a
         }
         int r = 0;
 #pragma unroll
-        for (int dg = 0; dg < DG; ++dg)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int par = 0; par < 2; ++par)
+            for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
+                for (int i = 0; i < 16; ++i) {
+                    const float o1 = src[(r++) * kWave];
+                    acc[db][qb][i] = (acc[db][qb][i] * f0[qb] + o1 * f1[qb]) * inv[qb];
+                }
+        // register i of block db is head-dim index 32*db + 8*(i/4) + 4*g + i%4
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float o1 = src[(r++) * kWave];
-                        acc[dg][par][qb][i] = (acc[dg][par][qb][i] * f0[qb] + o1 * f1[qb]) * inv[qb];
-                    }
-        // register i of block (dg, par) is head-dim index 64*dg + 2*(8*(i/4) + 4*g + i%4) + par
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < QB; ++qb) {
             if (rq[qb] >= rows) continue;
             const int j = rq[qb] / G, h = kvh * G + rq[qb] % G;
             __bf16* orow = static_cast<__bf16*>(a.out) + ((size_t)(node_base + j) * a.Hq + h) * D;
 #pragma unroll
-            for (int dg = 0; dg < DG; ++dg)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int ib = 0; ib < 4; ++ib) {
-                    union { bf16x2 p[4]; uint4 v; } o;
+                    union { bf16x2 p[2]; uint2 v; } o;
 #pragma unroll
-                    for (int ii = 0; ii < 4; ++ii) {
-                        floatx2 pr = { acc[dg][0][qb][4 * ib + ii], acc[dg][1][qb][4 * ib + ii] };
+                    for (int ii = 0; ii < 2; ++ii) {
+                        floatx2 pr = { acc[db][qb][4 * ib + 2 * ii], acc[db][qb][4 * ib + 2 * ii + 1] };
                         o.p[ii] = __builtin_convertvector(pr, bf16x2);
                     }
-                    *reinterpret_cast<uint4*>(orow + 64 * dg + 2 * (8 * ib + 4 * g)) = o.v;
+                    *reinterpret_cast<uint2*>(orow + 32 * db + 8 * ib + 4 * g) = o.v;
                 }
         }
     }
 }
 
-template <int D>
+template <int D, int QB>
 static hipError_t launch_one(const AttnArgs& a, const SeqArgs& sa, int tiles, hipStream_t stream)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<D>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<D, QB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Geo<D>::kLdsBytes);
     if (e != hipSuccess) return e;
-    tree_attn_mfma_kernel<D><<<tiles * a.Hkv, kAttnThreads, Geo<D>::kLdsBytes, stream>>>(a, sa);
+    tree_attn_mfma_kernel<D, QB><<<tiles * a.Hkv, 64 * 2 * (4 / QB), Geo<D>::kLdsBytes, stream>>>(a, sa);
     return hipGetLastError();
 }
 
@@ -435,7 +461,7 @@ hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, hipStream_t stre
     }
     a.tile_off[sa.n_seq] = tiles;
     if (tiles == 0) return hipSuccess;
-    return a.d == 128 ? launch_one<128>(a, sa, tiles, stream) : launch_one<64>(a, sa, tiles, stream);
+    return a.d == 128 ? launch_one<128, kQB>(a, sa, tiles, stream) : launch_one<64, kQB>(a, sa, tiles, stream);
 }
 
 }  // namespace dyspec
