@@ -4,25 +4,33 @@
 // Row folding.  All G = Hq/Hkv query heads that share a KV head are folded into the row
 // dimension (row = node*G + head), so a workgroup tile of 128 rows streams the prefix K/V
 // of its KV head once and every K/V byte feeds 128 rows of MFMA work; the tree part reuses
-// the same machinery with the ancestor bitmask applied to the score registers, and 64-key
+// the same machinery with the ancestor bitmask applied to the probabilities, and 64-key
 // tree tiles that no row of the wave can see are skipped (the paper's kernel skips empty
 // 32x32 blocks of the mask).
 //
-// Workgroup = 4 waves, one per SIMD.  Wave w owns the 64-row half (w & 1) and every second
-// 64-key tile ((w >> 1) picks even or odd tiles); the two waves of a row half merge their
-// (max, sum, accumulator) through LDS at the end.  Per 32-key block a wave computes
-// S^T = K Q^T (keys x queries: each lane then holds one query column, and exp(S^T) is
-// already in the register layout the second product wants as its B operand), the online
-// softmax, and O^T += V^T P^T.  The reference maximum of the softmax is raised lazily (only
-// when a score would push exp2 past 2^kLazy), so the accumulators are rescaled a handful of
-// times per row instead of once per block.
+// Workgroup = 8 waves, two per SIMD.  Wave w owns the 32-row block (w & 3) and every second
+// 64-key tile ((w >> 2) picks even or odd tiles); the two waves of a row block merge their
+// (max, sum, accumulator) through LDS at the end.  Per tile a wave computes S^T = K Q^T
+// (keys x queries: each lane then holds one query column, and exp(S^T) is already in the
+// register layout the second product wants as its B operand), the softmax numerators, and
+// O^T += V^T P^T.
+//
+// Software pipeline.  The vector work of the softmax and the matrix work run in different
+// pipes of a SIMD, but only instructions that are adjacent in one wave's stream overlap
+// reliably, so the loop is skewed: step i runs the exponentials of tile i while the matrix
+// pipe does the second product of tile i-1 and the first product of tile i+1, one MFMA,
+// its LDS reads a few slots ahead, and a few vector instructions per scheduling group.
+//
+// Lazy maximum.  Numerators are computed against the running reference maximum without
+// looking at the tile's own maximum first; only when a lane's tile sum leaves the safe range
+// (it is then recomputed, rarely) is the reference raised and the accumulators rescaled.
 //
 // Staging.  K/V tiles go from HBM/L2 to LDS with direct loads (global_load_lds_dwordx4: lane
-// i of a wave writes LDS bytes [16*i, 16*i+16) past a wave-uniform base), double buffered,
-// without passing through registers; the loads of the next stage are in flight while the
-// current one is consumed.  Rows sit unpadded in LDS; 16-byte chunks of a row are
-// XOR-swizzled so that the 16-byte K reads and the 4-byte V reads of a wave spread over all
-// 64 banks.
+// i of a wave writes LDS bytes [16*i, 16*i+16) past a wave-uniform base), two slots per
+// matrix, without passing through registers; step i loads K of tile i+2 and V of tile i
+// while it consumes K of tile i+1 and V of tile i-1.  Rows sit unpadded in LDS; 16-byte
+// chunks of a row are XOR-swizzled so that the 16-byte K reads and the transposing V reads
+// of a wave spread over all 64 banks.
 #include <utility>
 
 #include "dyspec_device.h"
@@ -40,6 +48,11 @@ __device__ __forceinline__ void static_for(F&& f)
 {
     static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
 }
+template <typename F>
+__device__ __forceinline__ void with_bool(bool b, F&& f)
+{
+    if (b) f(std::true_type{}); else f(std::false_type{});
+}
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -52,15 +65,16 @@ typedef __attribute__((address_space(3))) short4v* lds_short4;
 
 constexpr int kRowsPerWG = 128;
 constexpr int kKeysPerTile = 64;
-#ifndef DYSPEC_ATTN_QB
-#define DYSPEC_ATTN_QB 1
+constexpr float kSumLimit = 1024.0f;      // a lane's tile sum above this raises the reference maximum
+#ifndef DYSPEC_ATTN_LEAD
+#define DYSPEC_ATTN_LEAD 3
 #endif
-constexpr int kQB = DYSPEC_ATTN_QB;   // 32-row query blocks per wave (see the kernel)
-constexpr float kLazy = 8.0f;        // accumulators are rescaled only when exp2 would pass 2^kLazy
+constexpr int kLead = DYSPEC_ATTN_LEAD;   // MFMA slots between an LDS read and the MFMA that uses it
 
 // v_exp_f32 without the denormal-range fix-up: inputs below -126 give 0, which is what the
 // softmax wants.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float and_bits(float x, int m) { return __int_as_float(__float_as_int(x) & m); }
 // One wave-wide direct load: lane i moves 16 bytes from (base + voff_i) to LDS byte
 // lds_base + 16*i.  Issued as inline assembly so that the compiler does not pair every later
 // LDS read with a wait for these loads; the caller waits (wait_direct_loads) before the
@@ -89,31 +103,30 @@ template <int D> struct Geo {
     static constexpr int kChunks = D / 8;                        // 16-byte chunks per row
     static constexpr int kRowsPerLoad = 1024 / kRowBytes;        // rows one wave-wide direct load covers
     static constexpr int kMatBytes = kKeysPerTile * kRowBytes;   // one K or V tile
-    static constexpr int kStageBytes = 4 * kMatBytes;            // K,V of the even tile, K,V of the odd tile
-    static constexpr int kLdsBytes = 2 * kStageBytes;
+    static constexpr int kSlotBytes = 2 * kMatBytes;             // a slot holds an even and an odd tile
+    static constexpr int kVBase = 2 * kSlotBytes;                // K slots 0 and 1, then V slots 0 and 1
+    static constexpr int kLdsBytes = 4 * kSlotBytes;
     static constexpr int kLoadsPerMat = kKeysPerTile / kRowsPerLoad;
     // chunk c of K row r sits at chunk position c ^ swz_k(r); of V row r at c ^ swz_v(r)
     __device__ static __forceinline__ int swz_k(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
     __device__ static __forceinline__ int swz_v(int r) { return D == 128 ? ((r & 3) << 2) : 0; }
 };
 
-// QB = 32-row query blocks per wave.  QB = 2: 4 waves, one per SIMD, 512 registers each.
-// QB = 1: 8 waves, two per SIMD with 256 registers each, so the matrix work of one wave hides
-// behind the vector work of the other; every K/V byte is then read from LDS by four waves.
-template <int D, int QB>
-__global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs sa)
+template <int D>
+__global__ __launch_bounds__(512) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs sa)
 {
     using L = Geo<D>;
-    constexpr int NWQ = 4 / QB;                  // waves along the row dimension
-    constexpr int NW = 2 * NWQ;                  // waves per workgroup
     constexpr int KK = D / 16;                   // k-steps of the QK^T product
     constexpr int DB = D / 32;                   // 32-wide blocks of the head dimension
+    constexpr int NQ = 2 * KK;                   // MFMAs of one tile's first product
+    constexpr int NP = 4 * DB;                   // MFMAs of one tile's second product
+    static_assert(NQ == NP, "the interleave below alternates the two products");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, g = lane >> 5;
-    const int wq = wave % NWQ, wk = wave / NWQ;
+    const int wq = wave & 3, wk = wave >> 2;
 
     // ---- which tile
     const int kvh = blockIdx.x % a.Hkv;
@@ -131,7 +144,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     const int r_last = min(rows - 1, r0 + kRowsPerWG - 1);
     const int nTt = (r_last / G) / kKeysPerTile + 1;      // tree tiles up to the largest node of this row tile
     const int nT = nTp + nTt;
-    const int nIt = (nT + 1) / 2;
+    const int nIt = (nT + 1) / 2;                          // tiles per wave (the last odd one may not exist)
 
     const size_t kv_row_bytes = (size_t)a.Hkv * D * 2;
     const char* kp = static_cast<const char*>(a.kp) + (size_t)sa.kv_off[seq] * kv_row_bytes + (size_t)kvh * D * 2;
@@ -140,70 +153,60 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     const char* vt = static_cast<const char*>(a.vt) + (size_t)node_base * kv_row_bytes + (size_t)kvh * D * 2;
 
     // ---- Q fragments (B operand: lane holds query n, head-dim slice 16*kk + 8*g .. +7)
-    bf16x8 qf[QB][KK];
-    int rq[QB];
-    const uint64_t* mrow[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const int r = r0 + 32 * QB * wq + 32 * qb + n;
-        rq[qb] = r;
-        const int rc = min(r, rows - 1);
+    bf16x8 qf[KK];
+    const int rq = r0 + 32 * wq + n;
+    const uint64_t* mrow;
+    {
+        const int rc = min(rq, rows - 1);
         const int j = rc / G, h = kvh * G + rc % G;
         const __bf16* qrow = static_cast<const __bf16*>(a.q) + ((size_t)(node_base + j) * a.Hq + h) * D;
-        mrow[qb] = a.mask + (size_t)(node_base + j) * a.mask_words;
+        mrow = a.mask + (size_t)(node_base + j) * a.mask_words;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
-            qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * g);
+        for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * g);
     }
 
-    floatx16 acc[DB][QB];                        // O^T: [32-wide head-dim block][query block]
+    floatx16 acc[DB];                            // O^T, one 32-wide head-dim block each
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[db][qb][i] = 0.0f;
-    float m_run[QB], l_run[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -1e30f; l_run[qb] = 0.0f; }
+        for (int i = 0; i < 16; ++i) acc[db][i] = 0.0f;
+    floatx16 S[2];                               // scores of a 32-key half tile: half e in buffer e
+    uint32_t pbw[2][2][4];                       // numerators as bf16 pairs [buffer][16-key step][word]
+    float m_run = -1e30f, l_run = 0.0f;
     const float c2 = a.scale * 1.4426950408889634f;     // scores are used as exp2(c2 * s)
 
-    // ---- direct-load plan: a stage holds four matrices (0: K of the even tile, 1: V of the
-    //      even tile, 2: K odd, 3: V odd) of kLoadsPerMat wave-wide loads each; wave w fills
-    //      loads [LPW*part, LPW*part + LPW) of matrix w / (NW/4).  Lane i of load x writes row
-    //      position R = kRowsPerLoad*x + i/kChunks, chunk position i % kChunks, so it must fetch
-    //      chunk (i % kChunks) ^ swz(R) of that key row; with these swizzles the lane's byte
-    //      offset depends on x mod 4 only.
-    constexpr int LPW = L::kLoadsPerMat / (NW / 4);
-    const int ld_mm = wave / (NW / 4), ld_x0 = (wave % (NW / 4)) * LPW;
-    const bool ld_is_v = ld_mm & 1;
+    // ---- direct-load plan.  Matrix mm = wave / 2 (0: K of the even tile, 1: K odd, 2: V even,
+    //      3: V odd) takes kLoadsPerMat wave-wide loads; the two waves of a matrix issue half
+    //      each.  Lane i of load x writes row position R = kRowsPerLoad*x + i/kChunks, chunk
+    //      position i % kChunks, so it must fetch chunk (i % kChunks) ^ swz(R) of that key row;
+    //      with these swizzles the lane's byte offset depends on x mod 4 only.
+    constexpr int LPW = L::kLoadsPerMat / 2;
+    const int ld_mm = wave >> 1, ld_x0 = (wave & 1) * LPW;
+    const bool ld_is_v = ld_mm >= 2;
+    const int ld_par = ld_mm & 1;
     const int ld_lrow = lane / L::kChunks, ld_cpos = lane % L::kChunks;
-    int ld_voff[4];                               // byte offset of the lane's chunk for x mod 4
+    auto lane_offsets = [=](bool is_v, int (&voff)[4]) {
 #pragma unroll
-    for (int xm = 0; xm < 4; ++xm) {
-        const int row = L::kRowsPerLoad * xm + ld_lrow;
-        const int c = ld_cpos ^ (ld_is_v ? L::swz_v(row) : L::swz_k(row));
-        ld_voff[xm] = ld_lrow * (int)kv_row_bytes + 16 * c;
-    }
-    const char* const st_prefix = ld_is_v ? vp : kp;
-    const char* const st_tree = ld_is_v ? vt : kt;
-    unsigned char* const st_dst = lds + ld_mm * L::kMatBytes + ld_x0 * 1024;
+        for (int xm = 0; xm < 4; ++xm) {
+            const int row = L::kRowsPerLoad * xm + ld_lrow;
+            const int c = ld_cpos ^ (is_v ? L::swz_v(row) : L::swz_k(row));
+            voff[xm] = ld_lrow * (int)kv_row_bytes + 16 * c;
+        }
+    };
+    // Loads this wave's share of tile t (prefix or tree part of K or V) to LDS byte dst.
     // (captures by value: a conditional between variables captured by reference would be a
     //  conditional between addresses and force them into scratch memory)
-    auto issue_stage = [=](int it) {
-        const int t = 2 * it + (ld_mm >> 1);                     // the tile this wave stages
-        if (t >= nT) return;                                     // odd tile past the end: nobody reads it
-        unsigned char* dst0 = st_dst + (it & 1) * L::kStageBytes;
+    auto issue_tile = [=](const char* prefix_region, const char* tree_region, const int (&voff)[4], int t, uint32_t dst) {
+        if (t >= nT) return;
         const bool prefix = t < nTp;
-        const char* region = prefix ? st_prefix : st_tree;
+        const char* region = prefix ? prefix_region : tree_region;
         const int key0 = (prefix ? t : t - nTp) * kKeysPerTile;
         const int limit = prefix ? P : N;
         if (key0 + kKeysPerTile <= limit) {                      // whole tile in range: uniform base + lane offset
             const char* base = region + (size_t)(key0 + L::kRowsPerLoad * ld_x0) * kv_row_bytes;
             static_for<LPW>([=](auto xc) {
                 constexpr int x = decltype(xc)::value;
-                direct_load_16(base + (size_t)(L::kRowsPerLoad * x) * kv_row_bytes, (uint32_t)ld_voff[x & 3],
-                               lds_address(dst0) + x * 1024);
+                direct_load_16(base + (size_t)(L::kRowsPerLoad * x) * kv_row_bytes, (uint32_t)voff[x & 3], dst + x * 1024);
             });
         } else {
             // rows past the end read row 0 of the region (a key every query may see, so its
@@ -212,19 +215,20 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                 constexpr int x = decltype(xc)::value;
                 const int rowx = L::kRowsPerLoad * (ld_x0 + x);
                 const int key = key0 + rowx + ld_lrow;
-                const uint32_t off = (key < limit) ? (uint32_t)(key0 + rowx) * (uint32_t)kv_row_bytes + (uint32_t)ld_voff[x & 3]
-                                                   : (uint32_t)(ld_voff[x & 3] - ld_lrow * (int)kv_row_bytes);
-                direct_load_16(region, off, lds_address(dst0) + x * 1024);
+                const uint32_t off = (key < limit) ? (uint32_t)(key0 + rowx) * (uint32_t)kv_row_bytes + (uint32_t)voff[x & 3]
+                                                   : (uint32_t)(voff[x & 3] - ld_lrow * (int)kv_row_bytes);
+                direct_load_16(region, off, dst + x * 1024);
             });
         }
     };
+    const uint32_t lds0 = lds_address(lds);
 
-    // ---- LDS read offsets of this lane
+    // ---- LDS read offsets of this lane (the even/odd tile choice of the wave folded in)
     int k_off[KK];                               // K fragment of k-step kk, key row n (+32*ka rows)
     {
         const int h = g ^ L::swz_k(n);           // (2*kk + g) ^ swz == (2*kk) ^ (g ^ swz)
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) k_off[kk] = n * L::kRowBytes + (((2 * kk) ^ h) << 4);
+        for (int kk = 0; kk < KK; ++kk) k_off[kk] = wk * L::kMatBytes + n * L::kRowBytes + (((2 * kk) ^ h) << 4);
     }
     // V^T fragments come from the LDS transpose read (ds_read_b64_tr_b16).  Measured lane
     // layout of that instruction, per group of 16 lanes: lane i supplies the address of four
@@ -241,189 +245,261 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
             const int chunk = 4 * db + 2 * grp + ((sl & 3) >> 1);
-            v_off[db] = row * L::kRowBytes + ((chunk ^ L::swz_v(row)) << 4) + 8 * (sl & 1);
+            v_off[db] = L::kVBase + wk * L::kMatBytes + row * L::kRowBytes + ((chunk ^ L::swz_v(row)) << 4) + 8 * (sl & 1);
         }
     }
 
-    // Visibility words of a tile's 64 keys for the lane's two queries: all ones inside the
-    // prefix, the low bits for a ragged last prefix tile, the ancestor-mask word for a tree
-    // tile.  They are fetched one iteration ahead, BEFORE that iteration's direct loads are
-    // issued, so that the wait the compiler places at their first use finds nothing in flight.
-    uint64_t vis_next[QB];
-    auto fetch_vis = [=](int t, uint64_t (&v)[QB]) {
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) v[qb] = (t >= nTp && t < nT) ? mrow[qb][t - nTp] : ~0ull;
+    // Visibility words of a tile's 64 keys for the lane's query: all ones inside the prefix,
+    // the low bits for a ragged last prefix tile, the ancestor-mask word for a tree tile,
+    // zero for a tile that does not exist.
+    auto fetch_vis = [=](int t) -> uint64_t { return (t >= nTp && t < nT) ? mrow[t - nTp] : ~0ull; };
+    auto fix_vis = [=](int t, uint64_t v) -> uint64_t {
+        if (t >= nT) return 0ull;
+        if (t < nTp && (t + 1) * kKeysPerTile > P) return (1ull << (P - t * kKeysPerTile)) - 1ull;
+        return v;
     };
-    fetch_vis(wk, vis_next);
-    issue_stage(0);
+
+    // ---- one half step of the skewed loop, for the 32-key half e of tile i (SP = i & 1 is the
+    //      LDS slot of tile i).  HS: numerators of this half from S[e] into pbw[e]; HP: second
+    //      product of the previous half (pbw[e^1]); HQ: first product of the next half into
+    //      S[e^1]; MK: this half needs its mask (vis32: the lane's 32 visibility bits >> 4g).
+    //      The previous half is the upper half of tile i-1 (slot SP^1) for e = 0 and the lower
+    //      half of tile i for e = 1; the next half is the upper half of tile i for e = 0 and
+    //      the lower half of tile i+1 (slot SP^1) for e = 1.
+    const floatx16 zero16 = { 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0 };
+    float ls_half = 0.0f;                        // the lane's sum of numerators of the half just done
+    auto half_step = [&](auto hp_c, auto hq_c, auto hs_c, auto mk_c, auto sp_c, auto e_c, uint32_t vis32) {
+        constexpr bool HP = decltype(hp_c)::value, HQ = decltype(hq_c)::value;
+        constexpr bool HS = decltype(hs_c)::value, MK = decltype(mk_c)::value;
+        constexpr int SP = decltype(sp_c)::value, E = decltype(e_c)::value, O = E ^ 1;
+        constexpr int NP2 = 2 * DB, NQ2 = KK;                      // MFMAs per half: second, first product
+        static_assert(NP2 == NQ2, "the interleave below alternates the two products");
+        constexpr int NS = (HP ? NP2 : 0) + (HQ ? NQ2 : 0);       // MFMA slots of this half step
+        constexpr int kVsrc = (E == 0 ? (SP ^ 1) : SP) * L::kSlotBytes + 32 * O * L::kRowBytes;
+        constexpr int kKsrc = (E == 0 ? SP : (SP ^ 1)) * L::kSlotBytes + 32 * O * L::kRowBytes;
+        const float mc = m_run * c2;
+        float ls = 0.0f;
+        float pt[8][2];
+        // Register i of a 32x32 score block holds key row 8*(i/4) + 4*g + i%4, query column n.
+        // Item h of the vector work: pair p = h/2 covers scores 2p, 2p+1; even items take the
+        // exponentials, odd items mask, sum and pack them.
+        auto valu_item = [&](auto hc) {
+            constexpr int h = decltype(hc)::value, p = h / 2, i = 2 * p;
+            if constexpr (h % 2 == 0) {
+                pt[p][0] = fast_exp2(fmaf(S[E][i], c2, -mc));
+                pt[p][1] = fast_exp2(fmaf(S[E][i + 1], c2, -mc));
+            } else {
+                float p0 = pt[p][0], p1 = pt[p][1];
+                if constexpr (MK) {
+                    p0 = and_bits(p0, __builtin_amdgcn_sbfe((int)vis32, 8 * (i / 4) + (i % 4), 1));
+                    p1 = and_bits(p1, __builtin_amdgcn_sbfe((int)vis32, 8 * (i / 4) + (i % 4) + 1, 1));
+                }
+                ls += p0 + p1;
+                floatx2 pp = { p0, p1 };
+                uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
+                asm volatile("" : "+v"(w));                    // keep the conversion in this scheduling group
+                pbw[E][p / 4][p % 4] = w;
+            }
+        };
+        if constexpr (NS > 0) {
+            // with both products, even slots belong to the second product and odd slots to the first
+            bf16x8 fr[NS];
+            auto read_slot = [&](auto sc) {
+                constexpr int s = decltype(sc)::value;
+                constexpr bool isP = HP && (!HQ || s % 2 == 0);
+                constexpr int idx = (HP && HQ) ? s / 2 : s;
+                if constexpr (isP) {
+                    // k-slot (g, e) of step ts is key 8*(2*ts + e/4) + 4*g + e%4 of the half
+                    constexpr int ts = idx / DB, db = idx % DB;
+                    union { short4v h[2]; bf16x8 v; } f;
+#pragma unroll
+                    for (int half = 0; half < 2; ++half)
+                        f.h[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (lds_short4)(lds + kVsrc + 8 * (2 * ts + half) * L::kRowBytes + v_off[db]));
+                    fr[s] = f.v;
+                } else {
+                    fr[s] = *reinterpret_cast<const bf16x8*>(lds + kKsrc + k_off[idx]);
+                }
+            };
+            auto mfma_slot = [&](auto sc) {
+                constexpr int s = decltype(sc)::value;
+                constexpr bool isP = HP && (!HQ || s % 2 == 0);
+                constexpr int idx = (HP && HQ) ? s / 2 : s;
+                if constexpr (isP) {
+                    constexpr int ts = idx / DB, db = idx % DB;
+                    union { uint32_t w[4]; bf16x8 v; } b;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) b.w[w] = pbw[O][ts][w];
+                    acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[s], b.v, acc[db], 0, 0, 0);
+                } else {
+                    if constexpr (idx == 0)
+                        S[O] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[s], qf[idx], zero16, 0, 0, 0);
+                    else
+                        S[O] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[s], qf[idx], S[O], 0, 0, 0);
+                }
+            };
+            constexpr int IPS = 16 / NS;                       // items of vector work per slot
+            static_for<(kLead < NS ? kLead : NS)>([&](auto sc) { read_slot(sc); });
+            static_for<NS>([&](auto sc) {
+                constexpr int s = decltype(sc)::value;
+                if constexpr (s + kLead < NS) read_slot(std::integral_constant<int, s + kLead>{});
+                mfma_slot(sc);
+                if constexpr (HS)
+                    static_for<IPS>([&](auto hc) { valu_item(std::integral_constant<int, s * IPS + decltype(hc)::value>{}); });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        } else if constexpr (HS) {
+            static_for<16>(valu_item);
+        }
+        if constexpr (HS) ls_half = ls;
+    };
+    // Rare: some score of half e tops the reference maximum by too much (always so for the
+    // first half a wave sees).  Raise the reference to the true maximum, rescale what has been
+    // accumulated (the second product of the previous half is complete here), and redo this
+    // half's numerators.
+    auto redo_half = [&](auto e_c, bool mk, uint32_t vis32) {
+        constexpr int E = decltype(e_c)::value;
+        float sm[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            sm[i] = (mk && !((vis32 >> (8 * (i / 4) + (i % 4))) & 1u)) ? -INFINITY : S[E][i];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) mx = max3(mx, sm[i], sm[i + 1]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = fast_exp2((m_run - m_new) * c2);
+        m_run = m_new;
+        l_run *= alpha;
+        if (__any(alpha != 0.0f && alpha != 1.0f)) {           // alpha 0: accumulators still 0
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[db][i] *= alpha;
+        }
+        const float mc2 = m_run * c2;
+        float ls = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            const float p0 = fast_exp2(fmaf(sm[i], c2, -mc2));
+            const float p1 = fast_exp2(fmaf(sm[i + 1], c2, -mc2));
+            ls += p0 + p1;
+            floatx2 pp = { p0, p1 };
+            pbw[E][i / 8][(i / 2) % 4] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
+        }
+        ls_half = ls;
+    };
+    // A half step of the steady state: all three parts, then the (rare) raise of the reference.
+    auto run_half = [&](auto mk_c, auto sp_c, auto e_c, uint32_t vis32) {
+        half_step(std::true_type{}, std::true_type{}, std::true_type{}, mk_c, sp_c, e_c, vis32);
+        if (__any(!(ls_half <= kSumLimit))) redo_half(e_c, decltype(mk_c)::value, vis32);
+        l_run += ls_half;
+    };
+
+    // ---- prologue.  The steady-state half step always runs all three parts; what it reads for
+    //      a half that does not exist must therefore be harmless.  V slots start as zeros and
+    //      the numerators start as zeros (0 * 0 adds nothing to the accumulators); K of a tile
+    //      that does not exist is whatever the slot held, and the scores it gives are masked.
+    {
+        const uint4 z = { 0u, 0u, 0u, 0u };
+        for (int x = tid; x < 2 * L::kSlotBytes / 16; x += 512) reinterpret_cast<uint4*>(lds + L::kVBase)[x] = z;
+#pragma unroll
+        for (int bu = 0; bu < 2; ++bu)
+#pragma unroll
+            for (int ts = 0; ts < 2; ++ts)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) pbw[bu][ts][w] = 0u;
+    }
+    __syncthreads();
+    {
+        // K of the wave pair's first two tiles (tile mm = 2*slot + parity), V of the first
+        int voff_k[4];
+        lane_offsets(false, voff_k);
+        issue_tile(kp, kt, voff_k, ld_mm, lds0 + ld_mm * L::kMatBytes + ld_x0 * 1024);
+    }
+    int ld_voff[4];
+    lane_offsets(ld_is_v, ld_voff);
+    const char* const st_prefix = ld_is_v ? vp : kp;
+    const char* const st_tree = ld_is_v ? vt : kt;
+    const uint32_t st_dst = lds0 + (ld_is_v ? L::kVBase : 0) + ld_par * L::kMatBytes + ld_x0 * 1024;
+    if (ld_is_v) issue_tile(st_prefix, st_tree, ld_voff, ld_par, st_dst);
     wait_direct_loads();
     __syncthreads();
+    // first product of the lower half of tile 0 (K slot 0) into S[0]
+    half_step(std::false_type{}, std::true_type{}, std::false_type{}, std::false_type{},
+              std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, 0u);
 
-    for (int it = 0; it < nIt; ++it) {
-        uint64_t vis[QB];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            vis[qb] = vis_next[qb];
-            asm volatile("" : "+v"(vis[qb]));                     // first use of the prefetched words
-        }
-        fetch_vis(2 * (it + 1) + wk, vis_next);
-        if (it + 1 < nIt) issue_stage(it + 1);
-
-        const int t = 2 * it + wk;
-        if (t < nT) {
-            bool need_mask = t >= nTp;
-            if (t < nTp && (t + 1) * kKeysPerTile > P) {
-                const int live = P - t * kKeysPerTile;              // 1..63
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) vis[qb] = (1ull << live) - 1ull;
-                need_mask = true;
-            }
-            uint64_t vis_any = 0;
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) vis_any |= vis[qb];
-            if (__any(vis_any != 0ull)) {
-                const unsigned char* Ks = lds + (it & 1) * L::kStageBytes + 2 * wk * L::kMatBytes;
-                const unsigned char* Vs = Ks + L::kMatBytes;
-
-                // ---- S^T = K Q^T for the two 32-key blocks of the tile: independent
-                //      accumulation chains, so consecutive MFMAs never wait on each other
-                floatx16 S[2][QB];
-                const floatx16 zero16 = { 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0 };
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk) {
-                    bf16x8 kf[2];
-#pragma unroll
-                    for (int ka = 0; ka < 2; ++ka)
-                        kf[ka] = *reinterpret_cast<const bf16x8*>(Ks + 32 * ka * L::kRowBytes + k_off[kk]);
-#pragma unroll
-                    for (int ka = 0; ka < 2; ++ka)
-#pragma unroll
-                        for (int qb = 0; qb < QB; ++qb)
-                            S[ka][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ka], qf[qb][kk], kk == 0 ? zero16 : S[ka][qb], 0, 0, 0);
-                }
-
-                // ---- mask + online softmax.  Register i of a 32x32 block holds key row
-                //      8*(i/4) + 4*g + i%4 of the block, query column n.
-                bf16x8 pb[QB][2][2];                      // [query block][key block][16-key step]
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    if (need_mask) {
-#pragma unroll
-                        for (int ka = 0; ka < 2; ++ka) {
-                            const uint32_t v32 = (uint32_t)(vis[qb] >> (32 * ka + 4 * g));
-#pragma unroll
-                            for (int i = 0; i < 16; ++i)
-                                if (!((v32 >> (8 * (i / 4) + (i % 4))) & 1u)) S[ka][qb][i] = -INFINITY;
-                        }
-                    }
-                    float mx = -INFINITY;
-#pragma unroll
-                    for (int ka = 0; ka < 2; ++ka)
-#pragma unroll
-                        for (int i = 0; i < 16; i += 2) mx = max3(mx, S[ka][qb][i], S[ka][qb][i + 1]);
-                    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-                    // The reference maximum only has to keep exp2 in range, so it is raised
-                    // lazily: the accumulators are rescaled only when a score tops it by kLazy.
-                    if (__any(mx * c2 > m_run[qb] * c2 + kLazy)) {
-                        const float m_new = fmaxf(m_run[qb], mx);
-                        const float alpha = fast_exp2((m_run[qb] - m_new) * c2);
-                        m_run[qb] = m_new;
-                        l_run[qb] *= alpha;
-                        if (__any(alpha != 0.0f && alpha != 1.0f)) {   // alpha 0: accumulators still 0
-#pragma unroll
-                            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                                for (int i = 0; i < 16; ++i) acc[db][qb][i] *= alpha;
-                        }
-                    }
-                    const float mc = m_run[qb] * c2;
-                    float ls = 0.0f;
-#pragma unroll
-                    for (int ka = 0; ka < 2; ++ka)
-#pragma unroll
-                        for (int i = 0; i < 16; i += 2) {
-                            const float p0 = fast_exp2(fmaf(S[ka][qb][i], c2, -mc));
-                            const float p1 = fast_exp2(fmaf(S[ka][qb][i + 1], c2, -mc));
-                            ls += p0 + p1;
-                            floatx2 pp = { p0, p1 };
-                            const bf16x2 pc = __builtin_convertvector(pp, bf16x2);
-                            pb[qb][ka][i / 8][i % 8] = pc[0];
-                            pb[qb][ka][i / 8][i % 8 + 1] = pc[1];
-                        }
-                    l_run[qb] += ls;
-                }
-
-                // ---- O^T += V^T P^T.  k-slot (g, e) of step (ka, ts) is key
-                //      32*ka + 8*(2*ts + e/4) + 4*g + e%4, as in the P registers.
-#pragma unroll
-                for (int ka = 0; ka < 2; ++ka)
-#pragma unroll
-                    for (int ts = 0; ts < 2; ++ts)
-#pragma unroll
-                        for (int db = 0; db < DB; ++db) {
-                            union { short4v h[2]; bf16x8 v; } f;
-#pragma unroll
-                            for (int half = 0; half < 2; ++half) {
-                                const int krow = 32 * ka + 8 * (2 * ts + half);      // + s/4 + 4*g in v_off
-                                f.h[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                                    (lds_short4)(Vs + krow * L::kRowBytes + v_off[db]));
-                            }
-#pragma unroll
-                            for (int qb = 0; qb < QB; ++qb)
-                                acc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v, pb[qb][ka][ts], acc[db][qb], 0, 0, 0);
-                        }
-            }
-        }
-        wait_direct_loads();
-        __syncthreads();
+    // ---- step i: lower half of tile i; barrier; loads of K(i+2) and V(i+1) into the slots
+    //      the lower half was the last to read; upper half of tile i
+    auto issue_step_loads = [=](int i) {
+        issue_tile(st_prefix, st_tree, ld_voff, ld_is_v ? 2 * (i + 1) + ld_par : 2 * (i + 2) + ld_par,
+                   st_dst + ((ld_is_v ? i + 1 : i) & 1) * L::kSlotBytes);
+    };
+    // Steps whose tiles are whole prefix tiles for both waves of a row block need no mask.
+    const int nPlain = (P / kKeysPerTile) / 2;             // tiles 2i and 2i+1 both below P / 64
+    int i = 0;
+    for (; i + 1 < nPlain; i += 2) {
+        static_for<2>([&](auto sp_c) {
+            run_half(std::false_type{}, sp_c, std::integral_constant<int, 0>{}, 0u);
+            wait_direct_loads();
+            __syncthreads();
+            issue_step_loads(i + decltype(sp_c)::value);
+            run_half(std::false_type{}, sp_c, std::integral_constant<int, 1>{}, 0u);
+        });
     }
+    // The rest: ragged prefix tile, tree tiles (ancestor mask), tiles that do not exist (all
+    // masked), until the second product of the last real half has run.
+    uint64_t visC = fix_vis(2 * i + wk, fetch_vis(2 * i + wk));
+    uint64_t visN = fix_vis(2 * i + 2 + wk, fetch_vis(2 * i + 2 + wk));
+    for (; i <= nIt; i += 2) {
+        static_for<2>([&](auto sp_c) {
+            const int t2 = 2 * (i + decltype(sp_c)::value) + wk + 4;
+            uint64_t visL = fetch_vis(t2);
+            run_half(std::true_type{}, sp_c, std::integral_constant<int, 0>{}, (uint32_t)visC >> (4 * g));
+            wait_direct_loads();
+            __syncthreads();
+            asm volatile("" : "+v"(visL));
+            issue_step_loads(i + decltype(sp_c)::value);
+            run_half(std::true_type{}, sp_c, std::integral_constant<int, 1>{}, (uint32_t)(visC >> 32) >> (4 * g));
+            visC = visN;
+            visN = fix_vis(t2, visL);
+        });
+    }
+    __syncthreads();                                         // every LDS read is done before the merge reuses it
 
-    // ---- merge the two key halves of each row half through LDS, normalise, store
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) l_run[qb] += __shfl_xor(l_run[qb], 32, kWave);
+    // ---- merge the two key halves of each row block through LDS, normalise, store
+    l_run += __shfl_xor(l_run, 32, kWave);
     float* xs = reinterpret_cast<float*>(lds);               // [wq][register][lane]
-    constexpr int NR = DB * QB * 16 + 2 * QB;
+    constexpr int NR = DB * 16 + 2;
     if (wk == 1) {
         float* dst = xs + (size_t)wq * NR * kWave + lane;
         int r = 0;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) dst[(r++) * kWave] = acc[db][qb][i];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) dst[(r++) * kWave] = m_run[qb];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) dst[(r++) * kWave] = l_run[qb];
+            for (int i = 0; i < 16; ++i) dst[(r++) * kWave] = acc[db][i];
+        dst[(r++) * kWave] = m_run;
+        dst[(r++) * kWave] = l_run;
     }
     __syncthreads();
     if (wk == 0) {
         const float* src = xs + (size_t)wq * NR * kWave + lane;
-        float f0[QB], f1[QB], inv[QB];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            const float m1 = src[(NR - 2 * QB + qb) * kWave], l1 = src[(NR - QB + qb) * kWave];
-            const float m = fmaxf(m_run[qb], m1);
-            f0[qb] = exp2f((m_run[qb] - m) * c2);
-            f1[qb] = exp2f((m1 - m) * c2);
-            inv[qb] = 1.0f / (l_run[qb] * f0[qb] + l1 * f1[qb]);
-        }
+        const float m1 = src[(NR - 2) * kWave], l1 = src[(NR - 1) * kWave];
+        const float m = fmaxf(m_run, m1);
+        const float f0 = exp2f((m_run - m) * c2);
+        const float f1 = exp2f((m1 - m) * c2);
+        const float inv = 1.0f / (l_run * f0 + l1 * f1);
         int r = 0;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float o1 = src[(r++) * kWave];
-                    acc[db][qb][i] = (acc[db][qb][i] * f0[qb] + o1 * f1[qb]) * inv[qb];
-                }
+            for (int i = 0; i < 16; ++i) {
+                const float o1 = src[(r++) * kWave];
+                acc[db][i] = (acc[db][i] * f0 + o1 * f1) * inv;
+            }
         // register i of block db is head-dim index 32*db + 8*(i/4) + 4*g + i%4
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            if (rq[qb] >= rows) continue;
-            const int j = rq[qb] / G, h = kvh * G + rq[qb] % G;
+        if (rq < rows) {
+            const int j = rq / G, h = kvh * G + rq % G;
             __bf16* orow = static_cast<__bf16*>(a.out) + ((size_t)(node_base + j) * a.Hq + h) * D;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -432,7 +508,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                     union { bf16x2 p[2]; uint2 v; } o;
 #pragma unroll
                     for (int ii = 0; ii < 2; ++ii) {
-                        floatx2 pr = { acc[db][qb][4 * ib + 2 * ii], acc[db][qb][4 * ib + 2 * ii + 1] };
+                        floatx2 pr = { acc[db][4 * ib + 2 * ii], acc[db][4 * ib + 2 * ii + 1] };
                         o.p[ii] = __builtin_convertvector(pr, bf16x2);
                     }
                     *reinterpret_cast<uint2*>(orow + 32 * db + 8 * ib + 4 * g) = o.v;
@@ -441,13 +517,13 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     }
 }
 
-template <int D, int QB>
+template <int D>
 static hipError_t launch_one(const AttnArgs& a, const SeqArgs& sa, int tiles, hipStream_t stream)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<D, QB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Geo<D>::kLdsBytes);
     if (e != hipSuccess) return e;
-    tree_attn_mfma_kernel<D, QB><<<tiles * a.Hkv, 64 * 2 * (4 / QB), Geo<D>::kLdsBytes, stream>>>(a, sa);
+    tree_attn_mfma_kernel<D><<<tiles * a.Hkv, 512, Geo<D>::kLdsBytes, stream>>>(a, sa);
     return hipGetLastError();
 }
 
@@ -461,7 +537,7 @@ hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, hipStream_t stre
     }
     a.tile_off[sa.n_seq] = tiles;
     if (tiles == 0) return hipSuccess;
-    return a.d == 128 ? launch_one<128, kQB>(a, sa, tiles, stream) : launch_one<64, kQB>(a, sa, tiles, stream);
+    return a.d == 128 ? launch_one<128>(a, sa, tiles, stream) : launch_one<64>(a, sa, tiles, stream);
 }
 
 }  // namespace dyspec
