@@ -62,14 +62,19 @@ typedef __attribute__((address_space(1))) const void* global_ptr;
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v* lds_short4;
+typedef __attribute__((address_space(3))) const bf16x8* lds_bf16x8;
 
 constexpr int kRowsPerWG = 128;
 constexpr int kKeysPerTile = 64;
 constexpr float kSumLimit = 1024.0f;      // a lane's tile sum above this raises the reference maximum
 #ifndef DYSPEC_ATTN_LEAD
-#define DYSPEC_ATTN_LEAD 3
+#define DYSPEC_ATTN_LEAD 2
 #endif
-constexpr int kLead = DYSPEC_ATTN_LEAD;   // MFMA slots between an LDS read and the MFMA that uses it
+constexpr int kLead = DYSPEC_ATTN_LEAD;   // fragment slots between an LDS read and the MFMAs that use it
+#ifndef DYSPEC_ATTN_QB
+#define DYSPEC_ATTN_QB 1
+#endif
+constexpr int kQB = DYSPEC_ATTN_QB;       // 32-row query blocks per wave (see the kernel)
 
 // v_exp_f32 without the denormal-range fix-up: inputs below -126 give 0, which is what the
 // softmax wants.
@@ -98,6 +103,13 @@ __device__ __forceinline__ float max3(float a, float b, float c)
     return r;
 }
 
+#ifdef DBG_STAMPS
+__device__ unsigned long long dbg_stamps[4096 * 8];
+#define STAMP(k) do { if (lane == 0) dbg_stamps[(blockIdx.x * 8 + wave) * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define STAMP(k) do { } while (0)
+#endif
+
 template <int D> struct Geo {
     static constexpr int kRowBytes = 2 * D;
     static constexpr int kChunks = D / 8;                        // 16-byte chunks per row
@@ -112,22 +124,25 @@ template <int D> struct Geo {
     __device__ static __forceinline__ int swz_v(int r) { return D == 128 ? ((r & 3) << 2) : 0; }
 };
 
-template <int D>
-__global__ __launch_bounds__(512) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs sa)
+// QB = 32-row query blocks per wave.  Every K/V fragment read from LDS feeds QB MFMAs, so
+// QB = 2 halves the LDS traffic per flop: 4 waves, one per SIMD, with up to 512 registers each.
+// QB = 1: 8 waves, two per SIMD, 256 registers each.
+template <int D, int QB>
+__global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs sa)
 {
     using L = Geo<D>;
+    constexpr int NWQ = 4 / QB;                  // waves along the row dimension
+    constexpr int NW = 2 * NWQ;                  // waves per workgroup
     constexpr int KK = D / 16;                   // k-steps of the QK^T product
     constexpr int DB = D / 32;                   // 32-wide blocks of the head dimension
-    constexpr int NQ = 2 * KK;                   // MFMAs of one tile's first product
-    constexpr int NP = 4 * DB;                   // MFMAs of one tile's second product
-    static_assert(NQ == NP, "the interleave below alternates the two products");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, g = lane >> 5;
-    const int wq = wave & 3, wk = wave >> 2;
+    const int wq = wave % NWQ, wk = wave / NWQ;
 
+    STAMP(0);
     // ---- which tile
     const int kvh = blockIdx.x % a.Hkv;
     const int tile = blockIdx.x / a.Hkv;
@@ -153,35 +168,41 @@ __global__ __launch_bounds__(512) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs
     const char* vt = static_cast<const char*>(a.vt) + (size_t)node_base * kv_row_bytes + (size_t)kvh * D * 2;
 
     // ---- Q fragments (B operand: lane holds query n, head-dim slice 16*kk + 8*g .. +7)
-    bf16x8 qf[KK];
-    const int rq = r0 + 32 * wq + n;
-    const uint64_t* mrow;
-    {
-        const int rc = min(rq, rows - 1);
+    bf16x8 qf[QB][KK];
+    int rq[QB];
+    const uint64_t* mrow[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        rq[qb] = r0 + 32 * QB * wq + 32 * qb + n;
+        const int rc = min(rq[qb], rows - 1);
         const int j = rc / G, h = kvh * G + rc % G;
         const __bf16* qrow = static_cast<const __bf16*>(a.q) + ((size_t)(node_base + j) * a.Hq + h) * D;
-        mrow = a.mask + (size_t)(node_base + j) * a.mask_words;
+        mrow[qb] = a.mask + (size_t)(node_base + j) * a.mask_words;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * g);
+        for (int kk = 0; kk < KK; ++kk) qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * g);
     }
 
-    floatx16 acc[DB];                            // O^T, one 32-wide head-dim block each
+    floatx16 acc[DB][QB];                        // O^T: [32-wide head-dim block][query block]
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[db][i] = 0.0f;
-    floatx16 S[2];                               // scores of a 32-key half tile: half e in buffer e
-    uint32_t pbw[2][2][4];                       // numerators as bf16 pairs [buffer][16-key step][word]
-    float m_run = -1e30f, l_run = 0.0f;
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[db][qb][i] = 0.0f;
+    floatx16 S[2][QB];                           // scores of a 32-key half tile: half e in buffer e
+    uint32_t pbw[2][QB][2][4];                   // numerators as bf16 pairs [buffer][query block][16-key step][word]
+    float m_run[QB], l_run[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -1e30f; l_run[qb] = 0.0f; }
     const float c2 = a.scale * 1.4426950408889634f;     // scores are used as exp2(c2 * s)
 
-    // ---- direct-load plan.  Matrix mm = wave / 2 (0: K of the even tile, 1: K odd, 2: V even,
-    //      3: V odd) takes kLoadsPerMat wave-wide loads; the two waves of a matrix issue half
-    //      each.  Lane i of load x writes row position R = kRowsPerLoad*x + i/kChunks, chunk
-    //      position i % kChunks, so it must fetch chunk (i % kChunks) ^ swz(R) of that key row;
-    //      with these swizzles the lane's byte offset depends on x mod 4 only.
-    constexpr int LPW = L::kLoadsPerMat / 2;
-    const int ld_mm = wave >> 1, ld_x0 = (wave & 1) * LPW;
+    // ---- direct-load plan.  Matrix mm (0: K of the even tile, 1: K odd, 2: V even, 3: V odd)
+    //      takes kLoadsPerMat wave-wide loads, issued by NW/4 waves.  Lane i of load x writes row
+    //      position R = kRowsPerLoad*x + i/kChunks, chunk position i % kChunks, so it must fetch
+    //      chunk (i % kChunks) ^ swz(R) of that key row; with these swizzles the lane's byte
+    //      offset depends on x mod 4 only.
+    constexpr int LPW = L::kLoadsPerMat / (NW / 4);
+    const int ld_mm = wave / (NW / 4), ld_x0 = (wave % (NW / 4)) * LPW;
     const bool ld_is_v = ld_mm >= 2;
     const int ld_par = ld_mm & 1;
     const int ld_lrow = lane / L::kChunks, ld_cpos = lane % L::kChunks;
@@ -196,7 +217,8 @@ __global__ __launch_bounds__(512) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs
     // Loads this wave's share of tile t (prefix or tree part of K or V) to LDS byte dst.
     // (captures by value: a conditional between variables captured by reference would be a
     //  conditional between addresses and force them into scratch memory)
-    auto issue_tile = [=](const char* prefix_region, const char* tree_region, const int (&voff)[4], int t, uint32_t dst) {
+    auto issue_tile = [=](const char* prefix_region, const char* tree_region, const int (&voff)[4], int t, uint32_t dst)
+        __attribute__((always_inline)) {
         if (t >= nT) return;
         const bool prefix = t < nTp;
         const char* region = prefix ? prefix_region : tree_region;
@@ -222,13 +244,22 @@ __global__ __launch_bounds__(512) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs
         }
     };
     const uint32_t lds0 = lds_address(lds);
+    // steady state: this wave's matrix, the lane offsets for it, and its place in an LDS slot
+    int ld_voff[4];
+    lane_offsets(ld_is_v, ld_voff);
+    const char* const st_prefix = ld_is_v ? vp : kp;
+    const char* const st_tree = ld_is_v ? vt : kt;
+    const uint32_t st_dst = lds0 + (ld_is_v ? L::kVBase : 0) + ld_par * L::kMatBytes + ld_x0 * 1024;
+    uint32_t none32[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) none32[qb] = 0u;
 
-    // ---- LDS read offsets of this lane (the even/odd tile choice of the wave folded in)
-    int k_off[KK];                               // K fragment of k-step kk, key row n (+32*ka rows)
+    // ---- LDS read addresses of this lane (the LDS base and the even/odd tile choice of the wave folded in)
+    int k_off[KK];                               // K fragment of k-step kk, key row n of a half tile
     {
         const int h = g ^ L::swz_k(n);           // (2*kk + g) ^ swz == (2*kk) ^ (g ^ swz)
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) k_off[kk] = wk * L::kMatBytes + n * L::kRowBytes + (((2 * kk) ^ h) << 4);
+        for (int kk = 0; kk < KK; ++kk) k_off[kk] = (int)lds0 + wk * L::kMatBytes + n * L::kRowBytes + (((2 * kk) ^ h) << 4);
     }
     // V^T fragments come from the LDS transpose read (ds_read_b64_tr_b16).  Measured lane
     // layout of that instruction, per group of 16 lanes: lane i supplies the address of four
@@ -241,18 +272,21 @@ __global__ __launch_bounds__(512) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs
     int v_off[DB];                               // byte offset of the lane's 8-byte piece for block db
     {
         const int sl = lane & 15, grp = (lane >> 4) & 1;
-        const int row = (sl >> 2) + 4 * g;       // + 8*(2*ts + half) + 32*ka rows added at the read
+        const int row = (sl >> 2) + 4 * g;       // + 8*(2*ts + half) rows (+32 for an upper half) added at the read
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
             const int chunk = 4 * db + 2 * grp + ((sl & 3) >> 1);
-            v_off[db] = L::kVBase + wk * L::kMatBytes + row * L::kRowBytes + ((chunk ^ L::swz_v(row)) << 4) + 8 * (sl & 1);
+            v_off[db] = (int)lds0 + L::kVBase + wk * L::kMatBytes + row * L::kRowBytes + ((chunk ^ L::swz_v(row)) << 4) + 8 * (sl & 1);
         }
     }
 
-    // Visibility words of a tile's 64 keys for the lane's query: all ones inside the prefix,
+    // Visibility words of a tile's 64 keys for the lane's queries: all ones inside the prefix,
     // the low bits for a ragged last prefix tile, the ancestor-mask word for a tree tile,
     // zero for a tile that does not exist.
-    auto fetch_vis = [=](int t) -> uint64_t { return (t >= nTp && t < nT) ? mrow[t - nTp] : ~0ull; };
+    auto fetch_vis = [=](int t, uint64_t (&v)[QB]) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) v[qb] = (t >= nTp && t < nT) ? mrow[qb][t - nTp] : ~0ull;
+    };
     auto fix_vis = [=](int t, uint64_t v) -> uint64_t {
         if (t >= nT) return 0ull;
         if (t < nTp && (t + 1) * kKeysPerTile > P) return (1ull << (P - t * kKeysPerTile)) - 1ull;
@@ -267,44 +301,53 @@ __global__ __launch_bounds__(512) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs
     //      half of tile i for e = 1; the next half is the upper half of tile i for e = 0 and
     //      the lower half of tile i+1 (slot SP^1) for e = 1.
     const floatx16 zero16 = { 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0 };
-    float ls_half = 0.0f;                        // the lane's sum of numerators of the half just done
-    auto half_step = [&](auto hp_c, auto hq_c, auto hs_c, auto mk_c, auto sp_c, auto e_c, uint32_t vis32) {
+    const bf16x2 kOnes2 = { (__bf16)1.0f, (__bf16)1.0f };
+    float ls_half[QB];                           // the lane's sums of numerators of the half just done
+    //      LD: this wave's LPW direct loads of a whole tile (ld_base: its first row for this wave,
+    //      ld_dst: LDS byte) are issued one per two slots, so that they drain while the matrix
+    //      pipe works instead of queueing up behind the barrier.
+    auto half_step = [&](auto hp_c, auto hq_c, auto hs_c, auto mk_c, auto ld_c, auto sp_c, auto e_c,
+                         const uint32_t (&vis32)[QB], const char* ld_base, uint32_t ld_dst) __attribute__((always_inline)) {
+        constexpr bool LD = decltype(ld_c)::value;
         constexpr bool HP = decltype(hp_c)::value, HQ = decltype(hq_c)::value;
         constexpr bool HS = decltype(hs_c)::value, MK = decltype(mk_c)::value;
         constexpr int SP = decltype(sp_c)::value, E = decltype(e_c)::value, O = E ^ 1;
-        constexpr int NP2 = 2 * DB, NQ2 = KK;                      // MFMAs per half: second, first product
+        constexpr int NP2 = 2 * DB, NQ2 = KK;                      // fragments per half: second, first product
         static_assert(NP2 == NQ2, "the interleave below alternates the two products");
-        constexpr int NS = (HP ? NP2 : 0) + (HQ ? NQ2 : 0);       // MFMA slots of this half step
+        constexpr int NS = (HP ? NP2 : 0) + (HQ ? NQ2 : 0);       // fragment slots (QB MFMAs each) of this half step
         constexpr int kVsrc = (E == 0 ? (SP ^ 1) : SP) * L::kSlotBytes + 32 * O * L::kRowBytes;
         constexpr int kKsrc = (E == 0 ? SP : (SP ^ 1)) * L::kSlotBytes + 32 * O * L::kRowBytes;
-        const float mc = m_run * c2;
-        float ls = 0.0f;
-        float pt[8][2];
+        float mc[QB], ls[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) { mc[qb] = m_run[qb] * c2; ls[qb] = 0.0f; }
+        float pt[8 * QB][2];
         // Register i of a 32x32 score block holds key row 8*(i/4) + 4*g + i%4, query column n.
-        // Item h of the vector work: pair p = h/2 covers scores 2p, 2p+1; even items take the
-        // exponentials, odd items mask, sum and pack them.
-        auto valu_item = [&](auto hc) {
-            constexpr int h = decltype(hc)::value, p = h / 2, i = 2 * p;
+        // Item h of the vector work: pair p = (h/2) % 8 of query block h/16 covers scores 2p,
+        // 2p+1; even items take the exponentials, odd items mask, sum and pack them.
+        auto valu_item = [&](auto hc) __attribute__((always_inline)) {
+            constexpr int h = decltype(hc)::value, qb = h / 16, p = (h / 2) % 8, i = 2 * p;
             if constexpr (h % 2 == 0) {
-                pt[p][0] = fast_exp2(fmaf(S[E][i], c2, -mc));
-                pt[p][1] = fast_exp2(fmaf(S[E][i + 1], c2, -mc));
+                pt[8 * qb + p][0] = fast_exp2(fmaf(S[E][qb][i], c2, -mc[qb]));
+                pt[8 * qb + p][1] = fast_exp2(fmaf(S[E][qb][i + 1], c2, -mc[qb]));
             } else {
-                float p0 = pt[p][0], p1 = pt[p][1];
+                float p0 = pt[8 * qb + p][0], p1 = pt[8 * qb + p][1];
                 if constexpr (MK) {
-                    p0 = and_bits(p0, __builtin_amdgcn_sbfe((int)vis32, 8 * (i / 4) + (i % 4), 1));
-                    p1 = and_bits(p1, __builtin_amdgcn_sbfe((int)vis32, 8 * (i / 4) + (i % 4) + 1, 1));
+                    p0 = and_bits(p0, __builtin_amdgcn_sbfe((int)vis32[qb], 8 * (i / 4) + (i % 4), 1));
+                    p1 = and_bits(p1, __builtin_amdgcn_sbfe((int)vis32[qb], 8 * (i / 4) + (i % 4) + 1, 1));
                 }
-                ls += p0 + p1;
                 floatx2 pp = { p0, p1 };
-                uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
+                const bf16x2 pc = __builtin_convertvector(pp, bf16x2);
+                // the sum takes the rounded numerators, the ones the second product multiplies
+                ls[qb] = __builtin_amdgcn_fdot2_f32_bf16(pc, kOnes2, ls[qb], false);
+                uint32_t w = __builtin_bit_cast(uint32_t, pc);
                 asm volatile("" : "+v"(w));                    // keep the conversion in this scheduling group
-                pbw[E][p / 4][p % 4] = w;
+                pbw[E][qb][p / 4][p % 4] = w;
             }
         };
         if constexpr (NS > 0) {
             // with both products, even slots belong to the second product and odd slots to the first
             bf16x8 fr[NS];
-            auto read_slot = [&](auto sc) {
+            auto read_slot = [&](auto sc) __attribute__((always_inline)) {
                 constexpr int s = decltype(sc)::value;
                 constexpr bool isP = HP && (!HQ || s % 2 == 0);
                 constexpr int idx = (HP && HQ) ? s / 2 : s;
@@ -315,85 +358,104 @@ __global__ __launch_bounds__(512) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs
 #pragma unroll
                     for (int half = 0; half < 2; ++half)
                         f.h[half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (lds_short4)(lds + kVsrc + 8 * (2 * ts + half) * L::kRowBytes + v_off[db]));
+                            (lds_short4)(uint32_t)(kVsrc + 8 * (2 * ts + half) * L::kRowBytes + v_off[db]));
                     fr[s] = f.v;
                 } else {
-                    fr[s] = *reinterpret_cast<const bf16x8*>(lds + kKsrc + k_off[idx]);
+                    fr[s] = *(lds_bf16x8)(uint32_t)(kKsrc + k_off[idx]);
                 }
             };
-            auto mfma_slot = [&](auto sc) {
+            auto mfma_slot = [&](auto sc) __attribute__((always_inline)) {
                 constexpr int s = decltype(sc)::value;
                 constexpr bool isP = HP && (!HQ || s % 2 == 0);
                 constexpr int idx = (HP && HQ) ? s / 2 : s;
-                if constexpr (isP) {
-                    constexpr int ts = idx / DB, db = idx % DB;
-                    union { uint32_t w[4]; bf16x8 v; } b;
 #pragma unroll
-                    for (int w = 0; w < 4; ++w) b.w[w] = pbw[O][ts][w];
-                    acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[s], b.v, acc[db], 0, 0, 0);
-                } else {
-                    if constexpr (idx == 0)
-                        S[O] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[s], qf[idx], zero16, 0, 0, 0);
-                    else
-                        S[O] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[s], qf[idx], S[O], 0, 0, 0);
+                for (int qb = 0; qb < QB; ++qb) {
+                    if constexpr (isP) {
+                        constexpr int ts = idx / DB, db = idx % DB;
+                        union { uint32_t w[4]; bf16x8 v; } b;
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) b.w[w] = pbw[O][qb][ts][w];
+                        acc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[s], b.v, acc[db][qb], 0, 0, 0);
+                    } else {
+                        if constexpr (idx == 0)
+                            S[O][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[s], qf[qb][idx], zero16, 0, 0, 0);
+                        else
+                            S[O][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[s], qf[qb][idx], S[O][qb], 0, 0, 0);
+                    }
                 }
             };
-            constexpr int IPS = 16 / NS;                       // items of vector work per slot
+            constexpr int IPS = 16 * QB / NS;                  // items of vector work per slot
+            static_assert(!LD || 2 * LPW <= NS, "one direct load per two slots");
             static_for<(kLead < NS ? kLead : NS)>([&](auto sc) { read_slot(sc); });
             static_for<NS>([&](auto sc) {
                 constexpr int s = decltype(sc)::value;
                 if constexpr (s + kLead < NS) read_slot(std::integral_constant<int, s + kLead>{});
                 mfma_slot(sc);
+                if constexpr (LD && s % 2 == 0 && s / 2 < LPW)
+                    direct_load_16(ld_base + (size_t)(L::kRowsPerLoad * (s / 2)) * kv_row_bytes, (uint32_t)ld_voff[(s / 2) & 3],
+                                   ld_dst + (s / 2) * 1024);
                 if constexpr (HS)
                     static_for<IPS>([&](auto hc) { valu_item(std::integral_constant<int, s * IPS + decltype(hc)::value>{}); });
                 __builtin_amdgcn_sched_barrier(0);
             });
         } else if constexpr (HS) {
-            static_for<16>(valu_item);
+            static_for<16 * QB>(valu_item);
         }
-        if constexpr (HS) ls_half = ls;
+        if constexpr (HS) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) ls_half[qb] = ls[qb];
+        }
     };
     // Rare: some score of half e tops the reference maximum by too much (always so for the
     // first half a wave sees).  Raise the reference to the true maximum, rescale what has been
     // accumulated (the second product of the previous half is complete here), and redo this
     // half's numerators.
-    auto redo_half = [&](auto e_c, bool mk, uint32_t vis32) {
+    auto redo_half = [&](auto e_c, bool mk, const uint32_t (&vis32)[QB]) __attribute__((always_inline)) {
         constexpr int E = decltype(e_c)::value;
-        float sm[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-            sm[i] = (mk && !((vis32 >> (8 * (i / 4) + (i % 4))) & 1u)) ? -INFINITY : S[E][i];
-        float mx = -INFINITY;
+        for (int qb = 0; qb < QB; ++qb) {
+            float sm[16];
 #pragma unroll
-        for (int i = 0; i < 16; i += 2) mx = max3(mx, sm[i], sm[i + 1]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = fast_exp2((m_run - m_new) * c2);
-        m_run = m_new;
-        l_run *= alpha;
-        if (__any(alpha != 0.0f && alpha != 1.0f)) {           // alpha 0: accumulators still 0
+            for (int i = 0; i < 16; ++i)
+                sm[i] = (mk && !((vis32[qb] >> (8 * (i / 4) + (i % 4))) & 1u)) ? -INFINITY : S[E][qb][i];
+            float mx = -INFINITY;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+            for (int i = 0; i < 16; i += 2) mx = max3(mx, sm[i], sm[i + 1]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            const float m_new = fmaxf(m_run[qb], mx);
+            const float alpha = fast_exp2((m_run[qb] - m_new) * c2);
+            m_run[qb] = m_new;
+            l_run[qb] *= alpha;
+            if (__any(alpha != 0.0f && alpha != 1.0f)) {       // alpha 0: accumulators still 0
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[db][i] *= alpha;
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[db][qb][i] *= alpha;
+            }
+            const float mc2 = m_run[qb] * c2;
+            float ls = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float p0 = fast_exp2(fmaf(sm[i], c2, -mc2));
+                const float p1 = fast_exp2(fmaf(sm[i + 1], c2, -mc2));
+                floatx2 pp = { p0, p1 };
+                const bf16x2 pc = __builtin_convertvector(pp, bf16x2);
+                ls = __builtin_amdgcn_fdot2_f32_bf16(pc, kOnes2, ls, false);
+                pbw[E][qb][i / 8][(i / 2) % 4] = __builtin_bit_cast(uint32_t, pc);
+            }
+            ls_half[qb] = ls;
         }
-        const float mc2 = m_run * c2;
-        float ls = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-            const float p0 = fast_exp2(fmaf(sm[i], c2, -mc2));
-            const float p1 = fast_exp2(fmaf(sm[i + 1], c2, -mc2));
-            ls += p0 + p1;
-            floatx2 pp = { p0, p1 };
-            pbw[E][i / 8][(i / 2) % 4] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
-        }
-        ls_half = ls;
     };
     // A half step of the steady state: all three parts, then the (rare) raise of the reference.
-    auto run_half = [&](auto mk_c, auto sp_c, auto e_c, uint32_t vis32) {
-        half_step(std::true_type{}, std::true_type{}, std::true_type{}, mk_c, sp_c, e_c, vis32);
-        if (__any(!(ls_half <= kSumLimit))) redo_half(e_c, decltype(mk_c)::value, vis32);
-        l_run += ls_half;
+    auto run_half = [&](auto mk_c, auto ld_c, auto sp_c, auto e_c, const uint32_t (&vis32)[QB], const char* ld_base,
+                        uint32_t ld_dst) __attribute__((always_inline)) {
+        half_step(std::true_type{}, std::true_type{}, std::true_type{}, mk_c, ld_c, sp_c, e_c, vis32, ld_base, ld_dst);
+        bool high = false;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) high |= !(ls_half[qb] <= kSumLimit);
+        if (__any(high)) redo_half(e_c, decltype(mk_c)::value, vis32);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) l_run[qb] += ls_half[qb];
     };
 
     // ---- prologue.  The steady-state half step always runs all three parts; what it reads for
@@ -402,104 +464,174 @@ __global__ __launch_bounds__(512) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs
     //      that does not exist is whatever the slot held, and the scores it gives are masked.
     {
         const uint4 z = { 0u, 0u, 0u, 0u };
-        for (int x = tid; x < 2 * L::kSlotBytes / 16; x += 512) reinterpret_cast<uint4*>(lds + L::kVBase)[x] = z;
+        for (int x = tid; x < 2 * L::kSlotBytes / 16; x += 64 * NW) reinterpret_cast<uint4*>(lds + L::kVBase)[x] = z;
 #pragma unroll
         for (int bu = 0; bu < 2; ++bu)
 #pragma unroll
-            for (int ts = 0; ts < 2; ++ts)
+            for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-                for (int w = 0; w < 4; ++w) pbw[bu][ts][w] = 0u;
+                for (int ts = 0; ts < 2; ++ts)
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) pbw[bu][qb][ts][w] = 0u;
     }
     __syncthreads();
-    {
+    if constexpr (NW == 8) {
         // K of the wave pair's first two tiles (tile mm = 2*slot + parity), V of the first
         int voff_k[4];
         lane_offsets(false, voff_k);
         issue_tile(kp, kt, voff_k, ld_mm, lds0 + ld_mm * L::kMatBytes + ld_x0 * 1024);
+    } else {
+        // one matrix per wave: K tiles 0..3 go to waves 0..3, then the V waves add V of tiles 0, 1
+        int voff_k[4];
+        lane_offsets(false, voff_k);
+        issue_tile(kp, kt, voff_k, wave, lds0 + wave * L::kMatBytes);
     }
-    int ld_voff[4];
-    lane_offsets(ld_is_v, ld_voff);
-    const char* const st_prefix = ld_is_v ? vp : kp;
-    const char* const st_tree = ld_is_v ? vt : kt;
-    const uint32_t st_dst = lds0 + (ld_is_v ? L::kVBase : 0) + ld_par * L::kMatBytes + ld_x0 * 1024;
     if (ld_is_v) issue_tile(st_prefix, st_tree, ld_voff, ld_par, st_dst);
     wait_direct_loads();
     __syncthreads();
     // first product of the lower half of tile 0 (K slot 0) into S[0]
-    half_step(std::false_type{}, std::true_type{}, std::false_type{}, std::false_type{},
-              std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, 0u);
+    half_step(std::false_type{}, std::true_type{}, std::false_type{}, std::false_type{}, std::false_type{},
+              std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, none32, nullptr, 0u);
 
     // ---- step i: lower half of tile i; barrier; loads of K(i+2) and V(i+1) into the slots
     //      the lower half was the last to read; upper half of tile i
-    auto issue_step_loads = [=](int i) {
+    auto issue_step_loads = [=](int i) __attribute__((always_inline)) {
         issue_tile(st_prefix, st_tree, ld_voff, ld_is_v ? 2 * (i + 1) + ld_par : 2 * (i + 2) + ld_par,
                    st_dst + ((ld_is_v ? i + 1 : i) & 1) * L::kSlotBytes);
     };
-    // Steps whose tiles are whole prefix tiles for both waves of a row block need no mask.
-    const int nPlain = (P / kKeysPerTile) / 2;             // tiles 2i and 2i+1 both below P / 64
+    STAMP(1);
+    // Plain steps: tiles 2i and 2i+1 are whole prefix tiles (no mask) and so are the tiles the
+    // step loads (a uniform base per load, spread over the upper half step).
+    const int nPlain = (P / kKeysPerTile) / 2 - 2;
     int i = 0;
     for (; i + 1 < nPlain; i += 2) {
         static_for<2>([&](auto sp_c) {
-            run_half(std::false_type{}, sp_c, std::integral_constant<int, 0>{}, 0u);
+            const int ii = i + decltype(sp_c)::value;
+            run_half(std::false_type{}, std::false_type{}, sp_c, std::integral_constant<int, 0>{}, none32, nullptr, 0u);
+#ifndef DBG_NOWAIT
             wait_direct_loads();
+#endif
+#ifndef DBG_NOBAR
             __syncthreads();
-            issue_step_loads(i + decltype(sp_c)::value);
-            run_half(std::false_type{}, sp_c, std::integral_constant<int, 1>{}, 0u);
+#endif
+            const int tl = ld_is_v ? 2 * (ii + 1) + ld_par : 2 * (ii + 2) + ld_par;
+            const char* base = st_prefix + (size_t)(tl * kKeysPerTile + L::kRowsPerLoad * ld_x0) * kv_row_bytes;
+#ifdef DBG_NOLOAD
+            run_half(std::false_type{}, std::false_type{}, sp_c, std::integral_constant<int, 1>{}, none32, base,
+#else
+            run_half(std::false_type{}, std::true_type{}, sp_c, std::integral_constant<int, 1>{}, none32, base,
+#endif
+                     st_dst + ((ld_is_v ? ii + 1 : ii) & 1) * L::kSlotBytes);
         });
     }
+    STAMP(2);
     // The rest: ragged prefix tile, tree tiles (ancestor mask), tiles that do not exist (all
-    // masked), until the second product of the last real half has run.
-    uint64_t visC = fix_vis(2 * i + wk, fetch_vis(2 * i + wk));
-    uint64_t visN = fix_vis(2 * i + 2 + wk, fetch_vis(2 * i + 2 + wk));
+    // masked), until the second product of the last real half has run.  A half step does
+    // something only if this wave's queries see a key of the half itself or of a neighbour
+    // (whose second or first product it carries); otherwise it just clears its numerators.
+    uint64_t visC[QB], visN[QB];
+    fetch_vis(2 * i + wk, visC);
+    fetch_vis(2 * i + 2 + wk, visN);
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        visC[qb] = fix_vis(2 * i + wk, visC[qb]);
+        visN[qb] = fix_vis(2 * i + 2 + wk, visN[qb]);
+    }
+    auto any_half = [&](const uint64_t (&v)[QB], int hi) __attribute__((always_inline)) -> bool {
+        uint32_t x = 0u;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) x |= (uint32_t)(v[qb] >> (32 * hi));
+        return __any(x != 0u);
+    };
+    auto masked_half = [&](auto sp_c, auto e_c, bool act, const uint32_t (&v32)[QB]) __attribute__((always_inline)) {
+        if (act) {
+            run_half(std::true_type{}, std::false_type{}, sp_c, e_c, v32, nullptr, 0u);
+        } else {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int ts = 0; ts < 2; ++ts)
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) pbw[decltype(e_c)::value][qb][ts][w] = 0u;
+        }
+    };
+    bool aP1 = true;                                         // the upper half of the last plain tile
     for (; i <= nIt; i += 2) {
         static_for<2>([&](auto sp_c) {
-            const int t2 = 2 * (i + decltype(sp_c)::value) + wk + 4;
-            uint64_t visL = fetch_vis(t2);
-            run_half(std::true_type{}, sp_c, std::integral_constant<int, 0>{}, (uint32_t)visC >> (4 * g));
+            const int ii = i + decltype(sp_c)::value;
+            const int t2 = 2 * ii + wk + 4;
+            uint64_t visL[QB];
+            fetch_vis(t2, visL);
+            const bool aC0 = any_half(visC, 0), aC1 = any_half(visC, 1), aN0 = any_half(visN, 0);
+            uint32_t v32[QB];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) v32[qb] = (uint32_t)visC[qb] >> (4 * g);
+            masked_half(sp_c, std::integral_constant<int, 0>{}, aP1 || aC0 || aC1, v32);
             wait_direct_loads();
             __syncthreads();
-            asm volatile("" : "+v"(visL));
-            issue_step_loads(i + decltype(sp_c)::value);
-            run_half(std::true_type{}, sp_c, std::integral_constant<int, 1>{}, (uint32_t)(visC >> 32) >> (4 * g));
-            visC = visN;
-            visN = fix_vis(t2, visL);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) asm volatile("" : "+v"(visL[qb]));
+            issue_step_loads(ii);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) v32[qb] = (uint32_t)(visC[qb] >> 32) >> (4 * g);
+            masked_half(sp_c, std::integral_constant<int, 1>{}, aC0 || aC1 || aN0, v32);
+            aP1 = aC1;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                visC[qb] = visN[qb];
+                visN[qb] = fix_vis(t2, visL[qb]);
+            }
         });
     }
+    STAMP(3);
     __syncthreads();                                         // every LDS read is done before the merge reuses it
 
     // ---- merge the two key halves of each row block through LDS, normalise, store
-    l_run += __shfl_xor(l_run, 32, kWave);
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) l_run[qb] += __shfl_xor(l_run[qb], 32, kWave);
     float* xs = reinterpret_cast<float*>(lds);               // [wq][register][lane]
-    constexpr int NR = DB * 16 + 2;
+    constexpr int NR = DB * QB * 16 + 2 * QB;
     if (wk == 1) {
         float* dst = xs + (size_t)wq * NR * kWave + lane;
         int r = 0;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) dst[(r++) * kWave] = acc[db][i];
-        dst[(r++) * kWave] = m_run;
-        dst[(r++) * kWave] = l_run;
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int i2 = 0; i2 < 16; ++i2) dst[(r++) * kWave] = acc[db][qb][i2];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) dst[(r++) * kWave] = m_run[qb];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) dst[(r++) * kWave] = l_run[qb];
     }
     __syncthreads();
     if (wk == 0) {
         const float* src = xs + (size_t)wq * NR * kWave + lane;
-        const float m1 = src[(NR - 2) * kWave], l1 = src[(NR - 1) * kWave];
-        const float m = fmaxf(m_run, m1);
-        const float f0 = exp2f((m_run - m) * c2);
-        const float f1 = exp2f((m1 - m) * c2);
-        const float inv = 1.0f / (l_run * f0 + l1 * f1);
+        float f0[QB], f1[QB], inv[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float m1 = src[(NR - 2 * QB + qb) * kWave], l1 = src[(NR - QB + qb) * kWave];
+            const float m = fmaxf(m_run[qb], m1);
+            f0[qb] = exp2f((m_run[qb] - m) * c2);
+            f1[qb] = exp2f((m1 - m) * c2);
+            inv[qb] = 1.0f / (l_run[qb] * f0[qb] + l1 * f1[qb]);
+        }
         int r = 0;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float o1 = src[(r++) * kWave];
-                acc[db][i] = (acc[db][i] * f0 + o1 * f1) * inv;
-            }
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int i2 = 0; i2 < 16; ++i2) {
+                    const float o1 = src[(r++) * kWave];
+                    acc[db][qb][i2] = (acc[db][qb][i2] * f0[qb] + o1 * f1[qb]) * inv[qb];
+                }
         // register i of block db is head-dim index 32*db + 8*(i/4) + 4*g + i%4
-        if (rq < rows) {
-            const int j = rq / G, h = kvh * G + rq % G;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            if (rq[qb] >= rows) continue;
+            const int j = rq[qb] / G, h = kvh * G + rq[qb] % G;
             __bf16* orow = static_cast<__bf16*>(a.out) + ((size_t)(node_base + j) * a.Hq + h) * D;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -508,22 +640,27 @@ __global__ __launch_bounds__(512) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs
                     union { bf16x2 p[2]; uint2 v; } o;
 #pragma unroll
                     for (int ii = 0; ii < 2; ++ii) {
-                        floatx2 pr = { acc[db][4 * ib + 2 * ii], acc[db][4 * ib + 2 * ii + 1] };
+                        floatx2 pr = { acc[db][qb][4 * ib + 2 * ii], acc[db][qb][4 * ib + 2 * ii + 1] };
                         o.p[ii] = __builtin_convertvector(pr, bf16x2);
                     }
                     *reinterpret_cast<uint2*>(orow + 32 * db + 8 * ib + 4 * g) = o.v;
                 }
         }
     }
+    STAMP(4);
 }
 
-template <int D>
+#ifdef DBG_STAMPS
+extern "C" int dyspec_dbg_read(void* dst, size_t n) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(dbg_stamps), n); }
+#endif
+
+template <int D, int QB>
 static hipError_t launch_one(const AttnArgs& a, const SeqArgs& sa, int tiles, hipStream_t stream)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<D>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<D, QB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Geo<D>::kLdsBytes);
     if (e != hipSuccess) return e;
-    tree_attn_mfma_kernel<D><<<tiles * a.Hkv, 512, Geo<D>::kLdsBytes, stream>>>(a, sa);
+    tree_attn_mfma_kernel<D, QB><<<tiles * a.Hkv, 64 * 2 * (4 / QB), Geo<D>::kLdsBytes, stream>>>(a, sa);
     return hipGetLastError();
 }
 
@@ -537,7 +674,7 @@ hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, hipStream_t stre
     }
     a.tile_off[sa.n_seq] = tiles;
     if (tiles == 0) return hipSuccess;
-    return a.d == 128 ? launch_one<128>(a, sa, tiles, stream) : launch_one<64>(a, sa, tiles, stream);
+    return a.d == 128 ? launch_one<128, kQB>(a, sa, tiles, stream) : launch_one<64, kQB>(a, sa, tiles, stream);
 }
 
 }  // namespace dyspec
