@@ -4,33 +4,37 @@
 // Row folding.  All G = Hq/Hkv query heads that share a KV head are folded into the row
 // dimension (row = node*G + head), so a workgroup tile of 128 rows streams the prefix K/V
 // of its KV head once and every K/V byte feeds 128 rows of MFMA work; the tree part reuses
-// the same machinery with the ancestor bitmask applied to the probabilities, and 64-key
-// tree tiles that no row of the wave can see are skipped (the paper's kernel skips empty
-// 32x32 blocks of the mask).
+// the same machinery with the ancestor bitmask applied to the numerators.  Tree tiles (64
+// keys) in which no query of the workgroup sees a key are left out of the walk altogether,
+// and a wave does nothing for a 32-key half none of its own queries can see (the paper's
+// kernel skips empty 32x32 blocks of the mask).
 //
 // Workgroup = 8 waves, two per SIMD.  Wave w owns the 32-row block (w & 3) and every second
 // 64-key tile ((w >> 2) picks even or odd tiles); the two waves of a row block merge their
-// (max, sum, accumulator) through LDS at the end.  Per tile a wave computes S^T = K Q^T
-// (keys x queries: each lane then holds one query column, and exp(S^T) is already in the
-// register layout the second product wants as its B operand), the softmax numerators, and
-// O^T += V^T P^T.
+// (max, sum, accumulator) through LDS at the end.  Per 32-key half tile a wave computes
+// S^T = K Q^T (keys x queries: each lane then holds one query column, and exp(S^T) is
+// already in the register layout the second product wants as its B operand), the softmax
+// numerators, and O^T += V^T P^T.
 //
 // Software pipeline.  The vector work of the softmax and the matrix work run in different
 // pipes of a SIMD, but only instructions that are adjacent in one wave's stream overlap
-// reliably, so the loop is skewed: step i runs the exponentials of tile i while the matrix
-// pipe does the second product of tile i-1 and the first product of tile i+1, one MFMA,
-// its LDS reads a few slots ahead, and a few vector instructions per scheduling group.
+// reliably, so the loop is skewed by half tiles: a half step runs the exponentials of half
+// h while the matrix pipe does the second product of half h-1 and the first product of half
+// h+1; one scheduling group holds one MFMA, the LDS reads of an MFMA a few slots ahead, and
+// a few vector instructions.
 //
 // Lazy maximum.  Numerators are computed against the running reference maximum without
-// looking at the tile's own maximum first; only when a lane's tile sum leaves the safe range
-// (it is then recomputed, rarely) is the reference raised and the accumulators rescaled.
+// looking at the half's own maximum first; only when a lane's sum over the half leaves the
+// safe range (the half is then recomputed, rarely) is the reference raised and the
+// accumulators rescaled.
 //
 // Staging.  K/V tiles go from HBM/L2 to LDS with direct loads (global_load_lds_dwordx4: lane
 // i of a wave writes LDS bytes [16*i, 16*i+16) past a wave-uniform base), two slots per
-// matrix, without passing through registers; step i loads K of tile i+2 and V of tile i
-// while it consumes K of tile i+1 and V of tile i-1.  Rows sit unpadded in LDS; 16-byte
-// chunks of a row are XOR-swizzled so that the 16-byte K reads and the transposing V reads
-// of a wave spread over all 64 banks.
+// matrix, without passing through registers; in the middle of step i (after the only
+// barrier of the step) the loads of K of tile i+2 and V of tile i+1 start, spread over the
+// following half step so that they drain while the matrix pipe works.  Rows sit unpadded in
+// LDS; 16-byte chunks of a row are XOR-swizzled so that the 16-byte K reads and the
+// transposing V reads of a wave spread over all 64 banks.
 #include <utility>
 
 #include "dyspec_device.h"
@@ -103,13 +107,6 @@ __device__ __forceinline__ float max3(float a, float b, float c)
     return r;
 }
 
-#ifdef DBG_STAMPS
-__device__ unsigned long long dbg_stamps[4096 * 8];
-#define STAMP(k) do { if (lane == 0) dbg_stamps[(blockIdx.x * 8 + wave) * 8 + (k)] = wall_clock64(); } while (0)
-#else
-#define STAMP(k) do { } while (0)
-#endif
-
 template <int D> struct Geo {
     static constexpr int kRowBytes = 2 * D;
     static constexpr int kChunks = D / 8;                        // 16-byte chunks per row
@@ -142,7 +139,6 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     const int n = lane & 31, g = lane >> 5;
     const int wq = wave % NWQ, wk = wave / NWQ;
 
-    STAMP(0);
     // ---- which tile
     const int kvh = blockIdx.x % a.Hkv;
     const int tile = blockIdx.x / a.Hkv;
@@ -158,8 +154,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     const int nTp = (P + kKeysPerTile - 1) / kKeysPerTile;
     const int r_last = min(rows - 1, r0 + kRowsPerWG - 1);
     const int nTt = (r_last / G) / kKeysPerTile + 1;      // tree tiles up to the largest node of this row tile
-    const int nT = nTp + nTt;
-    const int nIt = (nT + 1) / 2;                          // tiles per wave (the last odd one may not exist)
+    const int nT = nTp + nTt;                              // a tile index >= nT stands for "no tile"
 
     const size_t kv_row_bytes = (size_t)a.Hkv * D * 2;
     const char* kp = static_cast<const char*>(a.kp) + (size_t)sa.kv_off[seq] * kv_row_bytes + (size_t)kvh * D * 2;
@@ -462,9 +457,11 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     //      a half that does not exist must therefore be harmless.  V slots start as zeros and
     //      the numerators start as zeros (0 * 0 adds nothing to the accumulators); K of a tile
     //      that does not exist is whatever the slot held, and the scores it gives are masked.
+    uint32_t* const tile_flag = reinterpret_cast<uint32_t*>(lds + L::kLdsBytes);
     {
         const uint4 z = { 0u, 0u, 0u, 0u };
         for (int x = tid; x < 2 * L::kSlotBytes / 16; x += 64 * NW) reinterpret_cast<uint4*>(lds + L::kVBase)[x] = z;
+        if (tid == 0) *tile_flag = 0u;
 #pragma unroll
         for (int bu = 0; bu < 2; ++bu)
 #pragma unroll
@@ -487,8 +484,35 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         issue_tile(kp, kt, voff_k, wave, lds0 + wave * L::kMatBytes);
     }
     if (ld_is_v) issue_tile(st_prefix, st_tree, ld_voff, ld_par, st_dst);
+    // Tree tiles in which no query of the workgroup sees any key are left out altogether: the
+    // waves agree on the set (bit tt = tree tile tt) through LDS, and the loops below walk the
+    // prefix tiles followed by the tiles of the set.  (With fewer than four prefix tiles the
+    // loads above already reach into the tree, so then every tree tile stays in.)
+    const bool squeeze = nTp >= 4;
+    if (squeeze) {
+        uint32_t mine = 0u;
+        for (int tt = 0; tt < nTt; ++tt) {
+            uint64_t w = 0ull;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) w |= mrow[qb][tt];
+            if (__any(w != 0ull)) mine |= 1u << tt;
+        }
+        if (lane == 0) atomicOr(tile_flag, mine);
+    }
     wait_direct_loads();
     __syncthreads();
+    const uint32_t active = squeeze ? (uint32_t)__builtin_amdgcn_readfirstlane((int)*tile_flag) : (0xffffffffu >> (32 - nTt));
+    const int nAct = __builtin_popcount(active);
+    const int nIt = (nTp + nAct + 1) / 2;                  // tiles per wave (the last odd one may not exist)
+    // position v in the walk -> tile index (prefix tiles, then the tree tiles of the set)
+    auto tile_of = [=](int v) __attribute__((always_inline)) -> int {
+        if (v < nTp) return v;
+        const int k = v - nTp;
+        if (k >= nAct) return nT;
+        uint32_t m = active;
+        for (int j = 0; j < k; ++j) m &= m - 1u;
+        return nTp + __builtin_ctz(m);
+    };
     // first product of the lower half of tile 0 (K slot 0) into S[0]
     half_step(std::false_type{}, std::true_type{}, std::false_type{}, std::false_type{}, std::false_type{},
               std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, none32, nullptr, 0u);
@@ -496,10 +520,9 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     // ---- step i: lower half of tile i; barrier; loads of K(i+2) and V(i+1) into the slots
     //      the lower half was the last to read; upper half of tile i
     auto issue_step_loads = [=](int i) __attribute__((always_inline)) {
-        issue_tile(st_prefix, st_tree, ld_voff, ld_is_v ? 2 * (i + 1) + ld_par : 2 * (i + 2) + ld_par,
+        issue_tile(st_prefix, st_tree, ld_voff, tile_of(ld_is_v ? 2 * (i + 1) + ld_par : 2 * (i + 2) + ld_par),
                    st_dst + ((ld_is_v ? i + 1 : i) & 1) * L::kSlotBytes);
     };
-    STAMP(1);
     // Plain steps: tiles 2i and 2i+1 are whole prefix tiles (no mask) and so are the tiles the
     // step loads (a uniform base per load, spread over the upper half step).
     const int nPlain = (P / kKeysPerTile) / 2 - 2;
@@ -508,34 +531,28 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         static_for<2>([&](auto sp_c) {
             const int ii = i + decltype(sp_c)::value;
             run_half(std::false_type{}, std::false_type{}, sp_c, std::integral_constant<int, 0>{}, none32, nullptr, 0u);
-#ifndef DBG_NOWAIT
             wait_direct_loads();
-#endif
-#ifndef DBG_NOBAR
             __syncthreads();
-#endif
             const int tl = ld_is_v ? 2 * (ii + 1) + ld_par : 2 * (ii + 2) + ld_par;
             const char* base = st_prefix + (size_t)(tl * kKeysPerTile + L::kRowsPerLoad * ld_x0) * kv_row_bytes;
-#ifdef DBG_NOLOAD
-            run_half(std::false_type{}, std::false_type{}, sp_c, std::integral_constant<int, 1>{}, none32, base,
-#else
             run_half(std::false_type{}, std::true_type{}, sp_c, std::integral_constant<int, 1>{}, none32, base,
-#endif
                      st_dst + ((ld_is_v ? ii + 1 : ii) & 1) * L::kSlotBytes);
         });
     }
-    STAMP(2);
     // The rest: ragged prefix tile, tree tiles (ancestor mask), tiles that do not exist (all
     // masked), until the second product of the last real half has run.  A half step does
     // something only if this wave's queries see a key of the half itself or of a neighbour
     // (whose second or first product it carries); otherwise it just clears its numerators.
     uint64_t visC[QB], visN[QB];
-    fetch_vis(2 * i + wk, visC);
-    fetch_vis(2 * i + 2 + wk, visN);
+    {
+        const int tc = tile_of(2 * i + wk), tn = tile_of(2 * i + 2 + wk);
+        fetch_vis(tc, visC);
+        fetch_vis(tn, visN);
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        visC[qb] = fix_vis(2 * i + wk, visC[qb]);
-        visN[qb] = fix_vis(2 * i + 2 + wk, visN[qb]);
+        for (int qb = 0; qb < QB; ++qb) {
+            visC[qb] = fix_vis(tc, visC[qb]);
+            visN[qb] = fix_vis(tn, visN[qb]);
+        }
     }
     auto any_half = [&](const uint64_t (&v)[QB], int hi) __attribute__((always_inline)) -> bool {
         uint32_t x = 0u;
@@ -559,7 +576,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     for (; i <= nIt; i += 2) {
         static_for<2>([&](auto sp_c) {
             const int ii = i + decltype(sp_c)::value;
-            const int t2 = 2 * ii + wk + 4;
+            const int t2 = tile_of(2 * ii + wk + 4);
             uint64_t visL[QB];
             fetch_vis(t2, visL);
             const bool aC0 = any_half(visC, 0), aC1 = any_half(visC, 1), aN0 = any_half(visN, 0);
@@ -583,7 +600,6 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
             }
         });
     }
-    STAMP(3);
     __syncthreads();                                         // every LDS read is done before the merge reuses it
 
     // ---- merge the two key halves of each row block through LDS, normalise, store
@@ -647,20 +663,15 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                 }
         }
     }
-    STAMP(4);
 }
-
-#ifdef DBG_STAMPS
-extern "C" int dyspec_dbg_read(void* dst, size_t n) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(dbg_stamps), n); }
-#endif
 
 template <int D, int QB>
 static hipError_t launch_one(const AttnArgs& a, const SeqArgs& sa, int tiles, hipStream_t stream)
 {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<D, QB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Geo<D>::kLdsBytes);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Geo<D>::kLdsBytes + 16);
     if (e != hipSuccess) return e;
-    tree_attn_mfma_kernel<D, QB><<<tiles * a.Hkv, 64 * 2 * (4 / QB), Geo<D>::kLdsBytes, stream>>>(a, sa);
+    tree_attn_mfma_kernel<D, QB><<<tiles * a.Hkv, 64 * 2 * (4 / QB), Geo<D>::kLdsBytes + 16, stream>>>(a, sa);
     return hipGetLastError();
 }
 

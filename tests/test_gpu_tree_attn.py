@@ -21,36 +21,46 @@ def dy():
     return m
 
 
-def random_parents(n, rng, chain=False):
+def random_parents(n, rng, chain=False, shallow=False):
     if chain:
         return np.arange(-1, n - 1, dtype=np.int32)
     par = np.full(n, -1, np.int32)
+    if shallow:                                   # every node hangs below one of the first few
+        for i in range(1, n):
+            par[i] = int(rng.integers(0, min(i, 6)))
+        return par
     for i in range(1, n):
         par[i] = int(rng.integers(max(0, i - 12), i)) if rng.random() < 0.7 else int(rng.integers(0, i))
     return par
 
 
-def make_case(nodes, prefix, Hq, Hkv, d, dtype, seed, chain=False):
+def make_case(nodes, prefix, Hq, Hkv, d, dtype, seed, chain=False, shallow=False, qscale=1.0, ramp=0.0):
     rng = np.random.default_rng(seed)
     g = torch.Generator().manual_seed(seed)
     dt = torch.float32 if dtype == "f32" else torch.bfloat16
     tn, tp = sum(nodes), sum(prefix)
     mk = lambda *sh: torch.randn(sh, generator=g, dtype=torch.float32).to(dt)
     q, kp, vp, kt, vt = mk(tn, Hq, d), mk(tp, Hkv, d), mk(tp, Hkv, d), mk(tn, Hkv, d), mk(tn, Hkv, d)
+    if qscale != 1.0:
+        q = (q.float() * qscale).to(dt)
+    if ramp and tp:                               # later prefix keys score higher and higher
+        f = 1.0 + ramp * torch.arange(tp, dtype=torch.float32) / tp
+        kp = (kp.float() * f[:, None, None]).to(dt)
     words = (max(nodes) + 63) // 64
     mask = np.zeros((tn, words), np.uint64)
     off = 0
     for n in nodes:
-        m = oracle.ancestor_mask(random_parents(n, rng, chain))
+        m = oracle.ancestor_mask(random_parents(n, rng, chain, shallow))
         mask[off:off + n, :m.shape[1]] = m
         off += n
     return q, kp, vp, kt, vt, mask
 
 
-def run_and_compare(dy, nodes, prefix, Hq, Hkv, d, dtype, seed, chain=False, api_dtype=None, max_rows=4000):
+def run_and_compare(dy, nodes, prefix, Hq, Hkv, d, dtype, seed, chain=False, api_dtype=None, max_rows=4000,
+                    shallow=False, qscale=1.0, ramp=0.0):
     print(f"attn case nodes={nodes} prefix={prefix} H={Hq}/{Hkv} d={d} {dtype} seed={seed}", flush=True)
     batch = dy.Batch.from_sizes(nodes, prefix)
-    q, kp, vp, kt, vt, mask = make_case(nodes, prefix, Hq, Hkv, d, dtype, seed, chain)
+    q, kp, vp, kt, vt, mask = make_case(nodes, prefix, Hq, Hkv, d, dtype, seed, chain, shallow, qscale, ramp)
     scale = 1.0 / math.sqrt(d)
     dev = lambda t: t.cuda() if t.numel() else torch.empty(t.shape, dtype=t.dtype, device="cuda")
     mask_dev = torch.from_numpy(mask.view(np.int64)).cuda()
@@ -93,6 +103,22 @@ def test_tiny_fp32_config(dy):
 ])
 def test_bf16_matrix_core_kernel(dy, nodes, prefix, Hq, Hkv, d, seed):
     run_and_compare(dy, nodes, prefix, Hq, Hkv, d, "bf16", seed)
+
+
+def test_bf16_long_prefix_wide_tree(dy):
+    # nine whole prefix tiles and a ragged one, a tree of sixteen key tiles
+    run_and_compare(dy, (1024,), (64 * 9 + 5,), 8, 1, 128, "bf16", 12)
+
+
+def test_bf16_shallow_tree_leaves_tiles_out(dy):
+    # ancestors all sit in the first key tile: most tree tiles hold no visible key for a row tile
+    run_and_compare(dy, (1024, 300), (512, 700), 8, 2, 128, "bf16", 13, shallow=True)
+
+
+def test_bf16_rising_scores_raise_the_reference(dy):
+    # large scores that keep growing along the prefix: the running maximum is raised many times
+    run_and_compare(dy, (96,), (2048,), 8, 2, 128, "bf16", 14, qscale=3.0, ramp=3.0)
+    run_and_compare(dy, (200,), (640,), 4, 4, 64, "bf16", 15, qscale=4.0, ramp=2.0)
 
 
 def test_bf16_chain_tree_is_causal(dy):
