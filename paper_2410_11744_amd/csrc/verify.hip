@@ -1,9 +1,10 @@
 // Vocabulary softmax statistics of every tree row and multi-candidate tree rejection
 // sampling (Algorithm 3, Appendix A.3; one-candidate rule of Section 2) for gfx950.
 //
-// Two kernels.  softmax_stats_kernel is the data-parallel part: one workgroup per tree row
-// reads the row's draft and target logits from HBM once and reduces them to (max, sum-exp),
-// the normalisers every later probability needs.  verify_walk_kernel is Algorithm 3 itself,
+// Two kernels.  The statistics kernel is the data-parallel part: it reads every tree row's
+// draft and target logits from HBM once and reduces each to (max, sum-exp), the normalisers
+// every later probability needs (a streaming form for V % 4 == 0, a plain one workgroup per
+// row form otherwise).  verify_walk_kernel is Algorithm 3 itself,
 // one workgroup per sequence walking from the root: the first child of a node is tested
 // from two logits and the row statistics alone; only after a rejection are the node's two
 // rows brought into registers (normalised with the statistics, no reduction) for the residual
@@ -46,6 +47,72 @@ __global__ __launch_bounds__(kBlock) void softmax_stats_kernel(
     if (threadIdx.x == 0) {
         *reinterpret_cast<float4*>(row_stats + 4 * (size_t)row) = make_float4(mx[0], sm[0], mx[1], sm[1]);
         accept_ratio[row] = (row == sa.node_off[seq]) ? 0.0f : -2.0f;      // -2: not tested by the walk
+    }
+}
+
+// Streaming form of the statistics pass for V % 4 == 0: one workgroup of 256 threads per
+// (row, table), so a 512-row batch puts 1024 independent 128 KB streams on the chip.  Each
+// thread keeps a running (max, sum) pair over its 16-byte pieces, eight pieces in flight, and
+// raises its reference once per batch of 32 values (33 exponentials per 32 values); pairs are
+// merged with (m, s) + (m', s') = (M, s 2^{c(m-M)} + s' 2^{c(m'-M)}), M = max(m, m').  The
+// maximum is taken over the raw logits, so max * (1/T) is rounded exactly as the plain
+// two-pass form rounds it.
+constexpr int kStatThreads = 256;
+constexpr int kStatUnroll = 8;
+
+__device__ __forceinline__ void merge_stat(float& m, float& s, float m2, float s2, float c)
+{
+    const float M = fmaxf(m, m2);
+    if (M == -INFINITY) return;                                  // both empty
+    s = s * __builtin_amdgcn_exp2f((m - M) * c) + s2 * __builtin_amdgcn_exp2f((m2 - M) * c);
+    m = M;
+}
+
+__global__ __launch_bounds__(kStatThreads) void softmax_stats_stream_kernel(
+    const float* __restrict__ draft_logits, const float* __restrict__ target_logits, int V,
+    SeqArgs sa, float* __restrict__ row_stats, float* __restrict__ accept_ratio)
+{
+    __shared__ float red[2 * (kStatThreads / kWave)];
+    const int row = blockIdx.x, table = blockIdx.y;
+    const int seq = find_seq(sa, row);
+    const float inv_t = 1.0f / (table ? sa.temp_t[seq] : sa.temp_d[seq]);
+    const float c = inv_t * 1.4426950408889634f;
+    const float4* __restrict__ x = reinterpret_cast<const float4*>((table ? target_logits : draft_logits) + (size_t)row * V);
+    const int n4 = V / 4;
+    float m = -INFINITY, s = 0.0f;
+    for (int i0 = threadIdx.x; i0 < n4; i0 += kStatThreads * kStatUnroll) {
+        float4 v[kStatUnroll];
+#pragma unroll
+        for (int u = 0; u < kStatUnroll; ++u) {
+            const int i = i0 + u * kStatThreads;
+            v[u] = (i < n4) ? x[i] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        }
+        float cm = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < kStatUnroll; ++u) cm = fmaxf(fmaxf(cm, fmaxf(v[u].x, v[u].y)), fmaxf(v[u].z, v[u].w));
+        const float M = fmaxf(m, cm);
+        if (M == -INFINITY) continue;                            // nothing but -inf logits so far
+        float acc = s * __builtin_amdgcn_exp2f((m - M) * c);
+        const float Mc = M * c;
+#pragma unroll
+        for (int u = 0; u < kStatUnroll; ++u) {
+            acc += __builtin_amdgcn_exp2f(fmaf(v[u].x, c, -Mc)) + __builtin_amdgcn_exp2f(fmaf(v[u].y, c, -Mc));
+            acc += __builtin_amdgcn_exp2f(fmaf(v[u].z, c, -Mc)) + __builtin_amdgcn_exp2f(fmaf(v[u].w, c, -Mc));
+        }
+        s = acc;
+        m = M;
+    }
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) merge_stat(m, s, __shfl_xor(m, o, kWave), __shfl_xor(s, o, kWave), c);
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) { red[2 * wave] = m; red[2 * wave + 1] = s; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = red[0]; s = red[1];
+#pragma unroll
+        for (int w = 1; w < kStatThreads / kWave; ++w) merge_stat(m, s, red[2 * w], red[2 * w + 1], c);
+        *reinterpret_cast<float2*>(row_stats + 4 * (size_t)row + 2 * table) = make_float2(m * inv_t, s);
+        if (table == 0) accept_ratio[row] = (row == sa.node_off[seq]) ? 0.0f : -2.0f;   // -2: not tested by the walk
     }
 }
 
@@ -220,7 +287,7 @@ hipError_t launch_verify(const float* draft_logits, const float* target_logits, 
 {
     const int rows = sa.node_off[sa.n_seq];
     if (V % 4 == 0) {
-        softmax_stats_kernel<true><<<rows, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
+        softmax_stats_stream_kernel<<<dim3(rows, 2), kStatThreads, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
         verify_walk_kernel<true><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, tree, seed, emit_bonus,
                                                                   row_stats, accept_ratio, accepted_nodes, n_accepted,
                                                                   final_token, min_margin);
