@@ -1,18 +1,44 @@
 // Greedy fixed-budget token-tree construction (Algorithm 1, Section 4.2, Appendix A.1)
 // and the ancestor bitmask of tree attention (Section 2) for gfx950.
 //
-// One 1024-thread workgroup builds one sequence's tree without leaving the GPU.  The
+// One 512-thread workgroup builds one sequence's tree without leaving the GPU.  The
 // paper keeps the expandable slots in a heap on the host; here the frontier (at most two
 // new slots per node) lives in LDS and the pop is a workgroup arg-max, which costs less
 // than a heap's pointer chasing at these sizes.  Each expansion is one pass over the
-// parent's draft row held in registers: fp64 softmax weights, workgroup sum and scan for
-// the inverse-CDF draw.  fp64 keeps every discrete decision (which slot, which token) equal
+// parent's draft row held in registers: fp64 softmax weights summed four tokens at a time,
+// workgroup sum and scan of those sums for the inverse-CDF draw.  fp64 keeps every discrete decision (which slot, which token) equal
 // to an fp64 evaluation of the algorithm except at relative margins near 1e-13.
 #include "vocab_common.h"
 
 namespace dyspec {
 
 constexpr int kMaxSlots = 2 * DYSPEC_MAX_NODES + 2;
+
+// exp(z) for z <= 0 (a softmax weight relative to the row maximum) in fp64: z = n ln2 + r with
+// |r| <= ln2 / 2, exp(r) by its Taylor series to degree 13 (truncation below 1e-17), scaled by
+// 2^n.  Arguments below the normal range, -inf included, give 0.
+__device__ __attribute__((noinline)) double exp_nonpos(double z)
+{
+    if (!(z >= -708.0)) return 0.0;
+    const double n = rint(z * 1.4426950408889634074);
+    double r = fma(n, -6.93147180369123816490e-01, z);
+    r = fma(n, -1.90821492927058770002e-10, r);
+    double p = 1.0 / 6227020800.0;
+    p = fma(p, r, 1.0 / 479001600.0);
+    p = fma(p, r, 1.0 / 39916800.0);
+    p = fma(p, r, 1.0 / 3628800.0);
+    p = fma(p, r, 1.0 / 362880.0);
+    p = fma(p, r, 1.0 / 40320.0);
+    p = fma(p, r, 1.0 / 5040.0);
+    p = fma(p, r, 1.0 / 720.0);
+    p = fma(p, r, 1.0 / 120.0);
+    p = fma(p, r, 1.0 / 24.0);
+    p = fma(p, r, 1.0 / 6.0);
+    p = fma(p, r, 0.5);
+    p = fma(p, r, 1.0);
+    p = fma(p, r, 1.0);
+    return ldexp(p, (int)n);
+}
 
 struct BuildShared {
     double slot_value[kMaxSlots];       // < 0: closed
@@ -43,7 +69,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
     const int seq = blockIdx.x;
     const int base = sa.node_off[seq];
     const int N = sa.node_off[seq + 1] - base;
-    const double temp = (double)sa.temp_d[seq];
+    const double inv_temp = 1.0 / (double)sa.temp_d[seq];
 
     // ---- initial state: every row unbuilt, root slot open
     for (int i = tid; i < N; i += kBlock) {
@@ -93,7 +119,10 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
         const double v = sh.slot_value[pick];
         const int rank = sh.n_children[p];
 
-        // ---- residual draft distribution of p: softmax weights, earlier children removed
+        // ---- residual draft distribution of p: softmax weights with the earlier children's
+        //      tokens removed.  Only the 4-token segment sums stay in registers (the row of
+        //      fp64 weights itself would not fit); bit k of `gone` marks this thread's k-th
+        //      token as already drawn at this position.
         float x[kMaxSeg][4];
         load_row<VEC>(draft_logits + (size_t)(base + p) * V, V, x);
         float mx[1] = { -INFINITY };
@@ -102,28 +131,37 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
 #pragma unroll
             for (int e = 0; e < 4; ++e) mx[0] = fmaxf(mx[0], x[j][e]);
         block_max<1>(mx, sh.fred);
-        const double m = (double)mx[0] / temp;
-        double w[kMaxSeg][4];
-#pragma unroll
-        for (int j = 0; j < kMaxSeg; ++j)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                w[j][e] = (tok_index(j, e) < V) ? exp((double)x[j][e] / temp - m) : 0.0;
+        const double m = (double)mx[0] * inv_temp;
+        uint64_t gone = 0ull;
         for (int c = sh.first_child[p]; c >= 0; c = sh.next_sibling[c]) {
             const int y = sh.token[c];
-            if (((y % kSeg) >> 2) == tid) {
+            if (((y % kSeg) >> 2) == tid) gone |= 1ull << (4 * (y / kSeg) + (y & 3));
+        }
+        auto weight = [&](int j, int e) -> double {
+            float xv = 0.0f;
 #pragma unroll
-                for (int j = 0; j < kMaxSeg; ++j)
+            for (int jj = 0; jj < kMaxSeg; ++jj)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (j == y / kSeg && e == (y & 3)) w[j][e] = 0.0;
+                for (int ee = 0; ee < 4; ++ee) if (jj == j && ee == e) xv = x[jj][ee];
+            const bool live = tok_index(j, e) < V && !((gone >> (4 * j + e)) & 1ull);
+            return live ? exp_nonpos(fma((double)xv, inv_temp, -m)) : 0.0;
+        };
+        double seg[kMaxSeg];
+#pragma unroll
+        for (int j = 0; j < kMaxSeg; ++j) {
+            double w4[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool live = tok_index(j, e) < V && !((gone >> (4 * j + e)) & 1ull);
+                w4[e] = live ? exp_nonpos(fma((double)x[j][e], inv_temp, -m)) : 0.0;
             }
+            seg[j] = (w4[0] + w4[1]) + (w4[2] + w4[3]);
         }
 
         // ---- draw the token
         const double u = (double)u01(seed, sh.pk[p], (uint32_t)rank, KIND_BUILD);
         double W, wy;
-        const int y = block_inverse_cdf<double>(w, u, &sh.cdf, &W, &wy);
+        const int y = block_inverse_cdf_seg(seg, u, &sh.cdf, &W, &wy, weight);
         if (y < 0) break;                              // nothing left to sample under p
 
         // ---- append node n, open its two slots

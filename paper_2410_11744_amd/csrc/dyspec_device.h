@@ -9,10 +9,10 @@
 namespace dyspec {
 
 constexpr int kWave = 64;
-constexpr int kBlock = 1024;                  // threads per workgroup of the vocabulary kernels
-constexpr int kWaves = kBlock / kWave;        // 16
+constexpr int kBlock = 512;                   // threads per workgroup of the vocabulary kernels
+constexpr int kWaves = kBlock / kWave;        // 8
 constexpr int kSeg = 4 * kBlock;              // tokens per vocabulary segment (float4 per thread)
-constexpr int kMaxSeg = DYSPEC_MAX_VOCAB / kSeg;   // 8
+constexpr int kMaxSeg = DYSPEC_MAX_VOCAB / kSeg;   // 16
 
 // Per-sequence scalars, passed to kernels by value.
 struct SeqArgs {

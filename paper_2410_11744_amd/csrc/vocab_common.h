@@ -1,6 +1,6 @@
 // Vocabulary-row helpers for the tree builder and the verifier.
 //
-// A row of V <= 8*4096 values is held in registers by a 1024-thread workgroup: thread t
+// A row of V <= 16*2048 values is held in registers by a 512-thread workgroup: thread t
 // owns elements {4096*j + 4*t + e : j < 8, e < 4}, so every wave reads whole 1 KiB
 // stretches of the row with 128-bit loads, and token order is (segment j, thread t,
 // element e) lexicographic -- the order the inverse CDF walks.
@@ -40,20 +40,18 @@ struct CdfScratch {
     double wy;
 };
 
-// Inverse CDF over the non-negative weights w (register-resident row): the smallest token
-// index y with sum_{x<=y} w[x] > u*W, W = total weight.  Zero-weight tokens are never
-// returned.  Every thread gets y (or -1 when W == 0), W and w[y].
-template <typename T>
-__device__ __forceinline__ int block_inverse_cdf(const T (&w)[kMaxSeg][4], double u,
-                                                 CdfScratch* sc, double* W_out, double* wy_out)
+// Inverse CDF over non-negative weights held one 4-token segment sum per (thread, j):
+// seg[j] = weight(j,0) + ... + weight(j,3) for tokens tok_index(j, 0..3).  Returns the smallest
+// token index y with sum_{x<=y} w[x] > u*W, W = total weight; zero-weight tokens are never
+// returned.  Every thread gets y (or -1 when W == 0), W and w[y].  Only the thread that owns
+// the crossing segment asks for single weights again (weight(j, e), j uniform in its loop).
+template <typename F>
+__device__ __forceinline__ int block_inverse_cdf_seg(const double (&seg_in)[kMaxSeg], double u, CdfScratch* sc,
+                                                     double* W_out, double* wy_out, F&& weight)
 {
     double seg[kMaxSeg];
 #pragma unroll
-    for (int j = 0; j < kMaxSeg; ++j)
-        seg[j] = ((double)w[j][0] + (double)w[j][1]) + ((double)w[j][2] + (double)w[j][3]);
-    double mine_all[kMaxSeg];
-#pragma unroll
-    for (int j = 0; j < kMaxSeg; ++j) mine_all[j] = seg[j];
+    for (int j = 0; j < kMaxSeg; ++j) seg[j] = seg_in[j];
     if (threadIdx.x == 0) { sc->owner = 0x7fffffff; sc->last = -1; sc->y = -1; sc->wy = 0.0; }
     block_sum<double, kMaxSeg>(seg, sc->red);
 
@@ -80,7 +78,7 @@ __device__ __forceinline__ int block_inverse_cdf(const T (&w)[kMaxSeg][4], doubl
     }
     double mine = 0.0;
 #pragma unroll
-    for (int j = 0; j < kMaxSeg; ++j) if (j == js) mine = mine_all[j];
+    for (int j = 0; j < kMaxSeg; ++j) if (j == js) mine = seg_in[j];
 
     double excl;
     const double incl = block_scan_inclusive<double>(mine, sc->red, &excl);
@@ -97,7 +95,7 @@ __device__ __forceinline__ int block_inverse_cdf(const T (&w)[kMaxSeg][4], doubl
             if (j != js) continue;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const double we = (double)w[j][e];
+                const double we = weight(j, e);
                 run += we;
                 if (we > 0.0) { ylast = tok_index(j, e); wlast = we; }
                 if (y < 0 && we > 0.0 && run > target) { y = tok_index(j, e); wy = we; }
@@ -112,6 +110,25 @@ __device__ __forceinline__ int block_inverse_cdf(const T (&w)[kMaxSeg][4], doubl
     *wy_out = sc->wy;
     __syncthreads();                   // scratch may be reset by the next call from here on
     return y_all;
+}
+
+// The same over a register-resident row of weights.
+template <typename T>
+__device__ __forceinline__ int block_inverse_cdf(const T (&w)[kMaxSeg][4], double u,
+                                                 CdfScratch* sc, double* W_out, double* wy_out)
+{
+    double seg[kMaxSeg];
+#pragma unroll
+    for (int j = 0; j < kMaxSeg; ++j)
+        seg[j] = ((double)w[j][0] + (double)w[j][1]) + ((double)w[j][2] + (double)w[j][3]);
+    return block_inverse_cdf_seg(seg, u, sc, W_out, wy_out, [&](int j, int e) {
+        double r = 0.0;
+#pragma unroll
+        for (int jj = 0; jj < kMaxSeg; ++jj)
+#pragma unroll
+            for (int ee = 0; ee < 4; ++ee) if (jj == j && ee == e) r = (double)w[jj][ee];
+        return r;
+    });
 }
 
 }  // namespace dyspec
