@@ -74,7 +74,7 @@ typedef struct {
 /* Words per row of the ancestor bitmask for this batch: ceil(max_s N_s / 64). */
 int32_t dyspec_mask_words(const dyspec_batch* batch);
 
-/* Bytes of DEVICE workspace the named call needs for this batch (0 = none). */
+/* Bytes of DEVICE workspace the named call can use for this batch (0 = none). */
 enum { DYSPEC_WS_BUILD_TREE = 0, DYSPEC_WS_TREE_ATTN = 1, DYSPEC_WS_VERIFY = 2 };
 size_t dyspec_workspace_bytes(int32_t which, const dyspec_batch* batch, int32_t vocab,
                               int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim);
@@ -105,7 +105,12 @@ const char* dyspec_status_string(dyspec_status s);
  *                 ancestor of local node j or i == j
  *   n_built       DEVICE [n_seq]: rows actually built (< N only if no slot of positive
  *                 value is left); later rows keep parent = token = -1 and their own mask bit
- *   workspace     DEVICE, dyspec_workspace_bytes(DYSPEC_WS_BUILD_TREE, ...) bytes
+ *   workspace     DEVICE, dyspec_workspace_bytes(DYSPEC_WS_BUILD_TREE, ...) bytes, 8-byte
+ *                 aligned, contents overwritten: the 4-token sums of every row's softmax
+ *                 weights, computed for all rows at once before the serial expansion and
+ *                 kept current by it.  NULL or fewer bytes: the expansion recomputes the
+ *                 parent row's sums at every draw instead (same arithmetic, same tree,
+ *                 several times slower).
  * vocab <= DYSPEC_MAX_VOCAB, N <= DYSPEC_MAX_NODES.
  */
 dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab,

@@ -17,6 +17,7 @@ from . import build as _build
 
 F32, BF16, BF16_WAVE = 0, 1, 0x101
 MAX_SEQ, MAX_NODES, MAX_VOCAB = 64, 1024, 32768
+WS_BUILD_TREE, WS_TREE_ATTN, WS_VERIFY = 0, 1, 2
 EXPORTS = ("dyspec_mask_words", "dyspec_workspace_bytes", "dyspec_status_string",
            "dyspec_build_tree", "dyspec_tree_attn", "dyspec_verify")
 
@@ -175,8 +176,9 @@ class BuiltTrees:
     n_built: "torch.Tensor"        # int32 [n_seq]
 
 
-def build_tree(draft_logits, batch: Batch, draft_temp, seed: int, stream=None) -> BuiltTrees:
-    """dyspec_build_tree: greedy token-tree construction (Algorithm 1) + ancestor mask."""
+def build_tree(draft_logits, batch: Batch, draft_temp, seed: int, stream=None, use_workspace: bool = True) -> BuiltTrees:
+    """dyspec_build_tree: greedy token-tree construction (Algorithm 1) + ancestor mask.
+    use_workspace=False passes no workspace (the slower form that recomputes row sums)."""
     import torch
     lib = load_library()
     dev = draft_logits.device
@@ -189,8 +191,14 @@ def build_tree(draft_logits, batch: Batch, draft_temp, seed: int, stream=None) -
     nb = torch.empty(batch.n_seq, dtype=torch.int32, device=dev)
     cb, ct = batch._c(), tree._c()
     tarr, tptr = _temps(draft_temp, batch.n_seq)
+    ws, ws_bytes = None, 0
+    if use_workspace:
+        ws_bytes = int(lib.dyspec_workspace_bytes(WS_BUILD_TREE, ctypes.byref(cb), V, 0, 0, 0))
+        if ws_bytes:
+            ws = torch.empty(ws_bytes // 8, dtype=torch.float64, device=dev)
     st = lib.dyspec_build_tree(_ptr(draft_logits, "float32"), V, ctypes.byref(cb), tptr, ctypes.c_uint64(seed),
-                               ctypes.byref(ct), _ptr(est), _ptr(mask), _ptr(nb), None, 0, _stream(stream))
+                               ctypes.byref(ct), _ptr(est), _ptr(mask), _ptr(nb),
+                               _ptr(ws) if ws is not None else None, ctypes.c_size_t(ws_bytes), _stream(stream))
     _check(st, "dyspec_build_tree")
     return BuiltTrees(tree, est, mask, nb)
 

@@ -54,9 +54,13 @@ int32_t dyspec_mask_words(const dyspec_batch* batch)
     return mask_words_of(batch);
 }
 
-size_t dyspec_workspace_bytes(int32_t, const dyspec_batch*, int32_t, int32_t, int32_t, int32_t)
+size_t dyspec_workspace_bytes(int32_t which, const dyspec_batch* batch, int32_t, int32_t, int32_t, int32_t)
 {
-    return 0;   // every kernel keeps its scratch in registers and LDS
+    // only the tree builder uses one (the rows' segment sums); everything else keeps its
+    // scratch in registers and LDS
+    SeqArgs sa;
+    if (which != DYSPEC_WS_BUILD_TREE || check_batch(batch, false, &sa) != DYSPEC_OK) return 0;
+    return build_tree_workspace_bytes(sa.node_off[sa.n_seq]);
 }
 
 const char* dyspec_status_string(dyspec_status s)
@@ -75,7 +79,7 @@ const char* dyspec_status_string(dyspec_status s)
 dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab, const dyspec_batch* batch,
                                 const float* draft_temp, uint64_t seed, const dyspec_tree* tree,
                                 float* est_value, uint64_t* anc_mask, int32_t* n_built,
-                                void*, size_t, void* hip_stream)
+                                void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     SeqArgs sa;
     const dyspec_status st = check_batch(batch, false, &sa);
@@ -88,7 +92,8 @@ dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab, const 
         sa.temp_d[s] = draft_temp[s];
     }
     const hipError_t e = launch_build_tree(draft_logits, vocab, sa, seed, *tree, est_value, anc_mask,
-                                           mask_words_of(batch), n_built, static_cast<hipStream_t>(hip_stream));
+                                           mask_words_of(batch), n_built, workspace, workspace_bytes,
+                                           static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
 }
 

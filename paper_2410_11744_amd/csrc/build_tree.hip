@@ -4,10 +4,17 @@
 // One 512-thread workgroup builds one sequence's tree without leaving the GPU.  The
 // paper keeps the expandable slots in a heap on the host; here the frontier (at most two
 // new slots per node) lives in LDS and the pop is a workgroup arg-max, which costs less
-// than a heap's pointer chasing at these sizes.  Each expansion is one pass over the
-// parent's draft row held in registers: fp64 softmax weights summed four tokens at a time,
-// workgroup sum and scan of those sums for the inverse-CDF draw.  fp64 keeps every discrete decision (which slot, which token) equal
-// to an fp64 evaluation of the algorithm except at relative margins near 1e-13.
+// than a heap's pointer chasing at these sizes.  A draw needs the parent's residual draft
+// distribution: fp64 softmax weights summed four tokens at a time, a workgroup sum and scan
+// of those sums for the inverse CDF.  fp64 keeps every discrete decision (which slot, which
+// token) equal to an fp64 evaluation of the algorithm except at relative margins near 1e-13.
+//
+// With a workspace the O(vocabulary) part leaves the serial loop: draft_row_sums_kernel (one
+// workgroup per row, all rows at once) stores every row's segment sums, and the builder keeps
+// them current -- a draw changes the one sum that held the drawn token and the total of its
+// segment -- so a draw reads 16 totals and one 4 KB line of sums instead of a whole row of
+// logits.  Without a workspace the builder recomputes the sums of the parent's row for every
+// draw; both ways do the same arithmetic and build the same tree.
 #include "vocab_common.h"
 
 namespace dyspec {
@@ -40,6 +47,77 @@ __device__ __attribute__((noinline)) double exp_nonpos(double z)
     return ldexp(p, (int)n);
 }
 
+// Workspace of the cached form, per row (doubles): kMaxSeg * kBlock segment sums S[j][t],
+// kMaxSeg segment totals, the row maximum (already divided by the temperature), and one bit
+// per token: drawn at this position already (its weight is no longer in the sums).
+constexpr int kGoneWords = DYSPEC_MAX_VOCAB / 32;
+constexpr int kRowSumDoubles = kMaxSeg * kBlock + kMaxSeg + 8 + kGoneWords / 2;
+__host__ __device__ inline double* ws_sums(double* ws, int row) { return ws + (size_t)row * kRowSumDoubles; }
+__host__ __device__ inline double* ws_totals(double* ws, int row) { return ws_sums(ws, row) + kMaxSeg * kBlock; }
+__host__ __device__ inline double* ws_rowmax(double* ws, int row) { return ws_totals(ws, row) + kMaxSeg; }
+__host__ __device__ inline uint32_t* ws_gone(double* ws, int row) { return reinterpret_cast<uint32_t*>(ws_totals(ws, row) + kMaxSeg + 8); }
+
+// weight of one token of a row: exp(x / T - m), m the row maximum over T
+__device__ __forceinline__ double token_weight(float x, double inv_temp, double m)
+{
+    return exp_nonpos(fma((double)x, inv_temp, -m));
+}
+
+// Row maximum (over T) and the 4-token segment sums of this thread for one draft row, with
+// the tokens flagged in `gone` (bit 4j+e) left out.
+template <bool VEC>
+__device__ __forceinline__ void row_segment_sums(const float* __restrict__ row, int V, double inv_temp, uint64_t gone,
+                                                 float* fred, double* m_out, double (&seg)[kMaxSeg])
+{
+    float x[kMaxSeg][4];
+    load_row<VEC>(row, V, x);
+    float mx[1] = { -INFINITY };
+#pragma unroll
+    for (int j = 0; j < kMaxSeg; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mx[0] = fmaxf(mx[0], x[j][e]);
+    block_max<1>(mx, fred);
+    const double m = (double)mx[0] * inv_temp;
+    *m_out = m;
+#pragma unroll
+    for (int j = 0; j < kMaxSeg; ++j) {
+        double w4[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool live = tok_index(j, e) < V && !((gone >> (4 * j + e)) & 1ull);
+            w4[e] = live ? token_weight(x[j][e], inv_temp, m) : 0.0;
+        }
+        seg[j] = (w4[0] + w4[1]) + (w4[2] + w4[3]);
+    }
+}
+
+// Data-parallel part (the draft softmax of every node, Algorithm 1's model call output):
+// one workgroup per row writes the row's segment sums, segment totals and maximum.
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void draft_row_sums_kernel(const float* __restrict__ draft_logits, int V, SeqArgs sa,
+                                                                double* __restrict__ ws)
+{
+    __shared__ float fred[kWaves];
+    __shared__ double red[kWaves * kMaxSeg];
+    const int row = blockIdx.x;
+    const int seq = find_seq(sa, row);
+    const double inv_temp = 1.0 / (double)sa.temp_d[seq];
+    double m, seg[kMaxSeg];
+    row_segment_sums<VEC>(draft_logits + (size_t)row * V, V, inv_temp, 0ull, fred, &m, seg);
+    double* S = ws_sums(ws, row);
+#pragma unroll
+    for (int j = 0; j < kMaxSeg; ++j) S[j * kBlock + threadIdx.x] = seg[j];
+    block_sum<double, kMaxSeg>(seg, red);
+    if (threadIdx.x < kMaxSeg) {
+        double t = 0.0;
+#pragma unroll
+        for (int j = 0; j < kMaxSeg; ++j) if (j == (int)threadIdx.x) t = seg[j];
+        ws_totals(ws, row)[threadIdx.x] = t;
+    }
+    if (threadIdx.x == 0) *ws_rowmax(ws, row) = m;
+    for (int w = threadIdx.x; w < kGoneWords; w += kBlock) ws_gone(ws, row)[w] = 0u;
+}
+
 struct BuildShared {
     double slot_value[kMaxSlots];       // < 0: closed
     int slot_parent[kMaxSlots];
@@ -58,11 +136,12 @@ struct BuildShared {
     int pick;
 };
 
-template <bool VEC>
+// CACHED: the rows' segment sums come from (and are kept current in) the workspace ws.
+template <bool VEC, bool CACHED>
 __global__ __launch_bounds__(kBlock) void build_tree_kernel(
     const float* __restrict__ draft_logits, int V, SeqArgs sa, uint64_t seed,
     dyspec_tree tree, float* __restrict__ est_value, uint64_t* __restrict__ anc_mask,
-    int mask_words, int* __restrict__ n_built)
+    int mask_words, int* __restrict__ n_built, double* ws)
 {
     __shared__ BuildShared sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -119,49 +198,60 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
         const double v = sh.slot_value[pick];
         const int rank = sh.n_children[p];
 
-        // ---- residual draft distribution of p: softmax weights with the earlier children's
-        //      tokens removed.  Only the 4-token segment sums stay in registers (the row of
-        //      fp64 weights itself would not fit); bit k of `gone` marks this thread's k-th
-        //      token as already drawn at this position.
-        float x[kMaxSeg][4];
-        load_row<VEC>(draft_logits + (size_t)(base + p) * V, V, x);
-        float mx[1] = { -INFINITY };
-#pragma unroll
-        for (int j = 0; j < kMaxSeg; ++j)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) mx[0] = fmaxf(mx[0], x[j][e]);
-        block_max<1>(mx, sh.fred);
-        const double m = (double)mx[0] * inv_temp;
-        uint64_t gone = 0ull;
-        for (int c = sh.first_child[p]; c >= 0; c = sh.next_sibling[c]) {
-            const int y = sh.token[c];
-            if (((y % kSeg) >> 2) == tid) gone |= 1ull << (4 * (y / kSeg) + (y & 3));
-        }
-        auto weight = [&](int j, int e) -> double {
-            float xv = 0.0f;
-#pragma unroll
-            for (int jj = 0; jj < kMaxSeg; ++jj)
-#pragma unroll
-                for (int ee = 0; ee < 4; ++ee) if (jj == j && ee == e) xv = x[jj][ee];
-            const bool live = tok_index(j, e) < V && !((gone >> (4 * j + e)) & 1ull);
-            return live ? exp_nonpos(fma((double)xv, inv_temp, -m)) : 0.0;
-        };
-        double seg[kMaxSeg];
-#pragma unroll
-        for (int j = 0; j < kMaxSeg; ++j) {
-            double w4[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool live = tok_index(j, e) < V && !((gone >> (4 * j + e)) & 1ull);
-                w4[e] = live ? exp_nonpos(fma((double)x[j][e], inv_temp, -m)) : 0.0;
-            }
-            seg[j] = (w4[0] + w4[1]) + (w4[2] + w4[3]);
-        }
-
-        // ---- draw the token
+        // ---- draw the token from the residual draft distribution of p (softmax weights with
+        //      the earlier children's tokens removed)
         const double u = (double)u01(seed, sh.pk[p], (uint32_t)rank, KIND_BUILD);
+        const float* __restrict__ row = draft_logits + (size_t)(base + p) * V;
         double W, wy;
-        const int y = block_inverse_cdf_seg(seg, u, &sh.cdf, &W, &wy, weight);
+        int y;
+        if constexpr (CACHED) {
+            // (ws is written by this kernel and not declared restrict or const, so these are
+            //  ordinary vector loads and stores, ordered by the barriers of the loop)
+            double* const S = ws_sums(ws, base + p);
+            double* const T = ws_totals(ws, base + p);
+            const double m = *ws_rowmax(ws, base + p);
+            double tot[kMaxSeg];
+#pragma unroll
+            for (int j = 0; j < kMaxSeg; ++j) tot[j] = T[j];
+            const SegPick pk = pick_segment(tot, u);
+            W = pk.W;
+            if (!(W > 0.0)) break;                     // nothing left to sample under p
+            const double mine = S[pk.js * kBlock + tid];
+            // weights of this thread's four tokens of segment js (they share one word of the
+            // drawn-already bits); only the thread that owns the crossing asks
+            uint32_t* const gone_word = ws_gone(ws, base + p) + tok_index(pk.js, 0) / 32;
+            const int gone_shift = tok_index(pk.js, 0) % 32;
+            auto weight_at = [&](int e, uint32_t gone) -> double {
+                const int idx = tok_index(pk.js, e);
+                if (idx >= V || ((gone >> (gone_shift + e)) & 1u)) return 0.0;
+                return token_weight(row[idx], inv_temp, m);
+            };
+            y = finish_inverse_cdf(pk, mine, &sh.cdf, &wy, [&](int, int e) { return weight_at(e, *gone_word); });
+            // the sum that held y and the total of its segment lose y's weight
+            double t1[1] = { mine };
+            if (((y % kSeg) >> 2) == tid) {
+                const uint32_t gone = *gone_word | (1u << (gone_shift + (y & 3)));
+                *gone_word = gone;
+                t1[0] = (weight_at(0, gone) + weight_at(1, gone)) + (weight_at(2, gone) + weight_at(3, gone));
+                S[pk.js * kBlock + tid] = t1[0];
+            }
+            block_sum<double, 1>(t1, sh.cdf.red);
+            if (tid == 0) T[pk.js] = t1[0];
+        } else {
+            // bit k of `gone` marks this thread's k-th token as already drawn at this position
+            uint64_t gone = 0ull;
+            for (int c = sh.first_child[p]; c >= 0; c = sh.next_sibling[c]) {
+                const int yc = sh.token[c];
+                if (((yc % kSeg) >> 2) == tid) gone |= 1ull << (4 * (yc / kSeg) + (yc & 3));
+            }
+            double m, seg[kMaxSeg];
+            row_segment_sums<VEC>(row, V, inv_temp, gone, sh.fred, &m, seg);
+            y = block_inverse_cdf_seg(seg, u, &sh.cdf, &W, &wy, [&](int j, int e) -> double {
+                const int idx = tok_index(j, e);
+                const bool live = idx < V && !((gone >> (4 * j + e)) & 1ull);
+                return live ? token_weight(row[idx], inv_temp, m) : 0.0;
+            });
+        }
         if (y < 0) break;                              // nothing left to sample under p
 
         // ---- append node n, open its two slots
@@ -193,16 +283,32 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
     if (tid == 0) n_built[seq] = n;
 }
 
+size_t build_tree_workspace_bytes(int total_rows) { return (size_t)total_rows * kRowSumDoubles * sizeof(double); }
+
 hipError_t launch_build_tree(const float* draft_logits, int V, const SeqArgs& sa, uint64_t seed,
                              const dyspec_tree& tree, float* est_value, uint64_t* anc_mask,
-                             int mask_words, int* n_built, hipStream_t stream)
+                             int mask_words, int* n_built, void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
-    if (V % 4 == 0)
-        build_tree_kernel<true><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
-                                                                 anc_mask, mask_words, n_built);
-    else
-        build_tree_kernel<false><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
-                                                                  anc_mask, mask_words, n_built);
+    const int rows = sa.node_off[sa.n_seq];
+    double* ws = static_cast<double*>(workspace);
+    const bool cached = ws != nullptr && workspace_bytes >= build_tree_workspace_bytes(rows);
+    if (cached) {
+        if (V % 4 == 0) {
+            draft_row_sums_kernel<true><<<rows, kBlock, 0, stream>>>(draft_logits, V, sa, ws);
+            build_tree_kernel<true, true><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
+                                                                           anc_mask, mask_words, n_built, ws);
+        } else {
+            draft_row_sums_kernel<false><<<rows, kBlock, 0, stream>>>(draft_logits, V, sa, ws);
+            build_tree_kernel<false, true><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
+                                                                            anc_mask, mask_words, n_built, ws);
+        }
+    } else if (V % 4 == 0) {
+        build_tree_kernel<true, false><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
+                                                                        anc_mask, mask_words, n_built, nullptr);
+    } else {
+        build_tree_kernel<false, false><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
+                                                                         anc_mask, mask_words, n_built, nullptr);
+    }
     return hipGetLastError();
 }
 

@@ -58,6 +58,22 @@ def test_build_and_verify_match_oracle(dy, nodes, V, sigma, tsigma, temps, seed)
         assert compared >= 1
 
 
+@pytest.mark.parametrize("nodes,V,sigma,tsigma,temps,seed", [CASES[2], CASES[3], CASES[6]])
+def test_build_without_workspace_builds_the_same_tree(dy, nodes, V, sigma, tsigma, temps, seed):
+    # no workspace: row sums are recomputed at every draw; same arithmetic, so the same bits
+    batch = dy.Batch.from_sizes(nodes)
+    d, _ = logits(sum(nodes), V, sigma, tsigma, 100 + seed)
+    dd = torch.from_numpy(d).cuda()
+    a = dy.build_tree(dd, batch, temps, seed)
+    b = dy.build_tree(dd, batch, temps, seed, use_workspace=False)
+    torch.cuda.synchronize()
+    for name in ("parent", "token", "sib_rank", "first_child", "next_sibling", "depth"):
+        assert torch.equal(getattr(a.tree, name), getattr(b.tree, name)), name
+    assert torch.equal(a.anc_mask, b.anc_mask) and torch.equal(a.n_built, b.n_built)
+    assert torch.equal(a.est_value, b.est_value)
+    assert compare_trees(b, batch, oracle_trees(d, nodes, temps, seed)) == len(nodes)
+
+
 def test_verify_many_seeds_accept_paths(dy):
     """Same tree, many Philox seeds: accepted path and final token agree wherever the
     oracle's decision margins are not tiny; the skipped fraction stays small."""
