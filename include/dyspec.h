@@ -180,6 +180,20 @@ dyspec_status dyspec_verify(const float* draft_logits, const float* target_logit
                             float* min_margin, void* workspace, size_t workspace_bytes,
                             void* hip_stream);
 
+/*
+ * Measurement helpers (no part of the method): two ceilings to set beside the published
+ * peaks of the chip.  Both only launch; the caller times them (HIP events on hip_stream).
+ *
+ * dyspec_probe_mfma_bf16: 1024 workgroups of 8 waves, every wave `iterations` rounds of four
+ * independent 32x32x16 bf16 MFMAs, no memory traffic.  *flops (HOST) receives the number of
+ * floating-point operations of the launch.  sink: DEVICE, one float, never written in practice.
+ *
+ * dyspec_probe_hbm_read: streams `bytes` (a multiple of 16, src DEVICE, 16-byte aligned) from
+ * memory once with 16-byte loads, eight in flight per thread.
+ */
+dyspec_status dyspec_probe_mfma_bf16(int32_t iterations, double* flops, float* sink, void* hip_stream);
+dyspec_status dyspec_probe_hbm_read(const void* src, size_t bytes, float* sink, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -3,7 +3,9 @@
 ``verify`` (Algorithm 3).  The work is done by hand-written HIP kernels behind the C ABI
 in ``include/dyspec.h``; this package only marshals arguments."""
 from .binding import (BF16, BF16_WAVE, F32, Batch, BuiltTrees, DyspecError, Tree, VerifyOutput,
-                      build_tree, load_library, status_string, tree_attn, verify)
+                      build_tree, load_library, probe_hbm_read, probe_mfma_bf16, status_string, tree_attn,
+                      verify)
 
 __all__ = ["BF16", "BF16_WAVE", "F32", "Batch", "BuiltTrees", "DyspecError", "Tree", "VerifyOutput",
-           "build_tree", "load_library", "status_string", "tree_attn", "verify"]
+           "build_tree", "load_library", "probe_hbm_read", "probe_mfma_bf16", "status_string", "tree_attn",
+           "verify"]

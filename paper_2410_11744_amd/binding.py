@@ -19,7 +19,8 @@ F32, BF16, BF16_WAVE = 0, 1, 0x101
 MAX_SEQ, MAX_NODES, MAX_VOCAB = 64, 1024, 32768
 WS_BUILD_TREE, WS_TREE_ATTN, WS_VERIFY = 0, 1, 2
 EXPORTS = ("dyspec_mask_words", "dyspec_workspace_bytes", "dyspec_status_string",
-           "dyspec_build_tree", "dyspec_tree_attn", "dyspec_verify")
+           "dyspec_build_tree", "dyspec_tree_attn", "dyspec_verify",
+           "dyspec_probe_mfma_bf16", "dyspec_probe_hbm_read")
 
 
 class DyspecError(RuntimeError):
@@ -67,6 +68,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.dyspec_verify.restype = I32
     lib.dyspec_verify.argtypes = [V, V, I32, PB, PT, ctypes.POINTER(F), ctypes.POINTER(F), U64, I32,
                                   V, V, V, V, V, V, V, SZ, V]
+    lib.dyspec_probe_mfma_bf16.restype = I32
+    lib.dyspec_probe_mfma_bf16.argtypes = [I32, ctypes.POINTER(ctypes.c_double), V, V]
+    lib.dyspec_probe_hbm_read.restype = I32
+    lib.dyspec_probe_hbm_read.argtypes = [V, SZ, V, V]
     if path is None:
         _lib = lib
     return lib
@@ -268,3 +273,19 @@ def verify(draft_logits, target_logits, batch: Batch, tree: Tree, draft_temp, ta
                            _ptr(out.min_margin), None, 0, _stream(stream))
     _check(st, "dyspec_verify")
     return out
+
+
+def probe_mfma_bf16(iterations: int, sink, stream=None) -> float:
+    """dyspec_probe_mfma_bf16: launches the MFMA-only loop, returns the flops of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(load_library().dyspec_probe_mfma_bf16(int(iterations), ctypes.byref(flops), _ptr(sink, "float32"),
+                                                 _stream(stream)), "dyspec_probe_mfma_bf16")
+    return float(flops.value)
+
+
+def probe_hbm_read(src, sink, stream=None) -> int:
+    """dyspec_probe_hbm_read: launches one streaming read of src, returns the bytes read."""
+    nbytes = (src.numel() * src.element_size()) // 16 * 16
+    _check(load_library().dyspec_probe_hbm_read(_ptr(src), ctypes.c_size_t(nbytes), _ptr(sink, "float32"),
+                                                _stream(stream)), "dyspec_probe_hbm_read")
+    return nbytes

@@ -49,6 +49,10 @@ CONFIGS = {
                                  (0.6,) * 4 + (1.0,) * 4, _N5, _P5, 4),
 }
 ORDER = ["tiny_f32", "llama2_7b", "llama2_13b", "llama2_70b", "llama2_70b_ragged8"]
+# supplementary point: the 70B shape with a tree so narrow (G*N = 256 rows per K/V byte) that
+# tree attention is bound by the K/V stream from HBM, not by the matrix cores
+CONFIGS["llama2_70b_n32"] = Config("llama2_70b_n32", 80, 64, 8, 128, 32000, "bf16", "normal", 3.0, (0.8, 0.8), (0.6,),
+                                   (32,), (4096,), 3)
 
 
 def make_logits(cfg: Config, seed: Optional[int] = None) -> Tuple[np.ndarray, np.ndarray]:
