@@ -134,8 +134,13 @@ dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab,
  *   anc_mask          DEVICE [sum N, mask_words] as written by dyspec_build_tree
  *   dtype             DYSPEC_F32 (any head_dim <= 256, multiple of 4) or DYSPEC_BF16
  *                     (head_dim 64 or 128; matrix-core path, fp32 accumulation)
- * All tensors are dense row-major and 16-byte aligned.  workspace may be NULL when
- * dyspec_workspace_bytes(DYSPEC_WS_TREE_ATTN, ...) is 0.
+ * All tensors are dense row-major and 16-byte aligned.
+ *   workspace         DEVICE, 16-byte aligned, dyspec_workspace_bytes(DYSPEC_WS_TREE_ATTN, ...)
+ *                     bytes, contents overwritten.  Non-zero only for batches whose (row
+ *                     tiles) x (KV heads) leave most of the chip idle: the bf16 path then
+ *                     splits every prefix over several workgroups, which leave partial
+ *                     (max, sum, rows) there for a second, combining kernel.  NULL or fewer
+ *                     bytes: no split (same result up to fp32 rounding of the combine).
  */
 dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* v_prefix,
                                const void* k_tree, const void* v_tree,

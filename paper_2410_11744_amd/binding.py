@@ -208,9 +208,25 @@ def build_tree(draft_logits, batch: Batch, draft_temp, seed: int, stream=None, u
     return BuiltTrees(tree, est, mask, nb)
 
 
+_scratch_cache = {}
+
+
+def _scratch(device, nbytes: int):
+    """A device buffer of at least nbytes, kept between calls (calls on one stream run in order,
+    so consecutive layers can share it)."""
+    import torch
+    key = str(device)
+    buf = _scratch_cache.get(key)
+    if buf is None or buf.numel() * 4 < nbytes:
+        buf = torch.empty((nbytes + 3) // 4, dtype=torch.float32, device=device)
+        _scratch_cache[key] = buf
+    return buf
+
+
 def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, softmax_scale: float,
-              out=None, dtype: Optional[int] = None, stream=None):
-    """dyspec_tree_attn: one layer of tree-masked attention.  q/out [sum N, Hq, d]."""
+              out=None, dtype: Optional[int] = None, stream=None, use_workspace: bool = True):
+    """dyspec_tree_attn: one layer of tree-masked attention.  q/out [sum N, Hq, d].
+    use_workspace=False passes no workspace (then the prefix is never split over workgroups)."""
     import torch
     lib = load_library()
     total, Hq, d = q.shape
@@ -230,9 +246,15 @@ def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, sof
     if out is None:
         out = torch.empty_like(q)
     cb = batch._c()
+    ws, ws_bytes = None, 0
+    if use_workspace and dtype == BF16:
+        ws_bytes = int(lib.dyspec_workspace_bytes(WS_TREE_ATTN, ctypes.byref(cb), 0, int(Hq), Hkv, int(d)))
+        if ws_bytes:
+            ws = _scratch(q.device, ws_bytes)
     st = lib.dyspec_tree_attn(_ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree),
                               _ptr(anc_mask, "int64"), ctypes.byref(cb), int(Hq), Hkv, int(d), int(dtype),
-                              ctypes.c_float(softmax_scale), _ptr(out), None, 0, _stream(stream))
+                              ctypes.c_float(softmax_scale), _ptr(out), _ptr(ws) if ws is not None else None,
+                              ctypes.c_size_t(ws_bytes), _stream(stream))
     _check(st, "dyspec_tree_attn")
     return out
 

@@ -54,13 +54,21 @@ int32_t dyspec_mask_words(const dyspec_batch* batch)
     return mask_words_of(batch);
 }
 
-size_t dyspec_workspace_bytes(int32_t which, const dyspec_batch* batch, int32_t, int32_t, int32_t, int32_t)
+size_t dyspec_workspace_bytes(int32_t which, const dyspec_batch* batch, int32_t, int32_t n_q_heads, int32_t n_kv_heads,
+                              int32_t head_dim)
 {
-    // only the tree builder uses one (the rows' segment sums); everything else keeps its
-    // scratch in registers and LDS
+    // the tree builder keeps the rows' segment sums there; tree attention its partial results
+    // when it splits the prefix over several workgroups; verification needs none
     SeqArgs sa;
-    if (which != DYSPEC_WS_BUILD_TREE || check_batch(batch, false, &sa) != DYSPEC_OK) return 0;
-    return build_tree_workspace_bytes(sa.node_off[sa.n_seq]);
+    if (which == DYSPEC_WS_BUILD_TREE)
+        return check_batch(batch, false, &sa) == DYSPEC_OK ? build_tree_workspace_bytes(sa.node_off[sa.n_seq]) : 0;
+    if (which == DYSPEC_WS_TREE_ATTN) {
+        if (check_batch(batch, true, &sa) != DYSPEC_OK || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads != 0 ||
+            (head_dim != 64 && head_dim != 128))
+            return 0;
+        return tree_attn_workspace_bytes(sa, n_q_heads, n_kv_heads, head_dim);
+    }
+    return 0;
 }
 
 const char* dyspec_status_string(dyspec_status s)
@@ -101,7 +109,7 @@ dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* 
                                const void* k_tree, const void* v_tree, const uint64_t* anc_mask,
                                const dyspec_batch* batch, int32_t n_q_heads, int32_t n_kv_heads,
                                int32_t head_dim, int32_t dtype, float softmax_scale, void* out,
-                               void*, size_t, void* hip_stream)
+                               void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     SeqArgs sa;
     const dyspec_status st = check_batch(batch, true, &sa);
@@ -128,7 +136,9 @@ dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* 
     a.mask = anc_mask; a.out = out;
     a.mask_words = mask_words_of(batch);
     a.Hq = n_q_heads; a.Hkv = n_kv_heads; a.d = head_dim; a.scale = softmax_scale;
-    const hipError_t e = launch_tree_attn(a, sa, dtype, force_simple, static_cast<hipStream_t>(hip_stream));
+    a.splits = 1; a.part_rows = 0; a.part_acc = nullptr; a.part_ml = nullptr;
+    const hipError_t e = launch_tree_attn(a, sa, dtype, force_simple, workspace, workspace_bytes,
+                                          static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
 }
 

@@ -31,6 +31,13 @@ struct AttnArgs {
     int mask_words, Hq, Hkv, d;
     float scale;
     int tile_off[DYSPEC_MAX_SEQ + 1];      // first row tile of each sequence (matrix-core kernel)
+    // prefix split of the matrix-core kernel: split z of `splits` takes every sequence's prefix
+    // tiles [z*c, (z+1)*c) (c: an even share), the last one the tree as well; with splits > 1
+    // each leaves (max, sum, unnormalised rows) in the workspace for the combine kernel
+    int splits;
+    long long part_rows;                   // total rows * Hq
+    float* part_acc;                       // [splits][total rows * Hq][d] fp32
+    float* part_ml;                        // [splits][total rows * Hq][2] fp32
 };
 
 // Launchers (one per source file); each returns the launch status.
@@ -42,8 +49,12 @@ hipError_t launch_verify(const float* draft_logits, const float* target_logits, 
                          const SeqArgs& sa, const dyspec_tree& tree, uint64_t seed, int emit_bonus,
                          float* row_stats, float* accept_ratio, int* accepted_nodes, int* n_accepted,
                          int* final_token, float* min_margin, hipStream_t stream);
-hipError_t launch_tree_attn(AttnArgs a, const SeqArgs& sa, int dtype, bool per_wave, hipStream_t stream);
-hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, hipStream_t stream);
+hipError_t launch_tree_attn(AttnArgs a, const SeqArgs& sa, int dtype, bool per_wave, void* workspace, size_t workspace_bytes,
+                            hipStream_t stream);
+hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, void* workspace, size_t workspace_bytes, hipStream_t stream);
+// splits the matrix-core kernel would like for this batch, and the workspace that takes
+int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv);
+size_t tree_attn_workspace_bytes(const SeqArgs& sa, int Hq, int Hkv, int d);
 
 enum : uint32_t { KIND_PATH = 0, KIND_BUILD = 1, KIND_ACCEPT = 2, KIND_RESID = 3 };
 

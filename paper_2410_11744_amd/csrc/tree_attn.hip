@@ -93,11 +93,12 @@ __global__ __launch_bounds__(kSimpleWaves* kWave) void tree_attn_simple_kernel(A
     }
 }
 
-hipError_t launch_tree_attn(AttnArgs a, const SeqArgs& sa, int dtype, bool per_wave, hipStream_t stream)
+hipError_t launch_tree_attn(AttnArgs a, const SeqArgs& sa, int dtype, bool per_wave, void* workspace, size_t workspace_bytes,
+                            hipStream_t stream)
 {
     const int total_rows = sa.node_off[sa.n_seq];
     if (dtype == DYSPEC_BF16 && !per_wave && (a.d == 128 || a.d == 64))
-        return launch_tree_attn_mfma(a, sa, stream);
+        return launch_tree_attn_mfma(a, sa, workspace, workspace_bytes, stream);
     if (total_rows == 0) return hipSuccess;
     const long long waves = (long long)total_rows * a.Hq;
     const int blocks = (int)((waves + kSimpleWaves - 1) / kSimpleWaves);

@@ -153,7 +153,14 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
 
     const int nTp = (P + kKeysPerTile - 1) / kKeysPerTile;
     const int r_last = min(rows - 1, r0 + kRowsPerWG - 1);
-    const int nTt = (r_last / G) / kKeysPerTile + 1;      // tree tiles up to the largest node of this row tile
+    // Prefix split: this workgroup walks prefix tiles [p_begin, p_begin + nPl) and, if it is
+    // the last split, the tree tiles as well.
+    const int split = blockIdx.y, n_split = a.splits;
+    const int share = (((nTp + n_split - 1) / n_split) + 1) & ~1;      // an even number of tiles
+    const int p_begin = min(split * share, nTp);
+    const int nPl = min(nTp - p_begin, share);
+    const bool last_split = split == n_split - 1;
+    const int nTt = last_split ? (r_last / G) / kKeysPerTile + 1 : 0;  // tree tiles up to the largest node of this row tile
     const int nT = nTp + nTt;                              // a tile index >= nT stands for "no tile"
 
     const size_t kv_row_bytes = (size_t)a.Hkv * D * 2;
@@ -472,23 +479,27 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                     for (int w = 0; w < 4; ++w) pbw[bu][qb][ts][w] = 0u;
     }
     __syncthreads();
-    if constexpr (NW == 8) {
-        // K of the wave pair's first two tiles (tile mm = 2*slot + parity), V of the first
-        int voff_k[4];
-        lane_offsets(false, voff_k);
-        issue_tile(kp, kt, voff_k, ld_mm, lds0 + ld_mm * L::kMatBytes + ld_x0 * 1024);
-    } else {
-        // one matrix per wave: K tiles 0..3 go to waves 0..3, then the V waves add V of tiles 0, 1
-        int voff_k[4];
-        lane_offsets(false, voff_k);
-        issue_tile(kp, kt, voff_k, wave, lds0 + wave * L::kMatBytes);
-    }
-    if (ld_is_v) issue_tile(st_prefix, st_tree, ld_voff, ld_par, st_dst);
     // Tree tiles in which no query of the workgroup sees any key are left out altogether: the
-    // waves agree on the set (bit tt = tree tile tt) through LDS, and the loops below walk the
-    // prefix tiles followed by the tiles of the set.  (With fewer than four prefix tiles the
-    // loads above already reach into the tree, so then every tree tile stays in.)
-    const bool squeeze = nTp >= 4;
+    // waves agree on the set (bit tt = tree tile tt) through LDS, and the loops below walk this
+    // split's prefix tiles followed by the tiles of the set.  (With fewer than four prefix
+    // tiles the first loads already reach into the tree, so then every tree tile stays in.)
+    const bool squeeze = nPl >= 4;
+    // positions 0..3 of the walk, known before the set is: prefix tiles, then tree tiles in order
+    auto first_tiles = [=](int v) __attribute__((always_inline)) -> int {
+        return v < nPl ? p_begin + v : (v - nPl < nTt ? nTp + (v - nPl) : nT);
+    };
+    if constexpr (NW == 8) {
+        // K of the wave pair's first two tiles (position mm = 2*slot + parity), V of the first
+        int voff_k[4];
+        lane_offsets(false, voff_k);
+        issue_tile(kp, kt, voff_k, first_tiles(ld_mm), lds0 + ld_mm * L::kMatBytes + ld_x0 * 1024);
+    } else {
+        // one matrix per wave: K positions 0..3 go to waves 0..3, then the V waves add V of 0, 1
+        int voff_k[4];
+        lane_offsets(false, voff_k);
+        issue_tile(kp, kt, voff_k, first_tiles(wave), lds0 + wave * L::kMatBytes);
+    }
+    if (ld_is_v) issue_tile(st_prefix, st_tree, ld_voff, first_tiles(ld_par), st_dst);
     if (squeeze) {
         uint32_t mine = 0u;
         for (int tt = 0; tt < nTt; ++tt) {
@@ -501,13 +512,14 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     }
     wait_direct_loads();
     __syncthreads();
-    const uint32_t active = squeeze ? (uint32_t)__builtin_amdgcn_readfirstlane((int)*tile_flag) : (0xffffffffu >> (32 - nTt));
+    const uint32_t active = squeeze ? (uint32_t)__builtin_amdgcn_readfirstlane((int)*tile_flag)
+                                    : (nTt ? 0xffffffffu >> (32 - nTt) : 0u);
     const int nAct = __builtin_popcount(active);
-    const int nIt = (nTp + nAct + 1) / 2;                  // tiles per wave (the last odd one may not exist)
-    // position v in the walk -> tile index (prefix tiles, then the tree tiles of the set)
+    const int nIt = (nPl + nAct + 1) / 2;                  // tiles per wave (the last odd one may not exist)
+    // position v in the walk -> tile index (this split's prefix tiles, then the tree tiles of the set)
     auto tile_of = [=](int v) __attribute__((always_inline)) -> int {
-        if (v < nTp) return v;
-        const int k = v - nTp;
+        if (v < nPl) return p_begin + v;
+        const int k = v - nPl;
         if (k >= nAct) return nT;
         uint32_t m = active;
         for (int j = 0; j < k; ++j) m &= m - 1u;
@@ -523,9 +535,9 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         issue_tile(st_prefix, st_tree, ld_voff, tile_of(ld_is_v ? 2 * (i + 1) + ld_par : 2 * (i + 2) + ld_par),
                    st_dst + ((ld_is_v ? i + 1 : i) & 1) * L::kSlotBytes);
     };
-    // Plain steps: tiles 2i and 2i+1 are whole prefix tiles (no mask) and so are the tiles the
-    // step loads (a uniform base per load, spread over the upper half step).
-    const int nPlain = (P / kKeysPerTile) / 2 - 2;
+    // Plain steps: positions 2i and 2i+1 are whole prefix tiles (no mask) and so are the tiles
+    // the step loads (a uniform base per load, spread over the upper half step).
+    const int nPlain = min(nPl, max(P / kKeysPerTile - p_begin, 0)) / 2 - 2;
     int i = 0;
     for (; i + 1 < nPlain; i += 2) {
         static_for<2>([&](auto sp_c) {
@@ -533,7 +545,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
             run_half(std::false_type{}, std::false_type{}, sp_c, std::integral_constant<int, 0>{}, none32, nullptr, 0u);
             wait_direct_loads();
             __syncthreads();
-            const int tl = ld_is_v ? 2 * (ii + 1) + ld_par : 2 * (ii + 2) + ld_par;
+            const int tl = p_begin + (ld_is_v ? 2 * (ii + 1) + ld_par : 2 * (ii + 2) + ld_par);
             const char* base = st_prefix + (size_t)(tl * kKeysPerTile + L::kRowsPerLoad * ld_x0) * kv_row_bytes;
             run_half(std::false_type{}, std::true_type{}, sp_c, std::integral_constant<int, 1>{}, none32, base,
                      st_dst + ((ld_is_v ? ii + 1 : ii) & 1) * L::kSlotBytes);
@@ -624,14 +636,17 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     __syncthreads();
     if (wk == 0) {
         const float* src = xs + (size_t)wq * NR * kWave + lane;
-        float f0[QB], f1[QB], inv[QB];
+        const bool partial = n_split > 1;                  // leave (max, sum, unnormalised row) for the combine kernel
+        float f0[QB], f1[QB], inv[QB], m_all[QB], l_all[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const float m1 = src[(NR - 2 * QB + qb) * kWave], l1 = src[(NR - QB + qb) * kWave];
             const float m = fmaxf(m_run[qb], m1);
             f0[qb] = exp2f((m_run[qb] - m) * c2);
             f1[qb] = exp2f((m1 - m) * c2);
-            inv[qb] = 1.0f / (l_run[qb] * f0[qb] + l1 * f1[qb]);
+            m_all[qb] = m;
+            l_all[qb] = l_run[qb] * f0[qb] + l1 * f1[qb];
+            inv[qb] = partial ? 1.0f : 1.0f / l_all[qb];
         }
         int r = 0;
 #pragma unroll
@@ -648,7 +663,20 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         for (int qb = 0; qb < QB; ++qb) {
             if (rq[qb] >= rows) continue;
             const int j = rq[qb] / G, h = kvh * G + rq[qb] % G;
-            __bf16* orow = static_cast<__bf16*>(a.out) + ((size_t)(node_base + j) * a.Hq + h) * D;
+            const size_t orow_index = (size_t)(node_base + j) * a.Hq + h;
+            if (partial) {
+                const size_t prow = (size_t)split * a.part_rows + orow_index;
+                float* prow_acc = a.part_acc + prow * D;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int ib = 0; ib < 4; ++ib)
+                        *reinterpret_cast<float4*>(prow_acc + 32 * db + 8 * ib + 4 * g) =
+                            make_float4(acc[db][qb][4 * ib], acc[db][qb][4 * ib + 1], acc[db][qb][4 * ib + 2], acc[db][qb][4 * ib + 3]);
+                if (g == 0) *reinterpret_cast<float2*>(a.part_ml + prow * 2) = make_float2(m_all[qb], l_all[qb]);
+                continue;
+            }
+            __bf16* orow = static_cast<__bf16*>(a.out) + orow_index * D;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -665,26 +693,95 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     }
 }
 
+// Combine of a prefix split: out[row] = sum_z w_z acc_z[row] / sum_z w_z l_z, w_z = 2^{c (m_z - M)},
+// M = max_z m_z.  One thread per four head-dim elements of a row.
+template <int D>
+__global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnArgs a, long long total)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const size_t row = (size_t)(idx / (D / 4));
+    const int c4 = (int)(idx % (D / 4));
+    const float c2 = a.scale * 1.4426950408889634f;
+    float M = -INFINITY;
+    for (int z = 0; z < a.splits; ++z) M = fmaxf(M, a.part_ml[((size_t)z * a.part_rows + row) * 2]);
+    float L = 0.0f;
+    float4 o = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int z = 0; z < a.splits; ++z) {
+        const size_t prow = (size_t)z * a.part_rows + row;
+        const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + prow * 2);
+        const float w = exp2f((ml.x - M) * c2);
+        const float4 v = *reinterpret_cast<const float4*>(a.part_acc + prow * D + 4 * c4);
+        L += ml.y * w;
+        o.x += v.x * w; o.y += v.y * w; o.z += v.z * w; o.w += v.w * w;
+    }
+    const float inv = 1.0f / L;
+    union { bf16x2 p[2]; uint2 v; } out;
+    floatx2 lo = { o.x * inv, o.y * inv }, hi = { o.z * inv, o.w * inv };
+    out.p[0] = __builtin_convertvector(lo, bf16x2);
+    out.p[1] = __builtin_convertvector(hi, bf16x2);
+    *reinterpret_cast<uint2*>(static_cast<__bf16*>(a.out) + row * D + 4 * c4) = out.v;
+}
+
 template <int D, int QB>
 static hipError_t launch_one(const AttnArgs& a, const SeqArgs& sa, int tiles, hipStream_t stream)
 {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<D, QB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Geo<D>::kLdsBytes + 16);
     if (e != hipSuccess) return e;
-    tree_attn_mfma_kernel<D, QB><<<tiles * a.Hkv, 64 * 2 * (4 / QB), Geo<D>::kLdsBytes + 16, stream>>>(a, sa);
+    tree_attn_mfma_kernel<D, QB><<<dim3(tiles * a.Hkv, a.splits), 64 * 2 * (4 / QB), Geo<D>::kLdsBytes + 16, stream>>>(a, sa);
+    if (a.splits > 1) {
+        const long long total = (long long)a.part_rows * (D / 4);
+        tree_attn_combine_kernel<D><<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(a, total);
+    }
     return hipGetLastError();
 }
 
-hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, hipStream_t stream)
+static int row_tiles(const SeqArgs& sa, int G, int* tile_off)
 {
-    const int G = a.Hq / a.Hkv;
     int tiles = 0;
     for (int s = 0; s < sa.n_seq; ++s) {
-        a.tile_off[s] = tiles;
+        if (tile_off) tile_off[s] = tiles;
         tiles += (G * (sa.node_off[s + 1] - sa.node_off[s]) + kRowsPerWG - 1) / kRowsPerWG;
     }
-    a.tile_off[sa.n_seq] = tiles;
+    if (tile_off) tile_off[sa.n_seq] = tiles;
+    return tiles;
+}
+
+// The kernel's parallelism is (row tiles) x (KV heads), one workgroup per CU at a time; when
+// that leaves most of the 256 CUs idle (narrow trees, few KV heads) the prefix is split until
+// the workgroups fill the chip once, as long as every split keeps at least two 64-key tiles
+// (one step of the walk) of every sequence's prefix.
+int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv)
+{
+    const int groups = row_tiles(sa, Hq / Hkv, nullptr) * Hkv;
+    if (groups == 0) return 1;
+    int min_tiles = 1 << 30;
+    for (int s = 0; s < sa.n_seq; ++s) min_tiles = min(min_tiles, (sa.prefix_len[s] + kKeysPerTile - 1) / kKeysPerTile);
+    const int by_work = 256 / groups, by_prefix = min_tiles / 2;
+    return max(1, min(min(by_work, by_prefix), 32));
+}
+
+size_t tree_attn_workspace_bytes(const SeqArgs& sa, int Hq, int Hkv, int d)
+{
+    const int splits = tree_attn_splits(sa, Hq, Hkv);
+    if (splits <= 1) return 0;
+    return (size_t)splits * sa.node_off[sa.n_seq] * Hq * (d + 2) * sizeof(float);
+}
+
+hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, void* workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    const int tiles = row_tiles(sa, a.Hq / a.Hkv, a.tile_off);
     if (tiles == 0) return hipSuccess;
+    a.splits = tree_attn_splits(sa, a.Hq, a.Hkv);
+    a.part_rows = (long long)sa.node_off[sa.n_seq] * a.Hq;
+    const size_t need = tree_attn_workspace_bytes(sa, a.Hq, a.Hkv, a.d);
+    if (a.splits > 1 && (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<size_t>(workspace) & 15)))
+        a.splits = 1;                                          // no room for partial results: one workgroup walks it all
+    if (a.splits > 1) {
+        a.part_acc = static_cast<float*>(workspace);
+        a.part_ml = a.part_acc + (size_t)a.splits * a.part_rows * a.d;
+    }
     return a.d == 128 ? launch_one<128, kQB>(a, sa, tiles, stream) : launch_one<64, kQB>(a, sa, tiles, stream);
 }
 

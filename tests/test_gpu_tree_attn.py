@@ -121,6 +121,27 @@ def test_bf16_rising_scores_raise_the_reference(dy):
     run_and_compare(dy, (200,), (640,), 4, 4, 64, "bf16", 15, qscale=4.0, ramp=2.0)
 
 
+@pytest.mark.parametrize("nodes,prefix,Hq,Hkv", [
+    ((32,), (4096,), 64, 8),               # 70B shape, narrow tree: 16 workgroups become 256
+    ((128,), (1024 + 37,), 8, 8),          # ragged last prefix tile inside the last split
+    ((40, 9), (64 * 11, 64 * 8 + 1), 4, 2),  # two splits with shares of uneven size, ragged batch
+])
+def test_bf16_prefix_split_matches_unsplit_and_oracle(dy, nodes, prefix, Hq, Hkv):
+    batch = dy.Batch.from_sizes(nodes, prefix)
+    q, kp, vp, kt, vt, mask = make_case(nodes, prefix, Hq, Hkv, 128, "bf16", 21)
+    scale = 1.0 / math.sqrt(128)
+    mask_dev = torch.from_numpy(mask.view(np.int64)).cuda()
+    args = [t.cuda() for t in (q, kp, vp, kt, vt)]
+    need = dy.load_library().dyspec_workspace_bytes(1, __import__("ctypes").byref(batch._c()), 0, Hq, Hkv, 128)
+    assert need > 0, "this shape is meant to be split"
+    split = dy.tree_attn(*args, mask_dev, batch, scale)
+    whole = dy.tree_attn(*args, mask_dev, batch, scale, use_workspace=False)
+    torch.cuda.synchronize()
+    # same products, one more fp32 combine and a different bf16 rounding point
+    assert float((split.float() - whole.float()).abs().max()) <= 2.0 ** -6
+    run_and_compare(dy, nodes, prefix, Hq, Hkv, 128, "bf16", 21)
+
+
 def test_bf16_chain_tree_is_causal(dy):
     run_and_compare(dy, (130,), (70,), 4, 2, 128, "bf16", 11, chain=True)
 
