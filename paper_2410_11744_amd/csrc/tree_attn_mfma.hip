@@ -322,36 +322,56 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         float mc[QB], ls[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) { mc[qb] = m_run[qb] * c2; ls[qb] = 0.0f; }
-        float pt[8 * QB][2];
         // Register i of a 32x32 score block holds key row 8*(i/4) + 4*g + i%4, query column n.
-        // Item h of the vector work: pair p = (h/2) % 8 of query block h/16 covers scores 2p,
-        // 2p+1; even items take the exponentials, odd items mask, sum and pack them.
+        // Vector work on pair p = scores 2p, 2p+1 of a query block: F (two fma: the exponents),
+        // X (two exponentials), M (mask, only for masked halves), C (round the pair to bf16 and
+        // store it as a numerator word), D (add the rounded pair to the row sum).  A wave issues
+        // in order and a dependent vector instruction waits for its operand, so the stages of a
+        // pair sit in different items: item h (two per pair) holds X(p) and D(p-1) when even,
+        // M(p), F(p+1) and C(p) when odd; F of the first pair comes before item 0, D of the last
+        // pair after the last item.  Nothing inside an item depends on anything else in it.
+        constexpr int NPAIR = 8 * QB;
+        float ft[NPAIR][2], pt[NPAIR][2];
+        uint32_t pw[NPAIR];
+        auto stage_f = [&](auto kc) __attribute__((always_inline)) {
+            constexpr int k = decltype(kc)::value, qb = k / 8, i = 2 * (k % 8);
+            ft[k][0] = fmaf(S[E][qb][i], c2, -mc[qb]);
+            ft[k][1] = fmaf(S[E][qb][i + 1], c2, -mc[qb]);
+        };
+        auto stage_d = [&](auto kc) __attribute__((always_inline)) {
+            constexpr int k = decltype(kc)::value, qb = k / 8;
+            // the sum takes the rounded numerators, the ones the second product multiplies
+            ls[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[k]), kOnes2, ls[qb], false);
+        };
         auto valu_item = [&](auto hc) __attribute__((always_inline)) {
-            constexpr int h = decltype(hc)::value, qb = h / 16, p = (h / 2) % 8, i = 2 * p;
+            constexpr int h = decltype(hc)::value, k = h / 2, qb = k / 8, p = k % 8, i = 2 * p;
             if constexpr (h % 2 == 0) {
-                pt[8 * qb + p][0] = fast_exp2(fmaf(S[E][qb][i], c2, -mc[qb]));
-                pt[8 * qb + p][1] = fast_exp2(fmaf(S[E][qb][i + 1], c2, -mc[qb]));
+                pt[k][0] = fast_exp2(ft[k][0]);
+                pt[k][1] = fast_exp2(ft[k][1]);
+                if constexpr (k > 0) stage_d(std::integral_constant<int, k - 1>{});
             } else {
-                float p0 = pt[8 * qb + p][0], p1 = pt[8 * qb + p][1];
+                float p0 = pt[k][0], p1 = pt[k][1];
                 if constexpr (MK) {
                     p0 = and_bits(p0, __builtin_amdgcn_sbfe((int)vis32[qb], 8 * (i / 4) + (i % 4), 1));
                     p1 = and_bits(p1, __builtin_amdgcn_sbfe((int)vis32[qb], 8 * (i / 4) + (i % 4) + 1, 1));
                 }
+                if constexpr (k + 1 < NPAIR) stage_f(std::integral_constant<int, k + 1>{});
                 floatx2 pp = { p0, p1 };
-                const bf16x2 pc = __builtin_convertvector(pp, bf16x2);
-                // the sum takes the rounded numerators, the ones the second product multiplies
-                ls[qb] = __builtin_amdgcn_fdot2_f32_bf16(pc, kOnes2, ls[qb], false);
-                uint32_t w = __builtin_bit_cast(uint32_t, pc);
+                uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
                 asm volatile("" : "+v"(w));                    // keep the conversion in this scheduling group
+                pw[k] = w;
                 pbw[E][qb][p / 4][p % 4] = w;
             }
         };
+        if constexpr (HS) stage_f(std::integral_constant<int, 0>{});
         if constexpr (NS > 0) {
-            // with both products, even slots belong to the second product and odd slots to the first
+            // with both products, even slots belong to the first product and odd slots to the second
+            // (the score chain then ends one MFMA before the half step does, so the next half
+            // step does not start by waiting for its scores)
             bf16x8 fr[NS];
             auto read_slot = [&](auto sc) __attribute__((always_inline)) {
                 constexpr int s = decltype(sc)::value;
-                constexpr bool isP = HP && (!HQ || s % 2 == 0);
+                constexpr bool isP = HP && (!HQ || s % 2 == 1);
                 constexpr int idx = (HP && HQ) ? s / 2 : s;
                 if constexpr (isP) {
                     // k-slot (g, e) of step ts is key 8*(2*ts + e/4) + 4*g + e%4 of the half
@@ -368,7 +388,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
             };
             auto mfma_slot = [&](auto sc) __attribute__((always_inline)) {
                 constexpr int s = decltype(sc)::value;
-                constexpr bool isP = HP && (!HQ || s % 2 == 0);
+                constexpr bool isP = HP && (!HQ || s % 2 == 1);
                 constexpr int idx = (HP && HQ) ? s / 2 : s;
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) {
@@ -404,6 +424,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
             static_for<16 * QB>(valu_item);
         }
         if constexpr (HS) {
+            stage_d(std::integral_constant<int, NPAIR - 1>{});
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) ls_half[qb] = ls[qb];
         }
@@ -460,14 +481,43 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         for (int qb = 0; qb < QB; ++qb) l_run[qb] += ls_half[qb];
     };
 
-    // ---- prologue.  The steady-state half step always runs all three parts; what it reads for
-    //      a half that does not exist must therefore be harmless.  V slots start as zeros and
-    //      the numerators start as zeros (0 * 0 adds nothing to the accumulators); K of a tile
-    //      that does not exist is whatever the slot held, and the scores it gives are masked.
+    // ---- prologue.  The first loads (K of walk positions 0..3, V of positions 0 and 1) start at
+    //      once, so that they fly beside the Q fragment loads and the zero fill below.
+    //      Tree tiles in which no query of the workgroup sees any key are left out of the walk:
+    //      the waves agree on the set (bit tt = tree tile tt) through LDS while those loads are in
+    //      flight.  (With fewer than four prefix tiles the first loads already reach into the
+    //      tree, so then every tree tile stays in.)
+    const bool squeeze = nPl >= 4;
+    // positions 0..3 of the walk, known before the set is: prefix tiles, then tree tiles in order
+    auto first_tiles = [=](int v) __attribute__((always_inline)) -> int {
+        return v < nPl ? p_begin + v : (v - nPl < nTt ? nTp + (v - nPl) : nT);
+    };
+    if constexpr (NW == 8) {
+        // position mm = 2*slot + parity
+        int voff_k[4];
+        lane_offsets(false, voff_k);
+        issue_tile(kp, kt, voff_k, first_tiles(ld_mm), lds0 + ld_mm * L::kMatBytes + ld_x0 * 1024);
+    } else {
+        // one matrix per wave: K positions 0..3 go to waves 0..3
+        int voff_k[4];
+        lane_offsets(false, voff_k);
+        issue_tile(kp, kt, voff_k, first_tiles(wave), lds0 + wave * L::kMatBytes);
+    }
+    if (ld_is_v) issue_tile(st_prefix, st_tree, ld_voff, first_tiles(ld_par), st_dst);
+    // The steady-state half step always runs all three parts; what it reads for a half that does
+    // not exist must therefore be harmless.  V of a tile that is not loaded starts as zeros (all
+    // of slot 1, and a matrix of slot 0 whose walk position does not exist) and the numerators
+    // start as zeros: 0 * 0 adds nothing to the accumulators.  K of a tile that does not exist is
+    // whatever the slot held, and the scores it gives are masked.
     uint32_t* const tile_flag = reinterpret_cast<uint32_t*>(lds + L::kLdsBytes);
     {
         const uint4 z = { 0u, 0u, 0u, 0u };
-        for (int x = tid; x < 2 * L::kSlotBytes / 16; x += 64 * NW) reinterpret_cast<uint4*>(lds + L::kVBase)[x] = z;
+        for (int x = tid; x < L::kSlotBytes / 16; x += 64 * NW) reinterpret_cast<uint4*>(lds + L::kVBase + L::kSlotBytes)[x] = z;
+#pragma unroll
+        for (int par = 0; par < 2; ++par)
+            if (first_tiles(par) >= nT)
+                for (int x = tid; x < L::kMatBytes / 16; x += 64 * NW)
+                    reinterpret_cast<uint4*>(lds + L::kVBase + par * L::kMatBytes)[x] = z;
         if (tid == 0) *tile_flag = 0u;
 #pragma unroll
         for (int bu = 0; bu < 2; ++bu)
@@ -479,27 +529,6 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                     for (int w = 0; w < 4; ++w) pbw[bu][qb][ts][w] = 0u;
     }
     __syncthreads();
-    // Tree tiles in which no query of the workgroup sees any key are left out altogether: the
-    // waves agree on the set (bit tt = tree tile tt) through LDS, and the loops below walk this
-    // split's prefix tiles followed by the tiles of the set.  (With fewer than four prefix
-    // tiles the first loads already reach into the tree, so then every tree tile stays in.)
-    const bool squeeze = nPl >= 4;
-    // positions 0..3 of the walk, known before the set is: prefix tiles, then tree tiles in order
-    auto first_tiles = [=](int v) __attribute__((always_inline)) -> int {
-        return v < nPl ? p_begin + v : (v - nPl < nTt ? nTp + (v - nPl) : nT);
-    };
-    if constexpr (NW == 8) {
-        // K of the wave pair's first two tiles (position mm = 2*slot + parity), V of the first
-        int voff_k[4];
-        lane_offsets(false, voff_k);
-        issue_tile(kp, kt, voff_k, first_tiles(ld_mm), lds0 + ld_mm * L::kMatBytes + ld_x0 * 1024);
-    } else {
-        // one matrix per wave: K positions 0..3 go to waves 0..3, then the V waves add V of 0, 1
-        int voff_k[4];
-        lane_offsets(false, voff_k);
-        issue_tile(kp, kt, voff_k, first_tiles(wave), lds0 + wave * L::kMatBytes);
-    }
-    if (ld_is_v) issue_tile(st_prefix, st_tree, ld_voff, first_tiles(ld_par), st_dst);
     if (squeeze) {
         uint32_t mine = 0u;
         for (int tt = 0; tt < nTt; ++tt) {

@@ -29,6 +29,7 @@ def dy():
     ("llama2_13b", 7, 512),
     ("llama2_70b", 79, 1024),
     ("llama2_70b_ragged8", 40, 256),
+    ("llama2_70b_n32", 3, 2048),            # supplementary HBM-bound point (16-way prefix split)
 ])
 def test_config(dy, name, layer, rows_per_seq):
     from paper_2410_11744_amd import synth
@@ -77,3 +78,16 @@ def test_config(dy, name, layer, rows_per_seq):
     print(f"  verify: paths compared {compared}, skipped for small margins {skipped}, "
           f"accepted {vout.n_accepted.cpu().tolist()}", flush=True)
     assert compared + skipped == batch.n_seq and compared >= max(1, batch.n_seq - 2)
+
+
+def test_ceiling_probes_run(dy):
+    """The two measurement helpers launch, finish and report plausible work sizes."""
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    flops = dy.probe_mfma_bf16(10, sink)
+    assert flops == 1024 * 8 * 10 * 4 * 2 * 32 * 32 * 16
+    buf = torch.ones(1 << 20, dtype=torch.float32, device="cuda")
+    assert dy.probe_hbm_read(buf, sink) == 4 << 20
+    torch.cuda.synchronize()
+    assert float(sink.item()) == 0.0
+    with pytest.raises(dy.DyspecError):
+        dy.probe_mfma_bf16(0, sink)
