@@ -183,6 +183,59 @@ def links_from_parent(parent):
     return fc, ns, dep
 
 
+def dfs_order(parent, first_child, next_sibling) -> np.ndarray:
+    """Depth-first (pre-order) visiting order of a token tree, children in sampling order
+    (Appendix "Block-Sparsity Friendly Token Order"): order[new] = old node index.  Rows that
+    were never attached to the tree (parent -1, not the root) follow the tree, in index order."""
+    par, fc, ns = (np.asarray(a, dtype=np.int64) for a in (parent, first_child, next_sibling))
+    N = par.shape[0]
+    order = []
+    stack = [0]
+    while stack:
+        node = stack.pop()
+        order.append(node)
+        kids = []
+        c = fc[node]
+        while c >= 0:
+            kids.append(int(c))
+            c = ns[c]
+        stack.extend(reversed(kids))                 # first-sampled child is visited first
+    seen = set(order)
+    order.extend(i for i in range(N) if i not in seen)
+    return np.asarray(order, dtype=np.int32)
+
+
+def relabel_tree(order, parent, token, sib_rank, first_child, next_sibling, depth):
+    """The same tree with node order[new] renamed to new.  Returns the six arrays and the
+    ancestor mask of the renamed tree (rows outside the tree keep only their own bit)."""
+    order = np.asarray(order, dtype=np.int64)
+    N = order.shape[0]
+    rank = np.empty(N, dtype=np.int64)
+    rank[order] = np.arange(N)
+    ren = lambda a: np.where(np.asarray(a)[order] >= 0, rank[np.maximum(np.asarray(a)[order], 0)], -1).astype(np.int32)
+    keep = lambda a: np.asarray(a)[order].astype(np.int32)
+    par_n = ren(parent)
+    words = (N + 63) // 64
+    mask = np.zeros((N, words), dtype=np.uint64)
+    for j in range(N):
+        a = j
+        while a >= 0:
+            mask[j, a // 64] |= np.uint64(1) << np.uint64(a % 64)
+            a = int(par_n[a])
+    return par_n, keep(token), keep(sib_rank), ren(first_child), ren(next_sibling), keep(depth), mask
+
+
+def mask_block_count(mask, n: int, block: int = 32) -> int:
+    """Number of block x block tiles of the n x n ancestor mask that hold at least one set bit."""
+    m = np.asarray(mask, dtype=np.uint64)
+    bits = ((m[:n, :, None] >> np.arange(64, dtype=np.uint64)[None, None, :]) & np.uint64(1)).astype(bool)
+    dense = bits.reshape(n, -1)[:, :n]
+    nb = (n + block - 1) // block
+    pad = np.zeros((nb * block, nb * block), dtype=bool)
+    pad[:n, :n] = dense
+    return int(pad.reshape(nb, block, nb, block).any(axis=(1, 3)).sum())
+
+
 def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, mask, scale: float) -> np.ndarray:
     """Tree-masked attention, plain definition in fp64.  q [N,Hq,d]; k/v_prefix [P,Hkv,d];
     k/v_tree [N,Hkv,d]; mask [N,words] uint64.  Returns [N,Hq,d] fp64."""
