@@ -120,6 +120,26 @@ dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * dyspec_dfs_reorder -- block-sparsity friendly token order (Appendix "Block-Sparsity
+ * Friendly Token Order"): renames the nodes of every built tree by their position in the
+ * depth-first pre-order walk that visits children in sampling order.  Subtrees become
+ * contiguous runs of rows, parents still precede children, and the ancestor mask of the renamed
+ * tree has fewer non-empty 32x32 blocks for tree attention to visit.  Rows that were never
+ * attached (n_built < N) follow the tree in index order.
+ *
+ *   tree           DEVICE inputs (all six arrays, as written by dyspec_build_tree)
+ *   tree_out       DEVICE outputs, six arrays distinct from the inputs: the renamed tree
+ *   order          DEVICE [sum N] i32: order[node_offset[s] + new] = old local index; the caller
+ *                  gathers token-aligned tensors (q, k_tree, v_tree, logit rows) with it
+ *   anc_mask_out   DEVICE [sum N, mask_words] u64: ancestor mask of the renamed tree
+ * Verification of the renamed tree reads logit rows by the new indices (gathered tables), and
+ * Philox draws are named by paths of sibling ranks, so its outcome does not change.
+ */
+dyspec_status dyspec_dfs_reorder(const dyspec_batch* batch, const dyspec_tree* tree,
+                                 const dyspec_tree* tree_out, int32_t* order,
+                                 uint64_t* anc_mask_out, void* hip_stream);
+
+/*
  * dyspec_tree_attn -- one layer of tree attention (Section 2, "Tree Attention";
  * Appendix C for the block-sparse treatment of the tree part).
  *

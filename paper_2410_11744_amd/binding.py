@@ -19,7 +19,7 @@ F32, BF16, BF16_WAVE = 0, 1, 0x101
 MAX_SEQ, MAX_NODES, MAX_VOCAB = 64, 1024, 32768
 WS_BUILD_TREE, WS_TREE_ATTN, WS_VERIFY = 0, 1, 2
 EXPORTS = ("dyspec_mask_words", "dyspec_workspace_bytes", "dyspec_status_string",
-           "dyspec_build_tree", "dyspec_tree_attn", "dyspec_verify",
+           "dyspec_build_tree", "dyspec_dfs_reorder", "dyspec_tree_attn", "dyspec_verify",
            "dyspec_probe_mfma_bf16", "dyspec_probe_hbm_read")
 
 
@@ -68,6 +68,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.dyspec_verify.restype = I32
     lib.dyspec_verify.argtypes = [V, V, I32, PB, PT, ctypes.POINTER(F), ctypes.POINTER(F), U64, I32,
                                   V, V, V, V, V, V, V, SZ, V]
+    lib.dyspec_dfs_reorder.restype = I32
+    lib.dyspec_dfs_reorder.argtypes = [PB, PT, PT, V, V, V]
     lib.dyspec_probe_mfma_bf16.restype = I32
     lib.dyspec_probe_mfma_bf16.argtypes = [I32, ctypes.POINTER(ctypes.c_double), V, V]
     lib.dyspec_probe_hbm_read.restype = I32
@@ -206,6 +208,34 @@ def build_tree(draft_logits, batch: Batch, draft_temp, seed: int, stream=None, u
                                _ptr(ws) if ws is not None else None, ctypes.c_size_t(ws_bytes), _stream(stream))
     _check(st, "dyspec_build_tree")
     return BuiltTrees(tree, est, mask, nb)
+
+
+@dataclass
+class ReorderedTrees:
+    tree: Tree
+    order: "torch.Tensor"          # int32 [sum N]: order[offset + new] = old local index
+    anc_mask: "torch.Tensor"       # int64 view of u64 [sum N, mask_words]
+
+    def gather_index(self, batch: "Batch"):
+        """Global row indices: tensor[gather_index] puts token-aligned rows into the new order."""
+        import torch
+        off = torch.from_numpy(np.repeat(batch.node_offset[:-1], np.diff(batch.node_offset)).astype(np.int64))
+        return self.order.long() + off.to(self.order.device)
+
+
+def dfs_reorder(tree: Tree, batch: Batch, stream=None) -> ReorderedTrees:
+    """dyspec_dfs_reorder: rename every tree's nodes in depth-first order (block-sparsity friendly)."""
+    import torch
+    lib = load_library()
+    dev = tree.parent.device
+    total = batch.total_nodes
+    out = Tree.empty(total, dev)
+    order = torch.empty(total, dtype=torch.int32, device=dev)
+    mask = torch.empty((total, batch.mask_words), dtype=torch.int64, device=dev)
+    cb, ci, co = batch._c(), tree._c(), out._c()
+    _check(lib.dyspec_dfs_reorder(ctypes.byref(cb), ctypes.byref(ci), ctypes.byref(co), _ptr(order, "int32"),
+                                  _ptr(mask, "int64"), _stream(stream)), "dyspec_dfs_reorder")
+    return ReorderedTrees(out, order, mask)
 
 
 _scratch_cache = {}

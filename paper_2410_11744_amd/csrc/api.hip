@@ -105,6 +105,21 @@ dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab, const 
     return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
 }
 
+dyspec_status dyspec_dfs_reorder(const dyspec_batch* batch, const dyspec_tree* tree, const dyspec_tree* tree_out,
+                                 int32_t* order, uint64_t* anc_mask_out, void* hip_stream)
+{
+    SeqArgs sa;
+    const dyspec_status st = check_batch(batch, false, &sa);
+    if (st != DYSPEC_OK) return st;
+    if (!tree_ok(tree) || !tree_ok(tree_out) || !order || !anc_mask_out) return DYSPEC_BAD_ARG;
+    if (tree->parent == tree_out->parent || tree->token == tree_out->token || tree->first_child == tree_out->first_child ||
+        tree->next_sibling == tree_out->next_sibling || tree->sib_rank == tree_out->sib_rank || tree->depth == tree_out->depth)
+        return DYSPEC_BAD_ARG;                                   // not in place
+    const hipError_t e = launch_dfs_reorder(sa, *tree, *tree_out, order, anc_mask_out, mask_words_of(batch),
+                                            static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
+}
+
 dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* v_prefix,
                                const void* k_tree, const void* v_tree, const uint64_t* anc_mask,
                                const dyspec_batch* batch, int32_t n_q_heads, int32_t n_kv_heads,
