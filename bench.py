@@ -32,6 +32,83 @@ TRAFFIC_BYTES_PER_LAUNCH = {"llama2_70b": 36336531,
                             "llama2_70b_n32": 34810653 + 17854905}      # split kernel + combine kernel
 
 
+def tree_only_sweep(dy, synth, torch, np, dev) -> int:
+    """Block-sparsity friendly token order (the paper's appendix on token order and its random-tree table):
+    tree attention alone, 64 heads x head_dim 128, no prefix, on trees in creation order and after
+    dyspec_dfs_reorder; also the number of non-empty 32x32 blocks of the ancestor mask either way."""
+    H, d, scale = 64, 128, 1.0 / math.sqrt(128)
+
+    def blocks(mask_i64, n):
+        m = mask_i64.cpu().numpy().view(np.uint64)
+        bits = ((m[:n, :, None] >> np.arange(64, dtype=np.uint64)[None, None, :]) & np.uint64(1)).astype(bool)
+        dense = np.zeros((-(-n // 32) * 32,) * 2, dtype=bool)
+        dense[:n, :n] = bits.reshape(n, -1)[:, :n]
+        return int(dense.reshape(dense.shape[0] // 32, 32, -1, 32).any(axis=(1, 3)).sum())
+
+    def time_attn(q, kt, vt, mask, batch, reps=40):
+        empty = torch.empty((0, H, d), dtype=q.dtype, device=dev)
+        out = torch.empty_like(q)
+        for _ in range(5):
+            dy.tree_attn(q, empty, empty, kt, vt, mask, batch, scale, out=out)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best = float("inf")
+        for _ in range(3):                 # best of three runs of `reps` launches
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                dy.tree_attn(q, empty, empty, kt, vt, mask, batch, scale, out=out)
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1) * 1e3 / reps)
+        return best
+
+    rows = []
+    for n in (256, 512, 1024):
+        batch = dy.Batch.from_sizes([n], [0])
+        g = torch.Generator(device=dev).manual_seed(n)
+        q, kt, vt = (torch.randn((n, H, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
+        for kind in ("random", "greedy"):
+            if kind == "random":           # parent of node i uniform among the earlier nodes, children in index order
+                rng = np.random.default_rng(n)
+                par = np.full(n, -1, np.int32)
+                par[1:] = [rng.integers(0, i) for i in range(1, n)]
+                fc, ns, last = np.full(n, -1, np.int32), np.full(n, -1, np.int32), np.full(n, -1, np.int32)
+                dep, rk, cnt = np.zeros(n, np.int32), np.zeros(n, np.int32), np.zeros(n, np.int32)
+                for i in range(1, n):
+                    p = par[i]
+                    dep[i], rk[i] = dep[p] + 1, cnt[p]
+                    cnt[p] += 1
+                    if last[p] < 0:
+                        fc[p] = i
+                    else:
+                        ns[last[p]] = i
+                    last[p] = i
+                mk = lambda a: torch.from_numpy(a).to(dev)
+                tree = dy.Tree(mk(par), mk(np.zeros(n, np.int32)), mk(rk), mk(fc), mk(ns), mk(dep))
+                m = np.zeros((n, batch.mask_words), np.uint64)
+                for j in range(n):
+                    a = j
+                    while a >= 0:
+                        m[j, a // 64] |= np.uint64(1) << np.uint64(a % 64)
+                        a = par[a]
+                mask = torch.from_numpy(m.view(np.int64)).to(dev)
+            else:                          # the builder's own tree on N(0, 3^2) logits at temperature 0.6
+                cfg = synth.CONFIGS["llama2_70b"]
+                rng = np.random.default_rng(7 * n)
+                logits = torch.from_numpy((rng.standard_normal((n, cfg.vocab)) * 3.0).astype(np.float32)).to(dev)
+                built = dy.build_tree(logits, batch, (0.6,), 3)
+                tree, mask = built.tree, built.anc_mask
+            re = dy.dfs_reorder(tree, batch)
+            idx = re.gather_index(batch)
+            t0 = time_attn(q, kt, vt, mask, batch)
+            t1 = time_attn(q[idx].contiguous(), kt[idx].contiguous(), vt[idx].contiguous(), re.anc_mask, batch)
+            rows.append({"tree": kind, "nodes": n, "blocks_creation_order": blocks(mask, n), "blocks_dfs_order": blocks(re.anc_mask, n),
+                         "us_creation_order": round(t0, 2), "us_dfs_order": round(t1, 2),
+                         "max_depth": int(tree.depth.max().item())})
+    print(json.dumps({"tree_only_sweep": {"heads": H, "head_dim": d, "block": 32, "dtype": "bf16", "rows": rows}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -42,6 +119,9 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (a known-size reference for HBM byte counters)")
+    ap.add_argument("--tree-only-sweep", action="store_true",
+                    help="instead of the step benchmark: tree-only attention (64 heads, head_dim 128, no prefix) on random "
+                         "and greedy trees of 256..1024 nodes, creation order against depth-first order")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the two measured ceilings (MFMA-only loop, streaming HBM read)")
     args = ap.parse_args()
@@ -61,6 +141,8 @@ def main() -> int:
         return 3
     dy.load_library()
     dev = torch.device("cuda:0")
+    if args.tree_only_sweep:
+        return tree_only_sweep(dy, synth, torch, np, dev)
     cfg = synth.CONFIGS[args.workload]
     batch = dy.Batch.from_sizes(cfg.n_nodes, cfg.prefix_len)
     n_tokens = batch.total_nodes

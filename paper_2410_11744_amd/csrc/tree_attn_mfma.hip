@@ -481,16 +481,43 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         for (int qb = 0; qb < QB; ++qb) l_run[qb] += ls_half[qb];
     };
 
-    // ---- prologue.  The first loads (K of walk positions 0..3, V of positions 0 and 1) start at
-    //      once, so that they fly beside the Q fragment loads and the zero fill below.
-    //      Tree tiles in which no query of the workgroup sees any key are left out of the walk:
-    //      the waves agree on the set (bit tt = tree tile tt) through LDS while those loads are in
-    //      flight.  (With fewer than four prefix tiles the first loads already reach into the
-    //      tree, so then every tree tile stays in.)
-    const bool squeeze = nPl >= 4;
-    // positions 0..3 of the walk, known before the set is: prefix tiles, then tree tiles in order
+    // ---- prologue.  Tree tiles in which no query of the workgroup sees any key are left out of
+    //      the walk: every wave ballots its queries' mask words per tile and the waves OR the
+    //      results into one LDS word (bit tt = tree tile tt).  With four or more prefix tiles
+    //      ahead of the tree this happens while the first loads (K of walk positions 0..3, V of
+    //      positions 0 and 1, all prefix) are in flight; with fewer, the first loads reach into
+    //      the tree, so the set is agreed on first, when it can shorten the walk at all.
+    uint32_t* const tile_flag = reinterpret_cast<uint32_t*>(lds + L::kLdsBytes);
+    auto ballot_tiles = [=]() __attribute__((always_inline)) {
+        uint32_t mine = 0u;
+        for (int tt = 0; tt < nTt; ++tt) {
+            uint64_t w = 0ull;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) w |= mrow[qb][tt];
+            if (__any(w != 0ull)) mine |= 1u << tt;
+        }
+        if (lane == 0) atomicOr(tile_flag, mine);
+    };
+    const bool squeeze = nPl >= 4;                         // set agreed on behind the first loads
+    const bool squeeze_first = !squeeze && nTt > 4 - nPl;  // set agreed on before them
+    uint32_t first_set = nTt ? 0xffffffffu >> (32 - nTt) : 0u;
+    if (squeeze_first) {
+        if (tid == 0) *tile_flag = 0u;
+        __syncthreads();
+        ballot_tiles();
+        __syncthreads();
+        first_set = (uint32_t)__builtin_amdgcn_readfirstlane((int)*tile_flag);
+        __syncthreads();                                   // everyone has read it before it is cleared again
+    }
+    // k-th tree tile (in ascending order) of a set
+    auto kth_tile = [=](uint32_t set, int k) __attribute__((always_inline)) -> int {
+        if (k >= __builtin_popcount(set)) return nT;
+        for (int j = 0; j < k; ++j) set &= set - 1u;
+        return nTp + __builtin_ctz(set);
+    };
+    // positions 0..3 of the walk: prefix tiles, then the tree tiles known so far
     auto first_tiles = [=](int v) __attribute__((always_inline)) -> int {
-        return v < nPl ? p_begin + v : (v - nPl < nTt ? nTp + (v - nPl) : nT);
+        return v < nPl ? p_begin + v : kth_tile(first_set, v - nPl);
     };
     if constexpr (NW == 8) {
         // position mm = 2*slot + parity
@@ -509,7 +536,6 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     // of slot 1, and a matrix of slot 0 whose walk position does not exist) and the numerators
     // start as zeros: 0 * 0 adds nothing to the accumulators.  K of a tile that does not exist is
     // whatever the slot held, and the scores it gives are masked.
-    uint32_t* const tile_flag = reinterpret_cast<uint32_t*>(lds + L::kLdsBytes);
     {
         const uint4 z = { 0u, 0u, 0u, 0u };
         for (int x = tid; x < L::kSlotBytes / 16; x += 64 * NW) reinterpret_cast<uint4*>(lds + L::kVBase + L::kSlotBytes)[x] = z;
@@ -529,30 +555,15 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                     for (int w = 0; w < 4; ++w) pbw[bu][qb][ts][w] = 0u;
     }
     __syncthreads();
-    if (squeeze) {
-        uint32_t mine = 0u;
-        for (int tt = 0; tt < nTt; ++tt) {
-            uint64_t w = 0ull;
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) w |= mrow[qb][tt];
-            if (__any(w != 0ull)) mine |= 1u << tt;
-        }
-        if (lane == 0) atomicOr(tile_flag, mine);
-    }
+    if (squeeze) ballot_tiles();
     wait_direct_loads();
     __syncthreads();
-    const uint32_t active = squeeze ? (uint32_t)__builtin_amdgcn_readfirstlane((int)*tile_flag)
-                                    : (nTt ? 0xffffffffu >> (32 - nTt) : 0u);
+    const uint32_t active = squeeze ? (uint32_t)__builtin_amdgcn_readfirstlane((int)*tile_flag) : first_set;
     const int nAct = __builtin_popcount(active);
     const int nIt = (nPl + nAct + 1) / 2;                  // tiles per wave (the last odd one may not exist)
     // position v in the walk -> tile index (this split's prefix tiles, then the tree tiles of the set)
     auto tile_of = [=](int v) __attribute__((always_inline)) -> int {
-        if (v < nPl) return p_begin + v;
-        const int k = v - nPl;
-        if (k >= nAct) return nT;
-        uint32_t m = active;
-        for (int j = 0; j < k; ++j) m &= m - 1u;
-        return nTp + __builtin_ctz(m);
+        return v < nPl ? p_begin + v : kth_tile(active, v - nPl);
     };
     // first product of the lower half of tile 0 (K slot 0) into S[0]
     half_step(std::false_type{}, std::true_type{}, std::false_type{}, std::false_type{}, std::false_type{},

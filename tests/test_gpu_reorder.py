@@ -131,3 +131,28 @@ def test_attention_on_the_renamed_tree_is_the_permuted_result(dy, nodes, prefix,
         want = oracle_attention_rows(*host, mask, batch, s, scale, rj, rh).reshape(n, Hq, d)
         err = np.abs(got[a:a + n] - want[order[a:a + n]]).max()
         assert err <= ATTN_TOL["bf16"], f"sequence {s}: max abs error {err}"
+
+
+def test_verification_of_the_renamed_tree_gives_the_same_tokens(dy):
+    # draws are named by paths of sibling ranks and rows travel with their nodes, so the walk
+    # over the renamed tree accepts the same nodes and emits the same token
+    rng = np.random.default_rng(11)
+    nodes, V = (150, 60), 3000
+    batch = dy.Batch.from_sizes(nodes)
+    d = (rng.standard_normal((sum(nodes), V)) * 3.0).astype(np.float32)
+    t = (d + rng.standard_normal((sum(nodes), V)) * 0.8).astype(np.float32)
+    dd, tt = torch.from_numpy(d).cuda(), torch.from_numpy(t).cuda()
+    temps = (0.7, 1.0)
+    for seed in range(6):
+        built = dy.build_tree(dd, batch, temps, seed)
+        re = dy.dfs_reorder(built.tree, batch)
+        idx = re.gather_index(batch)
+        a = dy.verify(dd, tt, batch, built.tree, temps, temps, seed)
+        b = dy.verify(dd[idx].contiguous(), tt[idx].contiguous(), batch, re.tree, temps, temps, seed)
+        torch.cuda.synchronize()
+        assert torch.equal(a.n_accepted, b.n_accepted) and torch.equal(a.final_token, b.final_token)
+        order = re.order.cpu().numpy()
+        acc_a, acc_b = a.accepted_nodes.cpu().numpy(), b.accepted_nodes.cpu().numpy()
+        for s in range(batch.n_seq):
+            off, k = int(batch.node_offset[s]), int(a.n_accepted[s])
+            assert order[off + acc_b[off:off + k]].tolist() == acc_a[off:off + k].tolist()

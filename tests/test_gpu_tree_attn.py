@@ -142,6 +142,13 @@ def test_bf16_prefix_split_matches_unsplit_and_oracle(dy, nodes, prefix, Hq, Hkv
     run_and_compare(dy, nodes, prefix, Hq, Hkv, 128, "bf16", 21)
 
 
+def test_bf16_tree_only_large_trees(dy):
+    # no prefix and a short one ahead of sixteen tree tiles: the tile set is agreed on before the first loads
+    run_and_compare(dy, (1024,), (0,), 8, 1, 128, "bf16", 16)
+    run_and_compare(dy, (1024, 640), (0, 100), 4, 4, 128, "bf16", 17, shallow=True)
+    run_and_compare(dy, (900,), (130,), 8, 8, 64, "bf16", 18, shallow=True)
+
+
 def test_bf16_chain_tree_is_causal(dy):
     run_and_compare(dy, (130,), (70,), 4, 2, 128, "bf16", 11, chain=True)
 
