@@ -25,7 +25,8 @@
  * Pins (see tests/test_oracle_*.py): Philox known answers; closed form of every slot
  * value (Appendix D); greedy = max-weight connected subtree (Appendix D.1); chain tree
  * = causal attention; one child = plain speculative sampling (Section 2); exact output
- * law on trees of 1-4 nodes; 10^6-trial marginals at V = 8.
+ * law on trees of 1-4 nodes; 10^6-trial marginals at V = 8; a temperature-0 target =
+ * the limit of small temperatures = following the target's argmax token down the tree.
  * The sample PATH for a given seed (which token, which accept) is fixed by this
  * file's own conventions (inverse CDF in ascending token order, the counter layout)
  * and is "parity unpinned" by the paper.
@@ -119,9 +120,20 @@ double oracle_u01(uint64_t seed, uint32_t pk_lo, uint32_t pk_hi, uint32_t rank, 
 /* ------------------------------------------------------------------ softmax rows */
 
 /* p = softmax(logits / temp) in fp64; returns m = max(logits)/temp and writes
- * s = sum exp(logits/temp - m). */
+ * s = sum exp(logits/temp - m).
+ * temp == 0 is the limit temp -> 0+ (Section 5, the temperature-0 target rows of the
+ * result tables): all mass on the largest logit, the smallest index winning a tie.  Then
+ * the return value is that largest raw logit and s is the index that holds it. */
 static double softmax_row(const float* logits, int V, double temp, double* p, double* s_out)
 {
+    if (temp == 0.0) {
+        int a = 0;
+        for (int x = 1; x < V; ++x) if (logits[x] > logits[a]) a = x;
+        for (int x = 0; x < V; ++x) p[x] = 0.0;
+        p[a] = 1.0;
+        if (s_out) *s_out = (double)a;
+        return (double)logits[a];
+    }
     double m = -INFINITY;
     for (int x = 0; x < V; ++x) { double z = (double)logits[x] / temp; if (z > m) m = z; }
     double s = 0.0;
@@ -136,7 +148,8 @@ void oracle_softmax(const float* logits, int V, double temp, double* p)
     softmax_row(logits, V, temp, p, NULL);
 }
 
-/* stats[4*i + {0,1,2,3}] = (max_d, sumexp_d, max_t, sumexp_t) for row i */
+/* stats[4*i + {0,1,2,3}] = (max_d, sumexp_d, max_t, sumexp_t) for row i; at temp_t == 0
+ * the last two are (largest raw target logit, its index) */
 void oracle_softmax_stats(const float* draft_logits, const float* target_logits, int n_rows,
                           int V, double temp_d, double temp_t, double* stats)
 {
