@@ -122,6 +122,9 @@ def main() -> int:
     ap.add_argument("--tree-only-sweep", action="store_true",
                     help="instead of the step benchmark: tree-only attention (64 heads, head_dim 128, no prefix) on random "
                          "and greedy trees of 256..1024 nodes, creation order against depth-first order")
+    ap.add_argument("--target-temp", type=float, default=None,
+                    help="target temperature of every sequence in verification (0 = the paper's temperature-0 "
+                         "target); default: the workload's own temperatures, as for the draft")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the two measured ceilings (MFMA-only loop, streaming HBM read)")
     args = ap.parse_args()
@@ -144,6 +147,7 @@ def main() -> int:
     if args.tree_only_sweep:
         return tree_only_sweep(dy, synth, torch, np, dev)
     cfg = synth.CONFIGS[args.workload]
+    target_temps = cfg.temps if args.target_temp is None else (args.target_temp,) * len(cfg.n_nodes)
     batch = dy.Batch.from_sizes(cfg.n_nodes, cfg.prefix_len)
     n_tokens = batch.total_nodes
     scale = 1.0 / math.sqrt(cfg.head_dim)
@@ -167,7 +171,7 @@ def main() -> int:
             dy.tree_attn(q, kp, vp, kt, vt, built.anc_mask, batch, scale, out=outs[l])
         if ev:
             ev[1].record()
-        dy.verify(draft, target, batch, built.tree, cfg.temps, cfg.temps, cfg.seed, out=vout)
+        dy.verify(draft, target, batch, built.tree, cfg.temps, target_temps, cfg.seed, out=vout)
         if ev:
             ev[2].record()
 
@@ -281,7 +285,7 @@ def main() -> int:
         for s, n in enumerate(cfg.n_nodes):
             tr = {k: getattr(built.tree, k).cpu().numpy()[off:off + n] for k in ("token", "first_child", "next_sibling")}
             oracle.verify(draft_h[off:off + n], target_h[off:off + n], tr["token"], tr["first_child"],
-                          tr["next_sibling"], float(np.float32(cfg.temps[s])), float(np.float32(cfg.temps[s])),
+                          tr["next_sibling"], float(np.float32(cfg.temps[s])), float(np.float32(target_temps[s])),
                           cfg.seed, seq=s)
             off += n
         t_verify = time.perf_counter() - t
@@ -299,8 +303,10 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: {cfg.layers} layers, {cfg.n_q_heads}q/{cfg.n_kv_heads}kv heads, "
                                f"head_dim {cfg.head_dim}, prefix {list(cfg.prefix_len)}, tree rows {list(cfg.n_nodes)}, "
                                f"vocab {cfg.vocab}, batch {batch.n_seq}",
+                   "draft_temp": [float(x) for x in cfg.temps], "target_temp": [float(x) for x in target_temps],
                    "tree_rows_built": [int(x) for x in n_built], "max_depth": int(depth.max())},
         "attn_ms_per_step": round(attn_ms, 4), "verify_ms_per_step": round(verify_ms, 4),
+        "n_accepted": [int(x) for x in vout.n_accepted.cpu().numpy()],
         "pct_hbm_peak": round(100.0 * hbm_gbs / PEAK_HBM_GBS, 2), "algorithmic_gbs": round(hbm_gbs, 1),
         "roofline": roofline, "cpu_baseline": cpu, "ceilings": ceilings,
     }

@@ -184,11 +184,17 @@ dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* 
  * walk reaches a leaf sample it from the leaf's target row if emit_bonus != 0 (the printed
  * algorithm returns without it: final_token = -1).  The final token is the smallest index
  * whose cumulative probability exceeds u * (total), u in [0,1) with 24 random bits.
+ * target_temp[s] == 0 (the temperature-0 target of Section 5's tables) is the limit
+ * T_t -> 0+: R is all mass on the largest target logit of the row, the smallest index
+ * winning a tie, so the walk follows the target's argmax token down the tree and the last
+ * token is the argmax of the row where it stops; the draws are still taken, in the same order.
  *
  *   draft_logits, target_logits DEVICE [sum N, vocab] fp32 (row i = distribution after node i)
- *   draft_temp, target_temp     HOST [n_seq] > 0
+ *   draft_temp                  HOST [n_seq] > 0
+ *   target_temp                 HOST [n_seq] >= 0, independent of draft_temp
  *   tree                        DEVICE inputs (token, first_child, next_sibling are read)
  *   row_stats    DEVICE [sum N,4] fp32: max and sum-exp of draft/T_d, then of target/T_t
+ *                (rows of a sequence with T_t == 0: largest raw target logit, then its index)
  *   accept_ratio DEVICE [sum N] fp32: R[y]/D[y] seen by every child the walk tested (root: 0;
  *                -1: not tried because the draft distribution was exhausted; -2: never reached)
  *   accepted_nodes DEVICE [sum N] i32: per sequence, from its node_offset, the accepted

@@ -173,7 +173,7 @@ dyspec_status dyspec_verify(const float* draft_logits, const float* target_logit
     if (vocab < 1) return DYSPEC_BAD_ARG;
     if (vocab > DYSPEC_MAX_VOCAB) return DYSPEC_UNSUPPORTED;
     for (int s = 0; s < sa.n_seq; ++s) {
-        if (!(draft_temp[s] > 0.0f) || !(target_temp[s] > 0.0f)) return DYSPEC_BAD_ARG;
+        if (!(draft_temp[s] > 0.0f) || !(target_temp[s] >= 0.0f)) return DYSPEC_BAD_ARG;   // target 0 = argmax row
         sa.temp_d[s] = draft_temp[s];
         sa.temp_t[s] = target_temp[s];
     }

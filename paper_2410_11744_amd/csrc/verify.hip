@@ -11,9 +11,37 @@
 // updates R <- norm(max(R-D,0)), D[y] <- 0, D <- norm(D), one workgroup reduction per
 // rejected child, stopping at the first accepted one.  Tree links and statistics of the
 // sequence are staged in LDS so the walk chases pointers there, not in HBM.
+//
+// A target temperature of 0 (the temperature-0 rows of Section 5's tables) makes the target
+// row all mass on its largest logit, the smallest index winning a tie.  For such a sequence
+// the statistics pass stores (largest raw target logit, its index) in place of (max, sum-exp)
+// and the walk builds its target row from that index instead of reading the logits; every
+// other step of Algorithm 3 runs unchanged.
 #include "vocab_common.h"
 
 namespace dyspec {
+
+// (value, index) pairs ordered by larger value, then smaller index
+__device__ __forceinline__ void better_of(float& m, int& i, float m2, int i2)
+{
+    if (m2 > m || (m2 == m && i2 < i)) { m = m2; i = i2; }
+}
+
+// Largest value and the first index holding it over a workgroup of NW waves; every thread
+// brings its own best pair.  The result is valid in thread 0.
+template <int NW>
+__device__ __forceinline__ void block_argmax(float& m, int& i, float* red_m, int* red_i)
+{
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) better_of(m, i, __shfl_xor(m, o, kWave), __shfl_xor(i, o, kWave));
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) { red_m[wave] = m; red_i[wave] = i; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = red_m[0]; i = red_i[0];
+        for (int w = 1; w < NW; ++w) better_of(m, i, red_m[w], red_i[w]);
+    }
+}
 
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void softmax_stats_kernel(
@@ -21,12 +49,25 @@ __global__ __launch_bounds__(kBlock) void softmax_stats_kernel(
     SeqArgs sa, float* __restrict__ row_stats, float* __restrict__ accept_ratio)
 {
     __shared__ float fred[kWaves * 2];
+    __shared__ int ired[kWaves];
     const int row = blockIdx.x;
     const int seq = find_seq(sa, row);
-    const float inv_td = 1.0f / sa.temp_d[seq], inv_tt = 1.0f / sa.temp_t[seq];
+    const bool greedy = sa.temp_t[seq] == 0.0f;
+    const float inv_td = 1.0f / sa.temp_d[seq], inv_tt = greedy ? 1.0f : 1.0f / sa.temp_t[seq];
     float D[kMaxSeg][4], R[kMaxSeg][4];
     load_row<VEC>(draft_logits + (size_t)row * V, V, D);
     load_row<VEC>(target_logits + (size_t)row * V, V, R);
+    float top = -INFINITY;
+    int top_i = 0;
+    if (greedy) {
+#pragma unroll
+        for (int j = 0; j < kMaxSeg; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (R[j][e] > top) { top = R[j][e]; top_i = tok_index(j, e); }   // ascending index per thread
+        block_argmax<kWaves>(top, top_i, fred, ired);
+        __syncthreads();
+    }
     float mx[2] = { -INFINITY, -INFINITY };
 #pragma unroll
     for (int j = 0; j < kMaxSeg; ++j)
@@ -45,7 +86,8 @@ __global__ __launch_bounds__(kBlock) void softmax_stats_kernel(
         }
     block_sum<float, 2>(sm, fred);
     if (threadIdx.x == 0) {
-        *reinterpret_cast<float4*>(row_stats + 4 * (size_t)row) = make_float4(mx[0], sm[0], mx[1], sm[1]);
+        *reinterpret_cast<float4*>(row_stats + 4 * (size_t)row) =
+            greedy ? make_float4(mx[0], sm[0], top, (float)top_i) : make_float4(mx[0], sm[0], mx[1], sm[1]);
         accept_ratio[row] = (row == sa.node_off[seq]) ? 0.0f : -2.0f;      // -2: not tested by the walk
     }
 }
@@ -75,10 +117,35 @@ __global__ __launch_bounds__(kStatThreads) void softmax_stats_stream_kernel(
     __shared__ float red[2 * (kStatThreads / kWave)];
     const int row = blockIdx.x, table = blockIdx.y;
     const int seq = find_seq(sa, row);
-    const float inv_t = 1.0f / (table ? sa.temp_t[seq] : sa.temp_d[seq]);
-    const float c = inv_t * 1.4426950408889634f;
     const float4* __restrict__ x = reinterpret_cast<const float4*>((table ? target_logits : draft_logits) + (size_t)row * V);
     const int n4 = V / 4;
+    if (table == 1 && sa.temp_t[seq] == 0.0f) {                  // whole workgroup takes this branch
+        __shared__ int ired[kStatThreads / kWave];
+        float top = -INFINITY;
+        int top_i = 0;
+        for (int i0 = threadIdx.x; i0 < n4; i0 += kStatThreads * kStatUnroll) {
+            float4 v[kStatUnroll];
+#pragma unroll
+            for (int u = 0; u < kStatUnroll; ++u) {
+                const int i = i0 + u * kStatThreads;
+                v[u] = (i < n4) ? x[i] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            }
+#pragma unroll
+            for (int u = 0; u < kStatUnroll; ++u) {              // ascending index per thread
+                const int i = 4 * (i0 + u * kStatThreads);
+                if (v[u].x > top) { top = v[u].x; top_i = i; }
+                if (v[u].y > top) { top = v[u].y; top_i = i + 1; }
+                if (v[u].z > top) { top = v[u].z; top_i = i + 2; }
+                if (v[u].w > top) { top = v[u].w; top_i = i + 3; }
+            }
+        }
+        block_argmax<kStatThreads / kWave>(top, top_i, red, ired);
+        if (threadIdx.x == 0)
+            *reinterpret_cast<float2*>(row_stats + 4 * (size_t)row + 2) = make_float2(top, (float)top_i);
+        return;
+    }
+    const float inv_t = 1.0f / (table ? sa.temp_t[seq] : sa.temp_d[seq]);
+    const float c = inv_t * 1.4426950408889634f;
     float m = -INFINITY, s = 0.0f;
     for (int i0 = threadIdx.x; i0 < n4; i0 += kStatThreads * kStatUnroll) {
         float4 v[kStatUnroll];
@@ -139,7 +206,8 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
     const int seq = blockIdx.x;
     const int base = sa.node_off[seq];
     const int N = sa.node_off[seq + 1] - base;
-    const float inv_td = 1.0f / sa.temp_d[seq], inv_tt = 1.0f / sa.temp_t[seq];
+    const bool greedy = sa.temp_t[seq] == 0.0f;                  // target row = all mass on stats.w
+    const float inv_td = 1.0f / sa.temp_d[seq], inv_tt = greedy ? 1.0f : 1.0f / sa.temp_t[seq];
     for (int i = tid; i < N; i += kBlock) {
         sh.token[i] = tree.token[base + i];
         sh.first_child[i] = tree.first_child[base + i];
@@ -152,7 +220,8 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
     auto prob_pair = [&](int node, int y) {
         const float4 st = sh.stats[node];
         const float d = expf(draft_logits[(size_t)(base + node) * V + y] * inv_td - st.x) / st.y;
-        const float r = expf(target_logits[(size_t)(base + node) * V + y] * inv_tt - st.z) / st.w;
+        const float r = greedy ? ((float)y == st.w ? 1.0f : 0.0f)
+                               : expf(target_logits[(size_t)(base + node) * V + y] * inv_tt - st.z) / st.w;
         return make_float2(d, r);
     };
     auto ratio_of = [](float d, float r) { return (d > 0.0f) ? r / d : (r > 0.0f ? INFINITY : 0.0f); };
@@ -169,14 +238,15 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
         float D[kMaxSeg][4], R[kMaxSeg][4];
         auto load_rows = [&](bool want_draft) {
             const float4 st = sh.stats[cur];
-            load_row<VEC>(target_logits + (size_t)(base + cur) * V, V, R);
+            if (!greedy) load_row<VEC>(target_logits + (size_t)(base + cur) * V, V, R);
             if (want_draft) load_row<VEC>(draft_logits + (size_t)(base + cur) * V, V, D);
-            const float id = 1.0f / st.y, it = 1.0f / st.w;
+            const float id = 1.0f / st.y, it = greedy ? 0.0f : 1.0f / st.w;
+            const int top = greedy ? (int)st.w : -1;
 #pragma unroll
             for (int j = 0; j < kMaxSeg; ++j)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    R[j][e] = expf(R[j][e] * inv_tt - st.z) * it;
+                    R[j][e] = greedy ? (tok_index(j, e) == top ? 1.0f : 0.0f) : expf(R[j][e] * inv_tt - st.z) * it;
                     D[j][e] = want_draft ? expf(D[j][e] * inv_td - st.x) * id : 0.0f;
                 }
         };
