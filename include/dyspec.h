@@ -170,6 +170,33 @@ dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* 
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * dyspec_tree_attn_layers -- dyspec_tree_attn for n_layers stacked layers in one call
+ * (the same operation as above, Section 2 "Tree Attention", once per layer; the tree and
+ * its mask are the same in every layer of one speculative step, the tensors are not).
+ * Layer l reads q, k_prefix/v_prefix and k_tree/v_tree at element offsets l * q_layer_stride,
+ * l * kv_prefix_layer_stride and l * kv_tree_layer_stride from the base pointers and writes
+ * out at l * q_layer_stride; within a layer the layout is that of dyspec_tree_attn.  Strides
+ * are >= 0 and keep every layer 16-byte aligned.  The bf16 matrix-core path runs all layers
+ * in ONE launch (workgroups of all layers fill the chip together, so short prefixes need
+ * no split and pay one launch latency); other dtypes launch once per layer.  This is for
+ * callers that hold all layers' tensors at once (benchmarks, layer-parallel schedules);
+ * a model that computes layer l+1's Q from layer l's output calls dyspec_tree_attn.
+ *   workspace  as for dyspec_tree_attn, dyspec_tree_attn_layers_workspace_bytes() bytes.
+ *   n_layers   1 .. 65535
+ */
+dyspec_status dyspec_tree_attn_layers(const void* q, const void* k_prefix, const void* v_prefix,
+                                      const void* k_tree, const void* v_tree,
+                                      const uint64_t* anc_mask, const dyspec_batch* batch,
+                                      int32_t n_layers, int64_t q_layer_stride,
+                                      int64_t kv_prefix_layer_stride, int64_t kv_tree_layer_stride,
+                                      int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                      int32_t dtype, float softmax_scale, void* out,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t dyspec_tree_attn_layers_workspace_bytes(const dyspec_batch* batch, int32_t n_layers,
+                                               int32_t n_q_heads, int32_t n_kv_heads,
+                                               int32_t head_dim);
+
+/*
  * dyspec_verify -- vocabulary softmax of every tree row and multi-candidate tree
  * rejection sampling (Algorithm 3; Appendix A.3; Section 2 for the one-candidate rule).
  *

@@ -19,7 +19,8 @@ F32, BF16, BF16_WAVE = 0, 1, 0x101
 MAX_SEQ, MAX_NODES, MAX_VOCAB = 64, 1024, 32768
 WS_BUILD_TREE, WS_TREE_ATTN, WS_VERIFY = 0, 1, 2
 EXPORTS = ("dyspec_mask_words", "dyspec_workspace_bytes", "dyspec_status_string",
-           "dyspec_build_tree", "dyspec_dfs_reorder", "dyspec_tree_attn", "dyspec_verify",
+           "dyspec_build_tree", "dyspec_dfs_reorder", "dyspec_tree_attn", "dyspec_tree_attn_layers",
+           "dyspec_tree_attn_layers_workspace_bytes", "dyspec_verify",
            "dyspec_probe_mfma_bf16", "dyspec_probe_hbm_read")
 
 
@@ -65,6 +66,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.dyspec_build_tree.argtypes = [V, I32, PB, ctypes.POINTER(F), U64, PT, V, V, V, V, SZ, V]
     lib.dyspec_tree_attn.restype = I32
     lib.dyspec_tree_attn.argtypes = [V, V, V, V, V, V, PB, I32, I32, I32, I32, F, V, V, SZ, V]
+    lib.dyspec_tree_attn_layers.restype = I32
+    lib.dyspec_tree_attn_layers.argtypes = [V, V, V, V, V, V, PB, I32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                            I32, I32, I32, I32, F, V, V, SZ, V]
+    lib.dyspec_tree_attn_layers_workspace_bytes.restype = SZ
+    lib.dyspec_tree_attn_layers_workspace_bytes.argtypes = [PB, I32, I32, I32, I32]
     lib.dyspec_verify.restype = I32
     lib.dyspec_verify.argtypes = [V, V, I32, PB, PT, ctypes.POINTER(F), ctypes.POINTER(F), U64, I32,
                                   V, V, V, V, V, V, V, SZ, V]
@@ -112,19 +118,36 @@ class Batch:
     def total_prefix(self) -> int:
         return int(self.kv_offset[-1])
 
+    def _memo(self) -> dict:
+        """Per-content cache (C struct, mask words, workspace sizes): calls in a layer loop
+        describe the same batch again and again."""
+        key = (self.node_offset.tobytes(), self.prefix_len.tobytes(), self.kv_offset.tobytes())
+        memo = self.__dict__.get("_memo_store")
+        if memo is None or memo["key"] != key:
+            memo = {"key": key}
+            self.__dict__["_memo_store"] = memo
+        return memo
+
     def _c(self) -> _Batch:
-        self.node_offset = np.ascontiguousarray(self.node_offset, dtype=np.int32)
-        self.prefix_len = np.ascontiguousarray(self.prefix_len, dtype=np.int32)
-        self.kv_offset = np.ascontiguousarray(self.kv_offset, dtype=np.int64)
-        return _Batch(self.n_seq,
-                      self.node_offset.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-                      self.prefix_len.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-                      self.kv_offset.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)))
+        memo = self._memo()
+        c = memo.get("c")
+        if c is None:
+            no = np.ascontiguousarray(self.node_offset, dtype=np.int32)
+            pl = np.ascontiguousarray(self.prefix_len, dtype=np.int32)
+            kv = np.ascontiguousarray(self.kv_offset, dtype=np.int64)
+            c = _Batch(self.n_seq,
+                       no.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                       pl.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                       kv.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)))
+            memo["c"], memo["keep"] = c, (no, pl, kv)          # the struct points into these copies
+        return c
 
     @property
     def mask_words(self) -> int:
-        c = self._c()
-        return int(load_library().dyspec_mask_words(ctypes.byref(c)))
+        memo = self._memo()
+        if "mask_words" not in memo:
+            memo["mask_words"] = int(load_library().dyspec_mask_words(ctypes.byref(self._c())))
+        return memo["mask_words"]
 
 
 @dataclass
@@ -161,8 +184,9 @@ def _ptr(t, want: Optional[str] = None) -> int:
 
 def _stream(stream=None) -> int:
     import torch
-    s = stream if stream is not None else torch.cuda.current_stream()
-    return int(s.cuda_stream)
+    if stream is not None:
+        return int(stream.cuda_stream)
+    return int(torch._C._cuda_getCurrentRawStream(torch.cuda.current_device()))
 
 
 def _temps(x, n_seq: int):
@@ -278,7 +302,10 @@ def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, sof
     cb = batch._c()
     ws, ws_bytes = None, 0
     if use_workspace and dtype == BF16:
-        ws_bytes = int(lib.dyspec_workspace_bytes(WS_TREE_ATTN, ctypes.byref(cb), 0, int(Hq), Hkv, int(d)))
+        memo, wkey = batch._memo(), ("ws_attn", int(Hq), Hkv, int(d))
+        if wkey not in memo:
+            memo[wkey] = int(lib.dyspec_workspace_bytes(WS_TREE_ATTN, ctypes.byref(cb), 0, int(Hq), Hkv, int(d)))
+        ws_bytes = memo[wkey]
         if ws_bytes:
             ws = _scratch(q.device, ws_bytes)
     st = lib.dyspec_tree_attn(_ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree),
@@ -286,6 +313,53 @@ def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, sof
                               ctypes.c_float(softmax_scale), _ptr(out), _ptr(ws) if ws is not None else None,
                               ctypes.c_size_t(ws_bytes), _stream(stream))
     _check(st, "dyspec_tree_attn")
+    return out
+
+
+def tree_attn_layers(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, softmax_scale: float,
+                     out=None, dtype: Optional[int] = None, stream=None, use_workspace: bool = True):
+    """dyspec_tree_attn_layers: tree-masked attention of L stacked layers in one call.
+    q/out [L, sum N, Hq, d], k_prefix/v_prefix [L, kv rows, Hkv, d], k_tree/v_tree [L, sum N, Hkv, d];
+    the leading dimension may be strided, the rest is dense."""
+    import torch
+    lib = load_library()
+    L, total, Hq, d = q.shape
+    Hkv = int(k_tree.shape[2])
+    if dtype is None:
+        dtype = {torch.float32: F32, torch.bfloat16: BF16}[q.dtype]
+    if total != batch.total_nodes or tuple(k_tree.shape) != (L, total, Hkv, d) or v_tree.shape != k_tree.shape:
+        raise ValueError("q / k_tree / v_tree need one row per tree node and layer")
+    if batch.total_prefix > 0 and (k_prefix.shape[0] != L or k_prefix.shape[1] < batch.total_prefix or k_prefix.shape[2] != Hkv
+                                   or k_prefix.shape[3] != d or v_prefix.shape != k_prefix.shape):
+        raise ValueError("prefix K/V shape does not match the batch")
+    if anc_mask.shape[0] != total or anc_mask.shape[1] != batch.mask_words:
+        raise ValueError("ancestor mask shape does not match the batch")
+    if out is None:
+        out = torch.empty_like(q)
+    for t in (q, out, k_prefix, v_prefix, k_tree, v_tree):
+        if t is None:
+            continue
+        if t.dtype != q.dtype:
+            raise ValueError("q, k, v, out must share a dtype")
+        if not t.is_cuda or not t[0].is_contiguous():
+            raise ValueError("device tensors with dense layers required")
+    if out.stride(0) != q.stride(0) or (k_prefix is not None and v_prefix.stride(0) != k_prefix.stride(0)) \
+            or v_tree.stride(0) != k_tree.stride(0):
+        raise ValueError("q/out, k_prefix/v_prefix and k_tree/v_tree must share their layer strides")
+    cb = batch._c()
+    ws, ws_bytes = None, 0
+    if use_workspace and dtype == BF16:
+        ws_bytes = int(lib.dyspec_tree_attn_layers_workspace_bytes(ctypes.byref(cb), int(L), int(Hq), Hkv, int(d)))
+        if ws_bytes:
+            ws = _scratch(q.device, ws_bytes)
+    kp_stride = int(k_prefix.stride(0)) if k_prefix is not None else 0
+    base = lambda t: 0 if t is None else t.data_ptr()          # the layer dimension may be strided
+    st = lib.dyspec_tree_attn_layers(base(q), base(k_prefix), base(v_prefix), base(k_tree), base(v_tree),
+                                     _ptr(anc_mask, "int64"), ctypes.byref(cb), int(L), int(q.stride(0)), kp_stride,
+                                     int(k_tree.stride(0)), int(Hq), Hkv, int(d), int(dtype),
+                                     ctypes.c_float(softmax_scale), base(out), _ptr(ws) if ws is not None else None,
+                                     ctypes.c_size_t(ws_bytes), _stream(stream))
+    _check(st, "dyspec_tree_attn_layers")
     return out
 
 

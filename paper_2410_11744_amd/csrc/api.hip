@@ -66,9 +66,19 @@ size_t dyspec_workspace_bytes(int32_t which, const dyspec_batch* batch, int32_t,
         if (check_batch(batch, true, &sa) != DYSPEC_OK || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads != 0 ||
             (head_dim != 64 && head_dim != 128))
             return 0;
-        return tree_attn_workspace_bytes(sa, n_q_heads, n_kv_heads, head_dim);
+        return tree_attn_workspace_bytes(sa, n_q_heads, n_kv_heads, head_dim, 1);
     }
     return 0;
+}
+
+size_t dyspec_tree_attn_layers_workspace_bytes(const dyspec_batch* batch, int32_t n_layers, int32_t n_q_heads,
+                                               int32_t n_kv_heads, int32_t head_dim)
+{
+    SeqArgs sa;
+    if (check_batch(batch, true, &sa) != DYSPEC_OK || n_layers < 1 || n_q_heads < 1 || n_kv_heads < 1 ||
+        n_q_heads % n_kv_heads != 0 || (head_dim != 64 && head_dim != 128))
+        return 0;
+    return tree_attn_workspace_bytes(sa, n_q_heads, n_kv_heads, head_dim, n_layers);
 }
 
 const char* dyspec_status_string(dyspec_status s)
@@ -120,11 +130,13 @@ dyspec_status dyspec_dfs_reorder(const dyspec_batch* batch, const dyspec_tree* t
     return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
 }
 
-dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* v_prefix,
-                               const void* k_tree, const void* v_tree, const uint64_t* anc_mask,
-                               const dyspec_batch* batch, int32_t n_q_heads, int32_t n_kv_heads,
-                               int32_t head_dim, int32_t dtype, float softmax_scale, void* out,
-                               void* workspace, size_t workspace_bytes, void* hip_stream)
+// Shared body of the one-layer and the stacked-layers call.  Strides are in bytes.
+static dyspec_status tree_attn_common(const void* q, const void* k_prefix, const void* v_prefix,
+                                      const void* k_tree, const void* v_tree, const uint64_t* anc_mask,
+                                      const dyspec_batch* batch, int32_t n_layers, long long q_stride,
+                                      long long kvp_stride, long long kvt_stride, int32_t n_q_heads,
+                                      int32_t n_kv_heads, int32_t head_dim, int32_t dtype, float softmax_scale,
+                                      void* out, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     SeqArgs sa;
     const dyspec_status st = check_batch(batch, true, &sa);
@@ -152,9 +164,51 @@ dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* 
     a.mask_words = mask_words_of(batch);
     a.Hq = n_q_heads; a.Hkv = n_kv_heads; a.d = head_dim; a.scale = softmax_scale;
     a.splits = 1; a.part_rows = 0; a.part_acc = nullptr; a.part_ml = nullptr;
-    const hipError_t e = launch_tree_attn(a, sa, dtype, force_simple, workspace, workspace_bytes,
-                                          static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
+    a.layers = n_layers; a.q_stride = q_stride; a.kvp_stride = kvp_stride; a.kvt_stride = kvt_stride;
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool one_launch = dtype == DYSPEC_BF16 && !force_simple;      // the matrix-core kernel takes a layer plane
+    if (one_launch || n_layers == 1)
+        return launch_tree_attn(a, sa, dtype, force_simple, workspace, workspace_bytes, stream) == hipSuccess
+                   ? DYSPEC_OK : DYSPEC_HIP_ERROR;
+    auto at = [](const void* p, long long off) { return p ? static_cast<const char*>(p) + off : nullptr; };
+    for (int l = 0; l < n_layers; ++l) {                                 // the per-wave kernels: one launch per layer
+        AttnArgs b = a;
+        b.layers = 1;
+        b.q = at(q, l * q_stride); b.out = static_cast<char*>(out) + l * q_stride;
+        b.kp = at(k_prefix, l * kvp_stride); b.vp = at(v_prefix, l * kvp_stride);
+        b.kt = at(k_tree, l * kvt_stride); b.vt = at(v_tree, l * kvt_stride);
+        if (launch_tree_attn(b, sa, dtype, force_simple, nullptr, 0, stream) != hipSuccess) return DYSPEC_HIP_ERROR;
+    }
+    return DYSPEC_OK;
+}
+
+dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* v_prefix,
+                               const void* k_tree, const void* v_tree, const uint64_t* anc_mask,
+                               const dyspec_batch* batch, int32_t n_q_heads, int32_t n_kv_heads,
+                               int32_t head_dim, int32_t dtype, float softmax_scale, void* out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return tree_attn_common(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch, 1, 0, 0, 0, n_q_heads,
+                            n_kv_heads, head_dim, dtype, softmax_scale, out, workspace, workspace_bytes, hip_stream);
+}
+
+dyspec_status dyspec_tree_attn_layers(const void* q, const void* k_prefix, const void* v_prefix,
+                                      const void* k_tree, const void* v_tree, const uint64_t* anc_mask,
+                                      const dyspec_batch* batch, int32_t n_layers, int64_t q_layer_stride,
+                                      int64_t kv_prefix_layer_stride, int64_t kv_tree_layer_stride,
+                                      int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int32_t dtype,
+                                      float softmax_scale, void* out, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream)
+{
+    if (n_layers < 1 || n_layers > 65535) return DYSPEC_BAD_SHAPE;
+    if (q_layer_stride < 0 || kv_prefix_layer_stride < 0 || kv_tree_layer_stride < 0) return DYSPEC_BAD_ARG;
+    const long long elt = dtype == DYSPEC_F32 ? 4 : 2;
+    // every layer's tensors stay 16-byte aligned
+    if ((q_layer_stride * elt) % 16 || (kv_prefix_layer_stride * elt) % 16 || (kv_tree_layer_stride * elt) % 16)
+        return DYSPEC_BAD_ARG;
+    return tree_attn_common(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch, n_layers, q_layer_stride * elt,
+                            kv_prefix_layer_stride * elt, kv_tree_layer_stride * elt, n_q_heads, n_kv_heads,
+                            head_dim, dtype, softmax_scale, out, workspace, workspace_bytes, hip_stream);
 }
 
 dyspec_status dyspec_verify(const float* draft_logits, const float* target_logits, int32_t vocab,

@@ -38,6 +38,11 @@ struct AttnArgs {
     long long part_rows;                   // total rows * Hq
     float* part_acc;                       // [splits][total rows * Hq][d] fp32
     float* part_ml;                        // [splits][total rows * Hq][2] fp32
+    // stacked layers (matrix-core kernel): layer l = blockIdx.z reads q/out, prefix K/V and
+    // tree K/V at byte offsets l * stride from the base pointers; the mask is shared.  With
+    // layers > 1 the partial buffers are [layers][splits][...].
+    int layers;
+    long long q_stride, kvp_stride, kvt_stride;
 };
 
 // Launchers (one per source file); each returns the launch status.
@@ -55,8 +60,8 @@ hipError_t launch_tree_attn(AttnArgs a, const SeqArgs& sa, int dtype, bool per_w
                             hipStream_t stream);
 hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, void* workspace, size_t workspace_bytes, hipStream_t stream);
 // splits the matrix-core kernel would like for this batch, and the workspace that takes
-int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv);
-size_t tree_attn_workspace_bytes(const SeqArgs& sa, int Hq, int Hkv, int d);
+int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv, int layers);
+size_t tree_attn_workspace_bytes(const SeqArgs& sa, int Hq, int Hkv, int d, int layers);
 
 enum : uint32_t { KIND_PATH = 0, KIND_BUILD = 1, KIND_ACCEPT = 2, KIND_RESID = 3 };
 

@@ -37,6 +37,7 @@
 // transposing V reads of a wave spread over all 64 banks.
 #include <utility>
 
+#include <atomic>
 #include "dyspec_device.h"
 
 namespace dyspec {
@@ -164,10 +165,14 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     const int nT = nTp + nTt;                              // a tile index >= nT stands for "no tile"
 
     const size_t kv_row_bytes = (size_t)a.Hkv * D * 2;
-    const char* kp = static_cast<const char*>(a.kp) + (size_t)sa.kv_off[seq] * kv_row_bytes + (size_t)kvh * D * 2;
-    const char* vp = static_cast<const char*>(a.vp) + (size_t)sa.kv_off[seq] * kv_row_bytes + (size_t)kvh * D * 2;
-    const char* kt = static_cast<const char*>(a.kt) + (size_t)node_base * kv_row_bytes + (size_t)kvh * D * 2;
-    const char* vt = static_cast<const char*>(a.vt) + (size_t)node_base * kv_row_bytes + (size_t)kvh * D * 2;
+    const int layer = blockIdx.z;                          // stacked layers: one grid plane each
+    const size_t kvp_off = (size_t)layer * a.kvp_stride + (size_t)sa.kv_off[seq] * kv_row_bytes + (size_t)kvh * D * 2;
+    const size_t kvt_off = (size_t)layer * a.kvt_stride + (size_t)node_base * kv_row_bytes + (size_t)kvh * D * 2;
+    const char* kp = static_cast<const char*>(a.kp) + kvp_off;
+    const char* vp = static_cast<const char*>(a.vp) + kvp_off;
+    const char* kt = static_cast<const char*>(a.kt) + kvt_off;
+    const char* vt = static_cast<const char*>(a.vt) + kvt_off;
+    const __bf16* q_layer = reinterpret_cast<const __bf16*>(static_cast<const char*>(a.q) + (size_t)layer * a.q_stride);
 
     // ---- Q fragments (B operand: lane holds query n, head-dim slice 16*kk + 8*g .. +7)
     bf16x8 qf[QB][KK];
@@ -178,7 +183,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         rq[qb] = r0 + 32 * QB * wq + 32 * qb + n;
         const int rc = min(rq[qb], rows - 1);
         const int j = rc / G, h = kvh * G + rc % G;
-        const __bf16* qrow = static_cast<const __bf16*>(a.q) + ((size_t)(node_base + j) * a.Hq + h) * D;
+        const __bf16* qrow = q_layer + ((size_t)(node_base + j) * a.Hq + h) * D;
         mrow[qb] = a.mask + (size_t)(node_base + j) * a.mask_words;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * g);
@@ -705,7 +710,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
             const int j = rq[qb] / G, h = kvh * G + rq[qb] % G;
             const size_t orow_index = (size_t)(node_base + j) * a.Hq + h;
             if (partial) {
-                const size_t prow = (size_t)split * a.part_rows + orow_index;
+                const size_t prow = ((size_t)layer * n_split + split) * a.part_rows + orow_index;
                 float* prow_acc = a.part_acc + prow * D;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
@@ -716,7 +721,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                 if (g == 0) *reinterpret_cast<float2*>(a.part_ml + prow * 2) = make_float2(m_all[qb], l_all[qb]);
                 continue;
             }
-            __bf16* orow = static_cast<__bf16*>(a.out) + orow_index * D;
+            __bf16* orow = reinterpret_cast<__bf16*>(static_cast<char*>(a.out) + (size_t)layer * a.q_stride) + orow_index * D;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -743,12 +748,13 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnArgs a, long
     const size_t row = (size_t)(idx / (D / 4));
     const int c4 = (int)(idx % (D / 4));
     const float c2 = a.scale * 1.4426950408889634f;
+    const size_t z0 = (size_t)blockIdx.y * a.splits;            // blockIdx.y: layer
     float M = -INFINITY;
-    for (int z = 0; z < a.splits; ++z) M = fmaxf(M, a.part_ml[((size_t)z * a.part_rows + row) * 2]);
+    for (int z = 0; z < a.splits; ++z) M = fmaxf(M, a.part_ml[((z0 + z) * a.part_rows + row) * 2]);
     float L = 0.0f;
     float4 o = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     for (int z = 0; z < a.splits; ++z) {
-        const size_t prow = (size_t)z * a.part_rows + row;
+        const size_t prow = (z0 + z) * a.part_rows + row;
         const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + prow * 2);
         const float w = exp2f((ml.x - M) * c2);
         const float4 v = *reinterpret_cast<const float4*>(a.part_acc + prow * D + 4 * c4);
@@ -760,19 +766,28 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnArgs a, long
     floatx2 lo = { o.x * inv, o.y * inv }, hi = { o.z * inv, o.w * inv };
     out.p[0] = __builtin_convertvector(lo, bf16x2);
     out.p[1] = __builtin_convertvector(hi, bf16x2);
-    *reinterpret_cast<uint2*>(static_cast<__bf16*>(a.out) + row * D + 4 * c4) = out.v;
+    *reinterpret_cast<uint2*>(reinterpret_cast<__bf16*>(static_cast<char*>(a.out) + (size_t)blockIdx.y * a.q_stride) + row * D + 4 * c4) = out.v;
 }
 
 template <int D, int QB>
 static hipError_t launch_one(const AttnArgs& a, const SeqArgs& sa, int tiles, hipStream_t stream)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<D, QB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Geo<D>::kLdsBytes + 16);
+    // the kernel needs more dynamic LDS than the default limit: raised once per device
+    static std::atomic<unsigned long long> raised{0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    tree_attn_mfma_kernel<D, QB><<<dim3(tiles * a.Hkv, a.splits), 64 * 2 * (4 / QB), Geo<D>::kLdsBytes + 16, stream>>>(a, sa);
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (!(raised.load(std::memory_order_acquire) & bit)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<D, QB>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, Geo<D>::kLdsBytes + 16);
+        if (e != hipSuccess) return e;
+        raised.fetch_or(bit, std::memory_order_release);
+    }
+    tree_attn_mfma_kernel<D, QB><<<dim3(tiles * a.Hkv, a.splits, a.layers), 64 * 2 * (4 / QB), Geo<D>::kLdsBytes + 16, stream>>>(a, sa);
     if (a.splits > 1) {
         const long long total = (long long)a.part_rows * (D / 4);
-        tree_attn_combine_kernel<D><<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(a, total);
+        tree_attn_combine_kernel<D><<<dim3((unsigned)((total + 255) / 256), a.layers), 256, 0, stream>>>(a, total);
     }
     return hipGetLastError();
 }
@@ -792,9 +807,9 @@ static int row_tiles(const SeqArgs& sa, int G, int* tile_off)
 // that leaves most of the 256 CUs idle (narrow trees, few KV heads) the prefix is split until
 // the workgroups fill the chip once, as long as every split keeps at least two 64-key tiles
 // (one step of the walk) of every sequence's prefix.
-int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv)
+int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv, int layers)
 {
-    const int groups = row_tiles(sa, Hq / Hkv, nullptr) * Hkv;
+    const int groups = row_tiles(sa, Hq / Hkv, nullptr) * Hkv * layers;
     if (groups == 0) return 1;
     int min_tiles = 1 << 30;
     for (int s = 0; s < sa.n_seq; ++s) min_tiles = min(min_tiles, (sa.prefix_len[s] + kKeysPerTile - 1) / kKeysPerTile);
@@ -802,25 +817,25 @@ int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv)
     return max(1, min(min(by_work, by_prefix), 32));
 }
 
-size_t tree_attn_workspace_bytes(const SeqArgs& sa, int Hq, int Hkv, int d)
+size_t tree_attn_workspace_bytes(const SeqArgs& sa, int Hq, int Hkv, int d, int layers)
 {
-    const int splits = tree_attn_splits(sa, Hq, Hkv);
+    const int splits = tree_attn_splits(sa, Hq, Hkv, layers);
     if (splits <= 1) return 0;
-    return (size_t)splits * sa.node_off[sa.n_seq] * Hq * (d + 2) * sizeof(float);
+    return (size_t)layers * splits * sa.node_off[sa.n_seq] * Hq * (d + 2) * sizeof(float);
 }
 
 hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
     const int tiles = row_tiles(sa, a.Hq / a.Hkv, a.tile_off);
     if (tiles == 0) return hipSuccess;
-    a.splits = tree_attn_splits(sa, a.Hq, a.Hkv);
+    a.splits = tree_attn_splits(sa, a.Hq, a.Hkv, a.layers);
     a.part_rows = (long long)sa.node_off[sa.n_seq] * a.Hq;
-    const size_t need = tree_attn_workspace_bytes(sa, a.Hq, a.Hkv, a.d);
+    const size_t need = tree_attn_workspace_bytes(sa, a.Hq, a.Hkv, a.d, a.layers);
     if (a.splits > 1 && (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<size_t>(workspace) & 15)))
         a.splits = 1;                                          // no room for partial results: one workgroup walks it all
     if (a.splits > 1) {
         a.part_acc = static_cast<float*>(workspace);
-        a.part_ml = a.part_acc + (size_t)a.splits * a.part_rows * a.d;
+        a.part_ml = a.part_acc + (size_t)a.layers * a.splits * a.part_rows * a.d;
     }
     return a.d == 128 ? launch_one<128, kQB>(a, sa, tiles, stream) : launch_one<64, kQB>(a, sa, tiles, stream);
 }
