@@ -351,3 +351,6 @@ def monte_carlo(draft_logits, target_logits, n_budget, temp_d, temp_t, seed0, n_
                             ctypes.c_int64(n_trials), _p(c1, ctypes.c_int64),
                             _p(c2, ctypes.c_int64), ctypes.byref(tot))
     return c1, c2, tot.value / float(n_trials)
+
+
+from .threshold import ThresholdTree, threshold_tree  # noqa: E402  (Algorithm 2; needs the definitions above)
