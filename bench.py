@@ -110,6 +110,49 @@ def tree_only_sweep(dy, synth, torch, np, dev) -> int:
     return 0
 
 
+def tree_builders(dy, synth, torch, np, dev, cfg) -> int:
+    """The two tree builders on the workload's draft table (outside the metric): the greedy fixed-budget
+    builder (Algorithm 1, N - 1 dependent draws in one workgroup per sequence) and the threshold builder
+    (Algorithm 2, every node of a level in its own workgroup), the latter at the smallest value the greedy
+    run opened and with 1.5 x the rows, as the paper relaxes the budget.  Wall time of the calls, synchronised."""
+    draft_h, _ = synth.make_logits(cfg)
+    cap = [min(n + n // 2, 1024) for n in cfg.n_nodes]
+    # rows past a sequence's own N repeat its first rows: the table only has to be large enough
+    parts, off = [], 0
+    for n, c in zip(cfg.n_nodes, cap):
+        rows = draft_h[off:off + n]
+        parts.append(np.concatenate([rows, rows[:c - n]]) if c > n else rows)
+        off += n
+    wide = torch.from_numpy(np.concatenate(parts)).to(dev)
+    draft = torch.from_numpy(draft_h).to(dev)
+    b_greedy, b_thr = dy.Batch.from_sizes(cfg.n_nodes), dy.Batch.from_sizes(cap)
+
+    def wall(fn, reps=3):
+        best, out = float("inf"), None
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            out = fn()
+            torch.cuda.synchronize()
+            best = min(best, time.perf_counter() - t)
+        return best * 1e3, out
+
+    ms_g, greedy = wall(lambda: dy.build_tree(draft, b_greedy, cfg.temps, cfg.seed))
+    est = greedy.est_value.cpu().numpy().astype(np.float64)
+    nb = greedy.n_built.cpu().numpy()
+    thr, off = [], 0
+    for n, k in zip(cfg.n_nodes, nb):
+        thr.append(float(est[off:off + k].min()))
+        off += n
+    ms_t, (built, levels) = wall(lambda: dy.build_tree_threshold(wide, b_thr, cfg.temps, thr, cfg.seed))
+    line = {"mode": "tree-builders", "workload": cfg.name, "vocab": cfg.vocab,
+            "greedy": {"rows": [int(x) for x in nb], "ms": round(ms_g, 3)},
+            "threshold": {"t": [round(x, 6) for x in thr], "capacity": cap,
+                          "rows": [int(x) for x in built.n_built.cpu().numpy()], "levels": levels, "ms": round(ms_t, 3)}}
+    print(json.dumps(line))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -130,6 +173,8 @@ def main() -> int:
                     help="attention of all layers through ONE dyspec_tree_attn_layers call per step instead of one "
                          "dyspec_tree_attn call per layer (same work; not what a model whose layers depend on each "
                          "other can do, so the default and the headline value stay per layer)")
+    ap.add_argument("--tree-builders", action="store_true",
+                    help="instead of the step benchmark: time the greedy and the threshold tree builder on the workload's draft table")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the two measured ceilings (MFMA-only loop, streaming HBM read)")
     args = ap.parse_args()
@@ -152,6 +197,8 @@ def main() -> int:
     if args.tree_only_sweep:
         return tree_only_sweep(dy, synth, torch, np, dev)
     cfg = synth.CONFIGS[args.workload]
+    if args.tree_builders:
+        return tree_builders(dy, synth, torch, np, dev, cfg)
     target_temps = cfg.temps if args.target_temp is None else (args.target_temp,) * len(cfg.n_nodes)
     batch = dy.Batch.from_sizes(cfg.n_nodes, cfg.prefix_len)
     n_tokens = batch.total_nodes

@@ -120,6 +120,42 @@ dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * dyspec_build_tree_threshold -- construction of the draft token tree with a threshold
+ * (Algorithm 2; Section 4.4, Appendix A.2), the level-by-level form of dyspec_build_tree.
+ *
+ * Per sequence, starting from the root alone (value 1): every node i of the current level
+ * with value v_i >= t reads its draft row D = softmax(draft_logits[i]/T) and, while v_i >= t
+ * and rows are left, draws y from D (inverse CDF as in dyspec_build_tree, the draw named by
+ * the node's sibling-rank path and the number of children it already has), appends a child
+ * with token y, estimated value v_i and own value v_i*D[y], then sets v_i <- v_i*(1-D[y]),
+ * D[y] <- 0, D <- norm(D).  The children of a level are the next level.  The loop condition
+ * is read as "at or above the threshold" (the listing prints the opposite sign; the text says
+ * nodes above the threshold are extended).  Rows are numbered in creation order: level by
+ * level, parents in row order, children in sampling order; construction stops when the
+ * sequence's N rows (root included) exist.  With t = the smallest est_value a run of
+ * dyspec_build_tree produced, the same tree results (Appendix A.1) when both give a node
+ * the same draft row; here a node reads the row of its own index, so the two calls agree on
+ * tables whose rows are alike.  Nodes of a level are expanded in parallel, one workgroup each.
+ *
+ *   threshold     HOST [n_seq] > 0 (the paper suggests about 1/N)
+ *   n_levels      HOST out, may be NULL: levels expanded (the number of draft model calls
+ *                 the paper's loop would make), the widest sequence counting
+ *   workspace     DEVICE, 8-byte aligned, dyspec_build_tree_threshold_workspace_bytes()
+ *                 bytes, REQUIRED (DYSPEC_WORKSPACE_TOO_SMALL otherwise)
+ *   all other arguments as for dyspec_build_tree.
+ * The call copies one small record per level back to the host and waits for it (it sizes
+ * the next level's launch), so it returns with the tree complete and cannot be captured
+ * in a graph.
+ */
+dyspec_status dyspec_build_tree_threshold(const float* draft_logits, int32_t vocab,
+                                          const dyspec_batch* batch, const float* draft_temp,
+                                          const double* threshold, uint64_t seed,
+                                          const dyspec_tree* tree, float* est_value,
+                                          uint64_t* anc_mask, int32_t* n_built, int32_t* n_levels,
+                                          void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t dyspec_build_tree_threshold_workspace_bytes(const dyspec_batch* batch);
+
+/*
  * dyspec_dfs_reorder -- block-sparsity friendly token order (Appendix "Block-Sparsity
  * Friendly Token Order"): renames the nodes of every built tree by their position in the
  * depth-first pre-order walk that visits children in sampling order.  Subtrees become

@@ -19,7 +19,8 @@ F32, BF16, BF16_WAVE = 0, 1, 0x101
 MAX_SEQ, MAX_NODES, MAX_VOCAB = 64, 1024, 32768
 WS_BUILD_TREE, WS_TREE_ATTN, WS_VERIFY = 0, 1, 2
 EXPORTS = ("dyspec_mask_words", "dyspec_workspace_bytes", "dyspec_status_string",
-           "dyspec_build_tree", "dyspec_dfs_reorder", "dyspec_tree_attn", "dyspec_tree_attn_layers",
+           "dyspec_build_tree", "dyspec_build_tree_threshold", "dyspec_build_tree_threshold_workspace_bytes",
+           "dyspec_dfs_reorder", "dyspec_tree_attn", "dyspec_tree_attn_layers",
            "dyspec_tree_attn_layers_workspace_bytes", "dyspec_verify",
            "dyspec_probe_mfma_bf16", "dyspec_probe_hbm_read")
 
@@ -64,6 +65,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.dyspec_status_string.argtypes = [I32]
     lib.dyspec_build_tree.restype = I32
     lib.dyspec_build_tree.argtypes = [V, I32, PB, ctypes.POINTER(F), U64, PT, V, V, V, V, SZ, V]
+    lib.dyspec_build_tree_threshold.restype = I32
+    lib.dyspec_build_tree_threshold.argtypes = [V, I32, PB, ctypes.POINTER(F), ctypes.POINTER(ctypes.c_double), U64, PT,
+                                                V, V, V, ctypes.POINTER(I32), V, SZ, V]
+    lib.dyspec_build_tree_threshold_workspace_bytes.restype = SZ
+    lib.dyspec_build_tree_threshold_workspace_bytes.argtypes = [PB]
     lib.dyspec_tree_attn.restype = I32
     lib.dyspec_tree_attn.argtypes = [V, V, V, V, V, V, PB, I32, I32, I32, I32, F, V, V, SZ, V]
     lib.dyspec_tree_attn_layers.restype = I32
@@ -232,6 +238,33 @@ def build_tree(draft_logits, batch: Batch, draft_temp, seed: int, stream=None, u
                                _ptr(ws) if ws is not None else None, ctypes.c_size_t(ws_bytes), _stream(stream))
     _check(st, "dyspec_build_tree")
     return BuiltTrees(tree, est, mask, nb)
+
+
+def build_tree_threshold(draft_logits, batch: Batch, draft_temp, threshold, seed: int, stream=None):
+    """dyspec_build_tree_threshold: level-by-level construction with a threshold (Algorithm 2)
+    + ancestor mask.  Returns (BuiltTrees, levels expanded); the call waits for the tree."""
+    import torch
+    lib = load_library()
+    dev = draft_logits.device
+    total, V = batch.total_nodes, int(draft_logits.shape[1])
+    if draft_logits.shape[0] != total:
+        raise ValueError("draft_logits needs one row per tree node")
+    tree = Tree.empty(total, dev)
+    est = torch.empty(total, dtype=torch.float32, device=dev)
+    mask = torch.empty((total, batch.mask_words), dtype=torch.int64, device=dev)
+    nb = torch.empty(batch.n_seq, dtype=torch.int32, device=dev)
+    cb, ct = batch._c(), tree._c()
+    tarr, tptr = _temps(draft_temp, batch.n_seq)
+    thr = np.ascontiguousarray(np.broadcast_to(np.asarray(threshold, dtype=np.float64), (batch.n_seq,)))
+    ws_bytes = int(lib.dyspec_build_tree_threshold_workspace_bytes(ctypes.byref(cb)))
+    ws = torch.empty(max(ws_bytes // 8, 1), dtype=torch.float64, device=dev)
+    levels = ctypes.c_int32(0)
+    st = lib.dyspec_build_tree_threshold(_ptr(draft_logits, "float32"), V, ctypes.byref(cb), tptr,
+                                         thr.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), ctypes.c_uint64(seed),
+                                         ctypes.byref(ct), _ptr(est), _ptr(mask), _ptr(nb), ctypes.byref(levels),
+                                         _ptr(ws), ctypes.c_size_t(ws_bytes), _stream(stream))
+    _check(st, "dyspec_build_tree_threshold")
+    return BuiltTrees(tree, est, mask, nb), int(levels.value)
 
 
 @dataclass

@@ -115,6 +115,39 @@ dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab, const 
     return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
 }
 
+size_t dyspec_build_tree_threshold_workspace_bytes(const dyspec_batch* batch)
+{
+    SeqArgs sa;
+    return check_batch(batch, false, &sa) == DYSPEC_OK ? build_threshold_workspace_bytes(sa) : 0;
+}
+
+dyspec_status dyspec_build_tree_threshold(const float* draft_logits, int32_t vocab, const dyspec_batch* batch,
+                                          const float* draft_temp, const double* threshold, uint64_t seed,
+                                          const dyspec_tree* tree, float* est_value, uint64_t* anc_mask,
+                                          int32_t* n_built, int32_t* n_levels, void* workspace,
+                                          size_t workspace_bytes, void* hip_stream)
+{
+    SeqArgs sa;
+    const dyspec_status st = check_batch(batch, false, &sa);
+    if (st != DYSPEC_OK) return st;
+    if (!draft_logits || !draft_temp || !threshold || !tree_ok(tree) || !est_value || !anc_mask || !n_built)
+        return DYSPEC_BAD_ARG;
+    if (vocab < 1) return DYSPEC_BAD_ARG;
+    if (vocab > DYSPEC_MAX_VOCAB) return DYSPEC_UNSUPPORTED;
+    for (int s = 0; s < sa.n_seq; ++s) {
+        if (!(draft_temp[s] > 0.0f) || !(threshold[s] > 0.0)) return DYSPEC_BAD_ARG;
+        sa.temp_d[s] = draft_temp[s];
+    }
+    if (!workspace || (reinterpret_cast<size_t>(workspace) & 7) || workspace_bytes < build_threshold_workspace_bytes(sa))
+        return DYSPEC_WORKSPACE_TOO_SMALL;
+    int levels = 0;
+    const hipError_t e = launch_build_threshold(draft_logits, vocab, sa, threshold, seed, *tree, est_value, anc_mask,
+                                                mask_words_of(batch), n_built, &levels, workspace,
+                                                static_cast<hipStream_t>(hip_stream));
+    if (n_levels) *n_levels = levels;
+    return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
+}
+
 dyspec_status dyspec_dfs_reorder(const dyspec_batch* batch, const dyspec_tree* tree, const dyspec_tree* tree_out,
                                  int32_t* order, uint64_t* anc_mask_out, void* hip_stream)
 {

@@ -15,37 +15,11 @@
 // segment -- so a draw reads 16 totals and one 4 KB line of sums instead of a whole row of
 // logits.  Without a workspace the builder recomputes the sums of the parent's row for every
 // draw; both ways do the same arithmetic and build the same tree.
-#include "vocab_common.h"
+#include "draft_row.h"
 
 namespace dyspec {
 
 constexpr int kMaxSlots = 2 * DYSPEC_MAX_NODES + 2;
-
-// exp(z) for z <= 0 (a softmax weight relative to the row maximum) in fp64: z = n ln2 + r with
-// |r| <= ln2 / 2, exp(r) by its Taylor series to degree 13 (truncation below 1e-17), scaled by
-// 2^n.  Arguments below the normal range, -inf included, give 0.
-__device__ __attribute__((noinline)) double exp_nonpos(double z)
-{
-    if (!(z >= -708.0)) return 0.0;
-    const double n = rint(z * 1.4426950408889634074);
-    double r = fma(n, -6.93147180369123816490e-01, z);
-    r = fma(n, -1.90821492927058770002e-10, r);
-    double p = 1.0 / 6227020800.0;
-    p = fma(p, r, 1.0 / 479001600.0);
-    p = fma(p, r, 1.0 / 39916800.0);
-    p = fma(p, r, 1.0 / 3628800.0);
-    p = fma(p, r, 1.0 / 362880.0);
-    p = fma(p, r, 1.0 / 40320.0);
-    p = fma(p, r, 1.0 / 5040.0);
-    p = fma(p, r, 1.0 / 720.0);
-    p = fma(p, r, 1.0 / 120.0);
-    p = fma(p, r, 1.0 / 24.0);
-    p = fma(p, r, 1.0 / 6.0);
-    p = fma(p, r, 0.5);
-    p = fma(p, r, 1.0);
-    p = fma(p, r, 1.0);
-    return ldexp(p, (int)n);
-}
 
 // Workspace of the cached form, per row (doubles): kMaxSeg * kBlock segment sums S[j][t],
 // kMaxSeg segment totals, the row maximum (already divided by the temperature), and one bit
@@ -56,40 +30,6 @@ __host__ __device__ inline double* ws_sums(double* ws, int row) { return ws + (s
 __host__ __device__ inline double* ws_totals(double* ws, int row) { return ws_sums(ws, row) + kMaxSeg * kBlock; }
 __host__ __device__ inline double* ws_rowmax(double* ws, int row) { return ws_totals(ws, row) + kMaxSeg; }
 __host__ __device__ inline uint32_t* ws_gone(double* ws, int row) { return reinterpret_cast<uint32_t*>(ws_totals(ws, row) + kMaxSeg + 8); }
-
-// weight of one token of a row: exp(x / T - m), m the row maximum over T
-__device__ __forceinline__ double token_weight(float x, double inv_temp, double m)
-{
-    return exp_nonpos(fma((double)x, inv_temp, -m));
-}
-
-// Row maximum (over T) and the 4-token segment sums of this thread for one draft row, with
-// the tokens flagged in `gone` (bit 4j+e) left out.
-template <bool VEC>
-__device__ __forceinline__ void row_segment_sums(const float* __restrict__ row, int V, double inv_temp, uint64_t gone,
-                                                 float* fred, double* m_out, double (&seg)[kMaxSeg])
-{
-    float x[kMaxSeg][4];
-    load_row<VEC>(row, V, x);
-    float mx[1] = { -INFINITY };
-#pragma unroll
-    for (int j = 0; j < kMaxSeg; ++j)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) mx[0] = fmaxf(mx[0], x[j][e]);
-    block_max<1>(mx, fred);
-    const double m = (double)mx[0] * inv_temp;
-    *m_out = m;
-#pragma unroll
-    for (int j = 0; j < kMaxSeg; ++j) {
-        double w4[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const bool live = tok_index(j, e) < V && !((gone >> (4 * j + e)) & 1ull);
-            w4[e] = live ? token_weight(x[j][e], inv_temp, m) : 0.0;
-        }
-        seg[j] = (w4[0] + w4[1]) + (w4[2] + w4[3]);
-    }
-}
 
 // Data-parallel part (the draft softmax of every node, Algorithm 1's model call output):
 // one workgroup per row writes the row's segment sums, segment totals and maximum.

@@ -50,6 +50,10 @@ hipError_t launch_build_tree(const float* draft_logits, int V, const SeqArgs& sa
                              const dyspec_tree& tree, float* est_value, uint64_t* anc_mask,
                              int mask_words, int* n_built, void* workspace, size_t workspace_bytes, hipStream_t stream);
 size_t build_tree_workspace_bytes(int total_rows);
+hipError_t launch_build_threshold(const float* draft_logits, int V, const SeqArgs& sa, const double* threshold,
+                                  uint64_t seed, const dyspec_tree& tree, float* est_value, uint64_t* anc_mask,
+                                  int mask_words, int* n_built, int* n_levels, void* workspace, hipStream_t stream);
+size_t build_threshold_workspace_bytes(const SeqArgs& sa);
 hipError_t launch_dfs_reorder(const SeqArgs& sa, const dyspec_tree& in, const dyspec_tree& out, int* order,
                               uint64_t* mask_out, int mask_words, hipStream_t stream);
 hipError_t launch_verify(const float* draft_logits, const float* target_logits, int V,

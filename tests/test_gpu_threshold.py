@@ -1,0 +1,164 @@
+"""GPU parity: dyspec_build_tree_threshold (Algorithm 2) against the CPU oracle, through the C ABI."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import compare_verify
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+MARGIN = 1e-9          # decisions of the fp64 builder closer than this are not compared
+
+
+@pytest.fixture(scope="module")
+def dy():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2410_11744_amd as m
+    m.load_library()
+    return m
+
+
+def draft_table(n, V, sigma, seed):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((n, V)) * sigma).astype(np.float32)
+
+
+def compare_threshold_trees(built, batch, draft, temps, thresholds, seed):
+    """Every array of every sequence against the oracle; returns how many sequences were compared."""
+    g = {k: getattr(built.tree, k).cpu().numpy() for k in ("parent", "token", "sib_rank", "first_child", "next_sibling", "depth")}
+    est = built.est_value.cpu().numpy()
+    mask = built.anc_mask.cpu().numpy().view(np.uint64)
+    nb = built.n_built.cpu().numpy()
+    compared = 0
+    for s in range(batch.n_seq):
+        a, b = int(batch.node_offset[s]), int(batch.node_offset[s + 1])
+        want = oracle.threshold_tree(draft[a:b], b - a, float(np.float32(temps[s])), float(thresholds[s]), seed, seq=s)
+        if min(want.margin_cdf, want.margin_threshold) < MARGIN:
+            continue
+        assert nb[s] == want.n_built, f"seq {s}: {nb[s]} rows, oracle {want.n_built}"
+        for k in g:
+            np.testing.assert_array_equal(g[k][a:b], getattr(want, k), err_msg=f"seq {s} {k}")
+        words = want.mask.shape[1]
+        np.testing.assert_array_equal(mask[a:b, :words], want.mask, err_msg=f"seq {s} mask")
+        assert not mask[a:b, words:].any()
+        np.testing.assert_allclose(est[a:b], want.est_value, rtol=1e-6, atol=1e-30)
+        compared += 1
+    return compared
+
+
+CASES = [
+    # (capacity per seq, V, sigma, temps, thresholds, seed)
+    ((64,), 1000, 3.0, (0.5,), (0.05,), 0),                     # seven levels, ends below the capacity
+    ((16,), 3, 0.0, (1.0,), (0.3,), 1),                         # three uniform tokens: seven nodes by hand
+    ((40,), 130, 2.0, (0.7,), (0.05,), 2),                      # V not a multiple of 4; the root alone fills the capacity
+    ((300,), 5000, 4.0, (0.5,), (0.01,), 3),                    # thirteen levels, several mask words
+    ((1,), 64, 1.0, (1.0,), (0.1,), 4),                         # root only
+    ((2,), 8, 1.0, (0.9,), (0.5,), 5),
+    ((64, 7, 200, 1), 5000, 4.0, (0.5, 1.0, 0.6, 1.0), (0.05, 0.2, 0.01, 0.5), 6),   # ragged batch, own thresholds; the third is cut
+    ((128,), 32768, 4.0, (0.5,), (0.05,), 7),                   # largest vocabulary
+    ((50,), 12, 1.0, (1.0,), (1e-3,), 8),                       # tiny vocabulary: rows run out of tokens
+    ((32,), 200, 2.0, (1.0,), (2.0,), 9),                       # threshold above 1: nothing is built
+    ((256,), 1001, 4.0, (0.5,), (0.004,), 10),                  # odd V, deep tree
+]
+
+
+@pytest.mark.parametrize("nodes,V,sigma,temps,thresholds,seed", CASES)
+def test_threshold_builder_matches_oracle(dy, nodes, V, sigma, temps, thresholds, seed):
+    print(f"case nodes={nodes} V={V} t={thresholds} seed={seed}", flush=True)
+    batch = dy.Batch.from_sizes(nodes)
+    d = draft_table(sum(nodes), V, sigma, 500 + seed)
+    dd = torch.from_numpy(d).cuda()
+    built, levels = dy.build_tree_threshold(dd, batch, temps, thresholds, seed)
+    assert compare_threshold_trees(built, batch, d, temps, thresholds, seed) == len(nodes), \
+        "an oracle decision had a margin below 1e-9: pick another seed"
+    assert levels >= 1
+
+
+def test_by_hand_uniform_three_tokens(dy):
+    batch = dy.Batch.from_sizes((16,))
+    dd = torch.zeros((16, 3), device="cuda")
+    built, levels = dy.build_tree_threshold(dd, batch, (1.0,), (0.3,), 3)
+    assert built.n_built.item() == 7 and levels == 3
+    np.testing.assert_array_equal(built.tree.parent.cpu().numpy()[:7], [-1, 0, 0, 0, 1, 2, 3])
+    np.testing.assert_allclose(built.est_value.cpu().numpy()[:7], [1, 1, 2 / 3, 1 / 3, 1 / 3, 1 / 3, 1 / 3], rtol=1e-6)
+
+
+def test_full_size_tree_and_verification_on_it(dy):
+    """The 70B-shaped draft table (32000 logits per row), capacity 768, t = 0.02: a tree of
+    several hundred rows in a handful of levels, equal to the oracle's; verification walks it."""
+    from paper_2410_11744_amd import synth
+    cfg = synth.CONFIGS["llama2_70b"]
+    d512, t512 = synth.make_logits(cfg)
+    d = np.concatenate([d512, d512[:256]])
+    t = np.concatenate([t512, t512[:256]])
+    batch = dy.Batch.from_sizes((768,))
+    dd, tg = torch.from_numpy(d).cuda(), torch.from_numpy(t).cuda()
+    built, levels = dy.build_tree_threshold(dd, batch, cfg.temps, (0.02,), cfg.seed)
+    assert compare_threshold_trees(built, batch, d, cfg.temps, (0.02,), cfg.seed) == 1
+    n = int(built.n_built.item())
+    assert 300 < n < 768 and 3 <= levels <= 12
+    out = dy.verify(dd, tg, batch, built.tree, cfg.temps, cfg.temps, cfg.seed)
+    tr = {k: getattr(built.tree, k).cpu().numpy() for k in ("token", "first_child", "next_sibling")}
+    compare_verify(out, batch, [(tr["token"], tr["first_child"], tr["next_sibling"])], d, t, cfg.temps, cfg.temps, cfg.seed)
+
+
+def test_same_tree_as_the_greedy_builder_on_a_context_free_table(dy):
+    """Every row of the table alike, so a node's draft row does not depend on how nodes are
+    numbered: with t just below the smallest value the greedy builder opened, both builders
+    produce the same set of (path, token) pairs (Appendix A.1)."""
+    compared = 0
+    for seed in range(6):
+        V, N = 400, 96
+        row = draft_table(1, V, 2.5, 900 + seed)
+        d = np.repeat(row, N + 32, axis=0)
+        dd = torch.from_numpy(d).cuda()
+        greedy = dy.build_tree(dd[:N].contiguous(), dy.Batch.from_sizes((N,)), (0.8,), seed)
+        ge = greedy.est_value.cpu().numpy().astype(np.float64)
+        t = ge.min() * (1.0 - 1e-5)
+        built, _ = dy.build_tree_threshold(dd, dy.Batch.from_sizes((N + 32,)), (0.8,), (t,), seed)
+        if built.n_built.item() != N:
+            continue                                            # another slot within 1e-5 of the last one
+        def keyed(tree, n):
+            par, rk, tok = (getattr(tree, k).cpu().numpy() for k in ("parent", "sib_rank", "token"))
+            paths = [()]
+            for i in range(1, n):
+                paths.append(paths[par[i]] + (int(rk[i]),))
+            return {paths[i]: int(tok[i]) for i in range(n)}
+        assert keyed(greedy.tree, N) == keyed(built.tree, N)
+        compared += 1
+    assert compared >= 4
+
+
+def test_bad_arguments(dy):
+    batch = dy.Batch.from_sizes((8,))
+    d = torch.zeros((8, 16), device="cuda")
+    with pytest.raises(dy.DyspecError) as e:
+        dy.build_tree_threshold(d, batch, (1.0,), (0.0,), 0)            # threshold must be positive
+    assert e.value.status == -1
+    with pytest.raises(dy.DyspecError) as e:
+        dy.build_tree_threshold(d, batch, (0.0,), (0.1,), 0)
+    assert e.value.status == -1
+    lib = dy.load_library()
+    cb = batch._c()
+    need = lib.dyspec_build_tree_threshold_workspace_bytes(ctypes.byref(cb))
+    assert need > 0
+    tree = dy.Tree.empty(8, "cuda")
+    ct = tree._c()
+    est = torch.empty(8, device="cuda")
+    mask = torch.empty((8, 1), dtype=torch.int64, device="cuda")
+    nb = torch.empty(1, dtype=torch.int32, device="cuda")
+    temp = (ctypes.c_float * 1)(1.0)
+    thr = (ctypes.c_double * 1)(0.1)
+    ws = torch.empty(need // 8 + 1, dtype=torch.float64, device="cuda")
+    st = lib.dyspec_build_tree_threshold(d.data_ptr(), 16, ctypes.byref(cb), temp, thr, 0, ctypes.byref(ct),
+                                         est.data_ptr(), mask.data_ptr(), nb.data_ptr(), None, ws.data_ptr(),
+                                         need - 8, None)
+    assert st == -4                                                     # workspace too small
+    st = lib.dyspec_build_tree_threshold(d.data_ptr(), 16, ctypes.byref(cb), temp, thr, 0, ctypes.byref(ct),
+                                         est.data_ptr(), mask.data_ptr(), nb.data_ptr(), None, None, 0, None)
+    assert st == -4
