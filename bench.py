@@ -258,6 +258,16 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         mfma_tflops = fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        dy.probe_mfma_bf16(2000, sink, random_operands=True)
+        torch.cuda.synchronize()
+        e0.record()
+        fl = dy.probe_mfma_bf16(20000, sink, random_operands=True)
+        e1.record()
+        torch.cuda.synchronize()
+        mfma_random_tflops = fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        # a loop of nothing but MFMAs keeps the matrix pipe of every SIMD busy every cycle:
+        # 1024 SIMDs x 32768 flops per 32 cycles, so the rate names the clock it ran at
+        implied_ghz = lambda tf: tf * 1e12 / (1024 * 1024) / 1e9
         buf = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         best = float("inf")
         for _ in range(5):
@@ -268,9 +278,13 @@ def main() -> int:
             torch.cuda.synchronize()
             best = min(best, e0.elapsed_time(e1))
         del buf
-        ceilings = {"mfma_bf16_tflops": round(mfma_tflops, 1), "hbm_read_gbs": round(nbytes / (best * 1e-3) / 1e9, 1),
-                    "how": "MFMA: 8192 waves of independent 32x32x16 bf16 MFMAs, no memory or vector work; "
-                           "HBM: one streaming read of 1 GiB, best of 5"}
+        ceilings = {"mfma_bf16_tflops": round(mfma_tflops, 1), "mfma_bf16_clock_ghz": round(implied_ghz(mfma_tflops), 3),
+                    "mfma_bf16_random_operands_tflops": round(mfma_random_tflops, 1),
+                    "mfma_bf16_random_operands_clock_ghz": round(implied_ghz(mfma_random_tflops), 3),
+                    "hbm_read_gbs": round(nbytes / (best * 1e-3) / 1e9, 1),
+                    "how": "MFMA: 8192 waves of independent 32x32x16 bf16 MFMAs, no memory or vector work, operands a smooth "
+                           "ramp of small values or random in +-[0.25, 4); the clock is the one at which 1024 busy matrix "
+                           "pipes give that rate (nominal 2.4 GHz); HBM: one streaming read of 1 GiB, best of 5"}
 
     # Untimed warmup.  The HIP runtime stalls one launch of this library for 35-40 ms once per
     # process, around its 350th kernel dispatch (seen on every run here, at any workload; nothing
@@ -293,6 +307,25 @@ def main() -> int:
     attn_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
     verify_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
     value = n_tokens / (ms_per_step * 1e-3)
+
+    # ---- the shader clock under this workload (after the timed region): one sleeping wave on a
+    #      stream of its own counts shader cycles and wall-clock ticks while a few more steps run
+    shader_clock_ghz = None
+    if not args.no_ceilings:
+        k2 = max(3, min(args.steps, int(60.0 / max(ms_per_step, 1e-3))))       # about 60 ms of steps
+        naps = int(max(1, min(1 << 24, 0.4 * k2 * ms_per_step * 1e-3 * 2.4e9 / 8128)))
+        counters = torch.zeros(2, dtype=torch.int64, device=dev)
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        step()
+        with torch.cuda.stream(side):
+            khz = dy.probe_clock(naps, counters)
+        for _ in range(k2 - 1):
+            step()
+        torch.cuda.synchronize()
+        cyc, ticks = (int(x) for x in counters.cpu().numpy())
+        if ticks > 0:
+            shader_clock_ghz = round(cyc / (ticks / (khz * 1e3)) / 1e9, 3)
 
     # ---- roofline of the dominant kernel (tree attention, one launch = one layer)
     # Algorithmic work per launch: every row scores and accumulates over all prefix keys and
@@ -386,6 +419,7 @@ def main() -> int:
         "attn_ms_per_step": round(attn_ms, 4), "verify_ms_per_step": round(verify_ms, 4),
         "n_accepted": [int(x) for x in vout.n_accepted.cpu().numpy()],
         "pct_hbm_peak": round(100.0 * hbm_gbs / PEAK_HBM_GBS, 2), "algorithmic_gbs": round(hbm_gbs, 1),
+        "shader_clock_ghz_under_this_workload": shader_clock_ghz,
         "roofline": roofline, "cpu_baseline": cpu, "ceilings": ceilings,
     }
     print(json.dumps(line))

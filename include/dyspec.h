@@ -275,17 +275,30 @@ dyspec_status dyspec_verify(const float* draft_logits, const float* target_logit
                             void* hip_stream);
 
 /*
- * Measurement helpers (no part of the method): two ceilings to set beside the published
- * peaks of the chip.  Both only launch; the caller times them (HIP events on hip_stream).
+ * Measurement helpers (no part of the method): ceilings to set beside the published peaks
+ * of the chip, and the clock the chip runs at under load.  All only launch; the caller times
+ * them (HIP events on hip_stream).
  *
  * dyspec_probe_mfma_bf16: 1024 workgroups of 8 waves, every wave `iterations` rounds of four
- * independent 32x32x16 bf16 MFMAs, no memory traffic.  *flops (HOST) receives the number of
- * floating-point operations of the launch.  sink: DEVICE, one float, never written in practice.
+ * independent 32x32x16 bf16 MFMAs, no memory traffic.  random_operands != 0: operands with
+ * random signs and mantissas and magnitudes in [0.25, 4) instead of a smooth ramp of small
+ * values (the clock the chip sustains under matrix load depends on the data).  *flops (HOST)
+ * receives the number of floating-point operations of the launch.  sink: DEVICE, one float,
+ * never written in practice.
+ *
+ * dyspec_probe_clock: one wave that sleeps through `iterations` (1 .. 2^24) naps of about
+ * 8000 cycles and then writes counters[0] = shader clock cycles and counters[1] = wall clock
+ * ticks that went by (DEVICE, two uint64); *wall_clock_khz (HOST) receives the rate of the
+ * wall clock counter.  Launched on a stream of its own next to other work it reports the
+ * shader clock that work ran at: cycles / (ticks / rate).
  *
  * dyspec_probe_hbm_read: streams `bytes` (a multiple of 16, src DEVICE, 16-byte aligned) from
  * memory once with 16-byte loads, eight in flight per thread.
  */
-dyspec_status dyspec_probe_mfma_bf16(int32_t iterations, double* flops, float* sink, void* hip_stream);
+dyspec_status dyspec_probe_mfma_bf16(int32_t iterations, int32_t random_operands, double* flops,
+                                     float* sink, void* hip_stream);
+dyspec_status dyspec_probe_clock(int32_t iterations, uint64_t* counters, int32_t* wall_clock_khz,
+                                 void* hip_stream);
 dyspec_status dyspec_probe_hbm_read(const void* src, size_t bytes, float* sink, void* hip_stream);
 
 #ifdef __cplusplus

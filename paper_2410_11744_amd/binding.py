@@ -22,7 +22,7 @@ EXPORTS = ("dyspec_mask_words", "dyspec_workspace_bytes", "dyspec_status_string"
            "dyspec_build_tree", "dyspec_build_tree_threshold", "dyspec_build_tree_threshold_workspace_bytes",
            "dyspec_dfs_reorder", "dyspec_tree_attn", "dyspec_tree_attn_layers",
            "dyspec_tree_attn_layers_workspace_bytes", "dyspec_verify",
-           "dyspec_probe_mfma_bf16", "dyspec_probe_hbm_read")
+           "dyspec_probe_mfma_bf16", "dyspec_probe_clock", "dyspec_probe_hbm_read")
 
 
 class DyspecError(RuntimeError):
@@ -83,7 +83,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.dyspec_dfs_reorder.restype = I32
     lib.dyspec_dfs_reorder.argtypes = [PB, PT, PT, V, V, V]
     lib.dyspec_probe_mfma_bf16.restype = I32
-    lib.dyspec_probe_mfma_bf16.argtypes = [I32, ctypes.POINTER(ctypes.c_double), V, V]
+    lib.dyspec_probe_mfma_bf16.argtypes = [I32, I32, ctypes.POINTER(ctypes.c_double), V, V]
+    lib.dyspec_probe_clock.restype = I32
+    lib.dyspec_probe_clock.argtypes = [I32, V, ctypes.POINTER(I32), V]
     lib.dyspec_probe_hbm_read.restype = I32
     lib.dyspec_probe_hbm_read.argtypes = [V, SZ, V, V]
     if path is None:
@@ -434,12 +436,21 @@ def verify(draft_logits, target_logits, batch: Batch, tree: Tree, draft_temp, ta
     return out
 
 
-def probe_mfma_bf16(iterations: int, sink, stream=None) -> float:
+def probe_mfma_bf16(iterations: int, sink, stream=None, random_operands: bool = False) -> float:
     """dyspec_probe_mfma_bf16: launches the MFMA-only loop, returns the flops of the launch."""
     flops = ctypes.c_double(0.0)
-    _check(load_library().dyspec_probe_mfma_bf16(int(iterations), ctypes.byref(flops), _ptr(sink, "float32"),
-                                                 _stream(stream)), "dyspec_probe_mfma_bf16")
+    _check(load_library().dyspec_probe_mfma_bf16(int(iterations), int(bool(random_operands)), ctypes.byref(flops),
+                                                 _ptr(sink, "float32"), _stream(stream)), "dyspec_probe_mfma_bf16")
     return float(flops.value)
+
+
+def probe_clock(iterations: int, counters, stream=None) -> int:
+    """dyspec_probe_clock: launches the sleeping wave; counters (int64[2], device) receives shader
+    cycles and wall clock ticks once it ends.  Returns the wall clock rate in kHz."""
+    khz = ctypes.c_int32(0)
+    _check(load_library().dyspec_probe_clock(int(iterations), _ptr(counters, "int64"), ctypes.byref(khz), _stream(stream)),
+           "dyspec_probe_clock")
+    return int(khz.value)
 
 
 def probe_hbm_read(src, sink, stream=None) -> int:

@@ -11,13 +11,30 @@ typedef float floatx16c __attribute__((ext_vector_type(16)));
 constexpr int kProbeGroups = 1024, kProbeThreads = 512;
 
 // Every wave runs `iterations` rounds of four MFMAs on four independent accumulators: two
-// waves per SIMD, no memory traffic, no vector work.
+// waves per SIMD, no memory traffic, no vector work.  RANDOM: operands with random sign,
+// mantissa and a magnitude in [0.25, 4) (the spread of N(0,1) tensors) in place of a smooth
+// ramp of small values: the chip's clock under matrix load depends on how many bits toggle.
+template <bool RANDOM>
 __global__ __launch_bounds__(kProbeThreads) void mfma_ceiling_kernel(int iterations, float* sink)
 {
     const int lane = threadIdx.x & 63;
     bf16x8c a, b;
+    if (RANDOM) {
+        union { uint32_t w[4]; bf16x8c v; } ua, ub;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(0.001f * (lane + i)); b[i] = (__bf16)(0.002f * (lane - i)); }
+        for (int i = 0; i < 4; ++i) {
+            uint32_t h = (uint32_t)(threadIdx.x * 8 + i) * 2654435761u + blockIdx.x * 40503u;
+            h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+            uint32_t g = h * 3266489917u; g ^= g >> 16;
+            // per bf16: sign and 7 mantissa bits random, exponent 125..128
+            ua.w[i] = (h & 0x817f817fu) | 0x3e803e80u | ((h >> 3) & 0x01800180u);
+            ub.w[i] = (g & 0x817f817fu) | 0x3e803e80u | ((g >> 3) & 0x01800180u);
+        }
+        a = ua.v; b = ub.v;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(0.001f * (lane + i)); b[i] = (__bf16)(0.002f * (lane - i)); }
+    }
     floatx16c c0 = {}, c1 = {}, c2 = {}, c3 = {};
     for (int it = 0; it < iterations; ++it) {
         c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
@@ -49,17 +66,42 @@ __global__ __launch_bounds__(256) void hbm_read_ceiling_kernel(const float4* __r
     if (acc == 1.2345e-30f) sink[0] = acc;
 }
 
+// One wave that sleeps through `iterations` short naps and reports how far the shader clock
+// counter and the constant-rate wall clock counter moved meanwhile: launched on a side stream
+// it shares the chip with whatever runs at the time and tells the clock that work ran at.
+__global__ __launch_bounds__(64) void clock_probe_kernel(int iterations, unsigned long long* out)
+{
+    const unsigned long long c0 = clock64(), w0 = wall_clock64();
+    for (int it = 0; it < iterations; ++it) __builtin_amdgcn_s_sleep(127);
+    const unsigned long long c1 = clock64(), w1 = wall_clock64();
+    if (threadIdx.x == 0) { out[0] = c1 - c0; out[1] = w1 - w0; }
+}
+
 }  // namespace dyspec
 
 using namespace dyspec;
 
 extern "C" {
 
-dyspec_status dyspec_probe_mfma_bf16(int32_t iterations, double* flops, float* sink, void* hip_stream)
+dyspec_status dyspec_probe_mfma_bf16(int32_t iterations, int32_t random_operands, double* flops, float* sink, void* hip_stream)
 {
     if (iterations < 1 || !flops || !sink) return DYSPEC_BAD_ARG;
     *flops = (double)kProbeGroups * (kProbeThreads / 64) * (double)iterations * 4.0 * (2.0 * 32 * 32 * 16);
-    mfma_ceiling_kernel<<<kProbeGroups, kProbeThreads, 0, static_cast<hipStream_t>(hip_stream)>>>(iterations, sink);
+    if (random_operands)
+        mfma_ceiling_kernel<true><<<kProbeGroups, kProbeThreads, 0, static_cast<hipStream_t>(hip_stream)>>>(iterations, sink);
+    else
+        mfma_ceiling_kernel<false><<<kProbeGroups, kProbeThreads, 0, static_cast<hipStream_t>(hip_stream)>>>(iterations, sink);
+    return hipGetLastError() == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
+}
+
+dyspec_status dyspec_probe_clock(int32_t iterations, uint64_t* counters, int32_t* wall_clock_khz, void* hip_stream)
+{
+    if (iterations < 1 || iterations > (1 << 24) || !counters || !wall_clock_khz) return DYSPEC_BAD_ARG;
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess)
+        return DYSPEC_HIP_ERROR;
+    *wall_clock_khz = khz;
+    clock_probe_kernel<<<1, 64, 0, static_cast<hipStream_t>(hip_stream)>>>(iterations, reinterpret_cast<unsigned long long*>(counters));
     return hipGetLastError() == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
 }
 

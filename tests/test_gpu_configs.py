@@ -91,3 +91,15 @@ def test_ceiling_probes_run(dy):
     assert float(sink.item()) == 0.0
     with pytest.raises(dy.DyspecError):
         dy.probe_mfma_bf16(0, sink)
+    # random operands: same work, results stay finite (the sink is never written)
+    assert dy.probe_mfma_bf16(200, sink, random_operands=True) == 1024 * 8 * 200 * 4 * 2 * 32 * 32 * 16
+    # the sleeping wave reports both counters and a plausible clock (between 0.3 and 3 GHz)
+    counters = torch.zeros(2, dtype=torch.int64, device="cuda")
+    khz = dy.probe_clock(200, counters)
+    torch.cuda.synchronize()
+    cyc, ticks = (int(x) for x in counters.cpu().numpy())
+    assert khz > 0 and cyc >= 200 * 64 and ticks > 0
+    assert 0.3 < cyc / (ticks / (khz * 1e3)) / 1e9 < 3.0
+    assert float(sink.item()) == 0.0
+    with pytest.raises(dy.DyspecError):
+        dy.probe_clock(0, counters)
