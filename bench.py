@@ -175,6 +175,9 @@ def main() -> int:
                          "other can do, so the default and the headline value stay per layer)")
     ap.add_argument("--tree-builders", action="store_true",
                     help="instead of the step benchmark: time the greedy and the threshold tree builder on the workload's draft table")
+    ap.add_argument("--dfs-order", action="store_true",
+                    help="rename the tree's nodes in depth-first order (dyspec_dfs_reorder) before attention and "
+                         "verification: subtrees become runs of rows, fewer tree tiles per workgroup")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the two measured ceilings (MFMA-only loop, streaming HBM read)")
     args = ap.parse_args()
@@ -208,6 +211,15 @@ def main() -> int:
     draft_h, target_h = synth.make_logits(cfg)
     draft, target = torch.from_numpy(draft_h).to(dev), torch.from_numpy(target_h).to(dev)
     built = dy.build_tree(draft, batch, cfg.temps, cfg.seed)
+    if args.dfs_order:
+        # the paper's token order for attention (Appendix C): nodes renamed in depth-first order, the
+        # rows of the logit tables follow their nodes; verification does not depend on the numbering
+        re = dy.dfs_reorder(built.tree, batch)
+        idx = re.gather_index(batch)
+        draft, target = draft[idx].contiguous(), target[idx].contiguous()
+        idx_h = idx.cpu().numpy()
+        draft_h, target_h = draft_h[idx_h], target_h[idx_h]
+        built = dy.BuiltTrees(re.tree, built.est_value[idx].contiguous(), re.anc_mask, built.n_built)
     # all layers' tensors live in five stacked allocations [L, ...]; the per-layer calls take views
     stacked = None
     for l in range(cfg.layers):
@@ -412,6 +424,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: {cfg.layers} layers, {cfg.n_q_heads}q/{cfg.n_kv_heads}kv heads, "
                                f"head_dim {cfg.head_dim}, prefix {list(cfg.prefix_len)}, tree rows {list(cfg.n_nodes)}, "
                                f"vocab {cfg.vocab}, batch {batch.n_seq}",
+                   "node_order": "depth-first (dyspec_dfs_reorder)" if args.dfs_order else "creation order",
                    "attention_call": "dyspec_tree_attn_layers, one call per step" if args.batched_layers
                                      else "dyspec_tree_attn, one call per layer",
                    "draft_temp": [float(x) for x in cfg.temps], "target_temp": [float(x) for x in target_temps],
