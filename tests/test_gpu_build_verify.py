@@ -150,3 +150,37 @@ def test_bad_arguments_are_rejected(dy):
     with pytest.raises(dy.DyspecError) as e:
         dy.build_tree(torch.zeros((2000, 16), device="cuda"), big, (1.0,), 0)
     assert e.value.status == -2
+
+
+def test_maximum_sizes_and_widest_batch(dy):
+    """The limits of the library in one place: a sequence with the maximum number of rows over the
+    maximum vocabulary, and a batch of the maximum number of sequences (ragged, some of one row)."""
+    import time
+    nodes, V = (1024,), 32768
+    print("max sizes: N=1024 V=32768", flush=True)
+    batch = dy.Batch.from_sizes(nodes)
+    d, t = logits(1024, V, 3.0, 1.0, 4242)
+    dd, tt = torch.from_numpy(d).cuda(), torch.from_numpy(t).cuda()
+    built = dy.build_tree(dd, batch, (0.7,), 11)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    trees = oracle_trees(d, nodes, (0.7,), 11)
+    print(f"  oracle build {time.time() - t0:.1f} s", flush=True)
+    assert compare_trees(built, batch, trees) == 1
+    out = dy.verify(dd, tt, batch, built.tree, (0.7,), (0.9,), 11)
+    compare_verify(out, batch, trees, d, t, (0.7,), (0.9,), 11)
+
+    rng = np.random.default_rng(64)
+    nodes = tuple(int(x) for x in rng.integers(1, 20, 64))
+    print(f"widest batch: 64 sequences, rows {sum(nodes)}", flush=True)
+    batch = dy.Batch.from_sizes(nodes)
+    temps = tuple(float(x) for x in rng.choice([0.6, 0.8, 1.0], 64))
+    d, t = logits(sum(nodes), 500, 2.0, 1.0, 4243)
+    dd, tt = torch.from_numpy(d).cuda(), torch.from_numpy(t).cuda()
+    built = dy.build_tree(dd, batch, temps, 12)
+    torch.cuda.synchronize()
+    trees = oracle_trees(d, nodes, temps, 12)
+    assert compare_trees(built, batch, trees) >= 62
+    out = dy.verify(dd, tt, batch, built.tree, temps, temps, 12)
+    compared, skipped = compare_verify(out, batch, trees, d, t, temps, temps, 12)
+    assert compared + skipped == 64 and compared >= 60

@@ -165,3 +165,12 @@ def test_unsupported_head_dim_is_rejected(dy):
     with pytest.raises(dy.DyspecError) as e:
         dy.tree_attn(z(4, 2, 96), z(4, 2, 96), z(4, 2, 96), z(4, 2, 96), z(4, 2, 96), mask, batch, 0.1)
     assert e.value.status == -3
+
+
+def test_widest_batch_of_sequences(dy):
+    """64 sequences (the batch limit) of a few rows each, ragged prefixes, some without prefix."""
+    rng = np.random.default_rng(640)
+    nodes = tuple(int(x) for x in rng.integers(1, 24, 64))
+    prefix = tuple(int(x) for x in rng.choice([0, 1, 63, 64, 65, 130], 64))
+    run_and_compare(dy, nodes, prefix, 8, 2, 128, "bf16", 64)
+    run_and_compare(dy, nodes, prefix, 4, 4, 64, "f32", 65)
