@@ -98,17 +98,29 @@ __global__ __launch_bounds__(256) void threshold_init_kernel(SeqArgs sa, dyspec_
 }
 
 struct ExpandShared {
-    CdfScratch cdf;
+    double red[kWaves * kMaxSeg];       // workgroup sums at set-up
+    double wave_tot[kWaves];            // per draw: the waves' sums of the picked segment
+    double w4[4];                       // weights of the four tokens of the thread that owns the crossing
+    double excl;                        // weight in front of those four
+    int first_hit[kWaves];              // first thread of each wave past the crossing, -1: none
+    int last_live[kWaves];              // last thread of each wave with weight left, -1: none
     float fred[kWaves];
 };
 
-// One workgroup per node of the current level: blockIdx.x = position in the level.
+// One workgroup per node of the current level: blockIdx.x = position in the level.  The node's
+// row of logits and a drawn-already bitmap live in LDS (dynamic: 4 bytes per token, 1 bit per
+// token), the threads' 4-token weight sums and the 16 segment totals in registers.  A draw is:
+// segment pick (registers), a scan of the 512 sums of that segment (shuffles, one barrier), a
+// ballot for the thread that holds the crossing (one barrier), the four weights of that thread
+// computed by four threads (one barrier), and then every thread finishes the draw by itself.
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void threshold_expand_kernel(const float* __restrict__ draft_logits, int V, SeqArgs sa,
                                                                   ThresholdArgs ta, uint64_t seed, ThresholdWs w)
 {
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn[];
     __shared__ ExpandShared sh;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int seq = blockIdx.y;
     const int base = sa.node_off[seq];
     const int lvl_begin = w.state[4 * seq + 0], lvl_end = w.state[4 * seq + 1], left = w.state[4 * seq + 2];
@@ -125,14 +137,18 @@ __global__ __launch_bounds__(kBlock) void threshold_expand_kernel(const float* _
     const float* __restrict__ row = draft_logits + (size_t)(base + p) * V;
     const uint2 pk_p = w.pk[base + p];
     const size_t pool0 = (size_t)w.pool_off[seq] + (size_t)f * left;
+    const int Vpad = (V + 31) & ~31;
+    float* const row_lds = reinterpret_cast<float*>(dyn);
+    uint32_t* const gone = reinterpret_cast<uint32_t*>(dyn + (size_t)Vpad * 4);
+    for (int i = tid; i < Vpad; i += kBlock) row_lds[i] = (i < V) ? row[i] : -INFINITY;
+    for (int i = tid; i < Vpad / 32; i += kBlock) gone[i] = 0u;
 
-    uint64_t gone = 0ull;                               // bit 4j+e: this thread's token (j, e) was drawn already
     double m, seg[kMaxSeg], tot[kMaxSeg];
     row_segment_sums<VEC>(row, V, inv_temp, 0ull, sh.fred, &m, seg);
 #pragma unroll
     for (int j = 0; j < kMaxSeg; ++j) tot[j] = seg[j];
-    block_sum<double, kMaxSeg>(tot, sh.cdf.red);
-    __syncthreads();
+    block_sum<double, kMaxSeg>(tot, sh.red);
+    __syncthreads();                                    // the row and the bitmap are in LDS for everyone
 
     int count = 0;
     while (v >= t && count < left) {
@@ -142,34 +158,73 @@ __global__ __launch_bounds__(kBlock) void threshold_expand_kernel(const float* _
         double mine = 0.0;
 #pragma unroll
         for (int j = 0; j < kMaxSeg; ++j) if (j == pk.js) mine = seg[j];
-        auto weight_at = [&](int e, uint64_t g) -> double {
-            const int idx = tok_index(pk.js, e);
-            if (idx >= V || ((g >> (4 * pk.js + e)) & 1ull)) return 0.0;
-            return token_weight(row[idx], inv_temp, m);
-        };
-        double wy;
-        const int y = finish_inverse_cdf(pk, mine, &sh.cdf, &wy, [&](int, int e) { return weight_at(e, gone); });
-        if (y < 0) break;
-        // the sum that held y and the total of its segment lose y's weight
-        double t1[1] = { mine };
-        if (((y % kSeg) >> 2) == tid) {
-            gone |= 1ull << (4 * pk.js + (y & 3));
-            t1[0] = (weight_at(0, gone) + weight_at(1, gone)) + (weight_at(2, gone) + weight_at(3, gone));
+        // ---- inclusive scan of the sums of segment js in thread order
+        double inc = mine;
 #pragma unroll
-            for (int j = 0; j < kMaxSeg; ++j) if (j == pk.js) seg[j] = t1[0];
+        for (int o = 1; o < kWave; o <<= 1) {
+            const double up = __shfl_up(inc, o, kWave);
+            if (lane >= o) inc += up;
         }
-        block_sum<double, 1>(t1, sh.cdf.red);
+        if (lane == kWave - 1) sh.wave_tot[wave] = inc;
+        __syncthreads();
+        double before = 0.0;
+        for (int k = 0; k < wave; ++k) before += sh.wave_tot[k];
+        const double incl = before + inc;
+        // ---- the first thread whose prefix passes u * W holds the drawn token
+        const unsigned long long hit = __ballot(mine > 0.0 && pk.cum_js + incl > pk.target);
+        const unsigned long long live = __ballot(mine > 0.0);
+        if (lane == 0) {
+            sh.first_hit[wave] = hit ? wave * kWave + __builtin_ctzll(hit) : -1;
+            sh.last_live[wave] = live ? wave * kWave + 63 - __builtin_clzll(live) : -1;
+        }
+        __syncthreads();
+        int owner = -1, last = -1;
 #pragma unroll
-        for (int j = 0; j < kMaxSeg; ++j) if (j == pk.js) tot[j] = t1[0];
+        for (int k = 0; k < kWaves; ++k) {
+            if (owner < 0 && sh.first_hit[k] >= 0) owner = sh.first_hit[k];
+            if (sh.last_live[k] >= 0) last = sh.last_live[k];
+        }
+        if (owner < 0) owner = last;                    // rounding at the very top: the last thread with weight left
+        if (owner < 0) break;                           // the totals held rounding dust only
+        const int tok0 = pk.js * kSeg + 4 * owner;      // first of the owner's four tokens
+        if (tid == owner) sh.excl = pk.cum_js + (incl - mine);
+        if (tid < 4) {
+            const int idx = tok0 + tid;
+            const bool there = idx < V && !((gone[idx >> 5] >> (idx & 31)) & 1u);
+            sh.w4[tid] = there ? token_weight(row_lds[idx], inv_temp, m) : 0.0;
+        }
+        __syncthreads();
+        // ---- every thread finishes the draw: the token among the four, what is left of their sum
+        const double w0 = sh.w4[0], w1 = sh.w4[1], w2 = sh.w4[2], w3 = sh.w4[3];
+        double run = sh.excl, wy = 0.0, wlast = 0.0;
+        int y = -1, ylast = -1;
+        const double w4v[4] = { w0, w1, w2, w3 };
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            run += w4v[e];
+            if (w4v[e] > 0.0) { ylast = tok0 + e; wlast = w4v[e]; }
+            if (y < 0 && w4v[e] > 0.0 && run > pk.target) { y = tok0 + e; wy = w4v[e]; }
+        }
+        if (y < 0) { y = ylast; wy = wlast; }
+        if (y < 0) break;
+        const int ey = y - tok0;
+        const double old_sum = (w0 + w1) + (w2 + w3);
+        const double new_sum = ((ey == 0 ? 0.0 : w0) + (ey == 1 ? 0.0 : w1)) + ((ey == 2 ? 0.0 : w2) + (ey == 3 ? 0.0 : w3));
+#pragma unroll
+        for (int j = 0; j < kMaxSeg; ++j)
+            if (j == pk.js) {
+                if (tid == owner) seg[j] = new_sum;
+                tot[j] = (tot[j] - old_sum) + new_sum;  // every thread keeps the same totals
+            }
         const double dy = wy / pk.W;
         if (tid == 0) {
+            gone[y >> 5] |= 1u << (y & 31);             // read again two barriers from here at the earliest
             w.pool_token[pool0 + count] = y;
             w.pool_v[pool0 + count] = v;
             w.pool_v0[pool0 + count] = v * dy;
         }
         v = v * (1.0 - dy);
         ++count;
-        __syncthreads();                                // the scratch of the sums is free again
     }
     if (tid == 0) w.counts[base + p] = count;
 }
@@ -245,15 +300,22 @@ hipError_t launch_build_threshold(const float* draft_logits, int V, const SeqArg
     const ThresholdWs w = carve(workspace, sa);
     ThresholdArgs ta;
     for (int s = 0; s < sa.n_seq; ++s) ta.t[s] = threshold[s];
+    // the expanding workgroups keep their row (4 bytes per token) and a bitmap (1 bit per token) in LDS
+    const int Vpad = (V + 31) & ~31;
+    const size_t dyn_bytes = (size_t)Vpad * 4 + Vpad / 8;
+    hipError_t ea = (V % 4 == 0)
+        ? hipFuncSetAttribute(reinterpret_cast<const void*>(&threshold_expand_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_bytes)
+        : hipFuncSetAttribute(reinterpret_cast<const void*>(&threshold_expand_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_bytes);
+    if (ea != hipSuccess) return ea;
     threshold_init_kernel<<<sa.n_seq, 256, 0, stream>>>(sa, tree, est_value, anc_mask, mask_words, n_built, w);
     int frontier = 1, levels = 0;                       // widest level over the sequences
     int state[4 * DYSPEC_MAX_SEQ];
     // a level adds at least one row or ends the loop, so this runs at most max N times
     while (frontier > 0) {
         if (V % 4 == 0)
-            threshold_expand_kernel<true><<<dim3(frontier, sa.n_seq), kBlock, 0, stream>>>(draft_logits, V, sa, ta, seed, w);
+            threshold_expand_kernel<true><<<dim3(frontier, sa.n_seq), kBlock, dyn_bytes, stream>>>(draft_logits, V, sa, ta, seed, w);
         else
-            threshold_expand_kernel<false><<<dim3(frontier, sa.n_seq), kBlock, 0, stream>>>(draft_logits, V, sa, ta, seed, w);
+            threshold_expand_kernel<false><<<dim3(frontier, sa.n_seq), kBlock, dyn_bytes, stream>>>(draft_logits, V, sa, ta, seed, w);
         threshold_commit_kernel<<<sa.n_seq, kBlock, 0, stream>>>(sa, seed, tree, est_value, anc_mask, mask_words, n_built, w);
         hipError_t e = hipMemcpyAsync(state, w.state, sizeof(int) * 4 * sa.n_seq, hipMemcpyDeviceToHost, stream);
         if (e != hipSuccess) return e;
