@@ -124,3 +124,27 @@ def test_layers_bad_arguments(dy):
     assert call(2, -1) == -1                    # negative stride
     assert call(2, 4) == -1                     # layers would lose their 16-byte alignment
     assert lib.dyspec_tree_attn_layers_workspace_bytes(ctypes.byref(cb), 0, 4, 4, 128) == 0
+
+
+@pytest.mark.parametrize("name,L", [("llama2_70b", 3), ("llama2_70b_n32", 3), ("llama2_7b", 4), ("llama2_70b_ragged8", 2)])
+def test_full_size_configs_through_the_stacked_call(dy, name, L):
+    """Benchmark shapes, the tree the builder makes for them, a few stacked layers: sampled rows of
+    every layer against the fp64 oracle (the N = 32 shape splits its prefix inside the stacked call)."""
+    from paper_2410_11744_amd import synth
+    cfg = synth.CONFIGS[name]
+    print(f"stacked full size {name} L={L}", flush=True)
+    batch = dy.Batch.from_sizes(cfg.n_nodes, cfg.prefix_len)
+    draft, _ = synth.make_logits(cfg)
+    built = dy.build_tree(torch.from_numpy(draft).cuda(), batch, cfg.temps, cfg.seed)
+    per_layer = [synth.make_attention_inputs(cfg, l, device="cuda") for l in range(L)]
+    dev = [torch.stack([per_layer[l][k] for l in range(L)]) for k in range(5)]
+    del per_layer
+    scale = 1.0 / math.sqrt(cfg.head_dim)
+    out = dy.tree_attn_layers(*dev, built.anc_mask, batch, scale)
+    torch.cuda.synchronize()
+    mask = built.anc_mask.cpu().numpy().view(np.uint64)
+    stack = [t.cpu() for t in dev]
+    nodes = [int(batch.node_offset[s + 1] - batch.node_offset[s]) for s in range(batch.n_seq)]
+    check_layers(dy, out, stack, mask, batch, nodes, cfg.n_q_heads, "bf16", scale, 5, max_rows=96)
+    one = dy.tree_attn(*[t[L - 1] for t in dev], built.anc_mask, batch, scale)
+    assert float((one.float() - out[L - 1].float()).abs().max()) <= 2.0 ** -6
