@@ -803,17 +803,19 @@ static int row_tiles(const SeqArgs& sa, int G, int* tile_off)
     return tiles;
 }
 
-// The kernel's parallelism is (row tiles) x (KV heads), one workgroup per CU at a time; when
-// that leaves most of the 256 CUs idle (narrow trees, few KV heads) the prefix is split until
-// the workgroups fill the chip once, as long as every split keeps at least two 64-key tiles
-// (one step of the walk) of every sequence's prefix.
+// The kernel's parallelism is (row tiles) x (KV heads) x layers, one workgroup per CU at a time;
+// when that leaves most of the 256 CUs idle (narrow trees, few KV heads) the prefix is split
+// until the workgroups fill the chip once, as long as every split keeps at least eight 64-key
+// tiles of every sequence's prefix: below that the partial results and the combining kernel
+// cost more than the shorter walk saves (measured: 1024 keys over 32 workgroups run best in
+// two or three parts, 4096 keys over 16 workgroups in eight).
 int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv, int layers)
 {
     const int groups = row_tiles(sa, Hq / Hkv, nullptr) * Hkv * layers;
     if (groups == 0) return 1;
     int min_tiles = 1 << 30;
     for (int s = 0; s < sa.n_seq; ++s) min_tiles = min(min_tiles, (sa.prefix_len[s] + kKeysPerTile - 1) / kKeysPerTile);
-    const int by_work = 256 / groups, by_prefix = min_tiles / 2;
+    const int by_work = 256 / groups, by_prefix = min_tiles / 8;
     return max(1, min(min(by_work, by_prefix), 32));
 }
 

@@ -122,9 +122,9 @@ def test_bf16_rising_scores_raise_the_reference(dy):
 
 
 @pytest.mark.parametrize("nodes,prefix,Hq,Hkv", [
-    ((32,), (4096,), 64, 8),               # 70B shape, narrow tree: 16 workgroups become 256
+    ((32,), (4096,), 64, 8),               # 70B shape, narrow tree: 16 workgroups become 128
     ((128,), (1024 + 37,), 8, 8),          # ragged last prefix tile inside the last split
-    ((40, 9), (64 * 11, 64 * 8 + 1), 4, 2),  # two splits with shares of uneven size, ragged batch
+    ((40, 9), (64 * 22, 64 * 17 + 1), 4, 2),  # two splits with shares of uneven size, ragged batch
 ])
 def test_bf16_prefix_split_matches_unsplit_and_oracle(dy, nodes, prefix, Hq, Hkv):
     batch = dy.Batch.from_sizes(nodes, prefix)

@@ -50,9 +50,9 @@ def check_layers(dy, out, stack, mask, batch, nodes, Hq, dtype, scale, seed, max
 
 
 @pytest.mark.parametrize("L,nodes,prefix,Hq,Hkv,d,seed", [
-    (3, (70,), (300,), 4, 4, 128, 1),                      # one-layer call would split the prefix, three layers not
+    (3, (70,), (1100,), 4, 4, 128, 1),                     # the one-layer call splits the prefix, the three-layer call less
     (2, (64, 7, 200, 1), (100, 1, 513, 64), 8, 2, 128, 2),  # ragged batch, GQA
-    (5, (40,), (64 * 12,), 4, 2, 128, 3),                  # few workgroups per layer: split stays on, per layer
+    (5, (40,), (64 * 24,), 4, 2, 128, 3),                  # few workgroups per layer: split stays on, per layer
     (4, (300,), (64,), 6, 2, 64, 4),                       # head_dim 64
     (1, (128,), (1024,), 4, 4, 128, 5),                    # a single layer through the stacked call
     (2, (33,), (0,), 4, 2, 128, 6),                        # no prefix
