@@ -175,6 +175,9 @@ def main() -> int:
                          "other can do, so the default and the headline value stay per layer)")
     ap.add_argument("--tree-builders", action="store_true",
                     help="instead of the step benchmark: time the greedy and the threshold tree builder on the workload's draft table")
+    ap.add_argument("--bf16-logits", action="store_true",
+                    help="verification reads bf16 logit tables (dyspec_verify_bf16): the fp32 tables rounded once, "
+                         "half the bytes of the statistics pass; the tree is built from the same rounded values")
     ap.add_argument("--dfs-order", action="store_true",
                     help="rename the tree's nodes in depth-first order (dyspec_dfs_reorder) before attention and "
                          "verification: subtrees become runs of rows, fewer tree tiles per workgroup")
@@ -209,6 +212,9 @@ def main() -> int:
 
     # ---- inputs (resident in HBM before timing)
     draft_h, target_h = synth.make_logits(cfg)
+    if args.bf16_logits:               # every consumer (builder, verification, oracle) sees the rounded values
+        draft_h = torch.from_numpy(draft_h).to(torch.bfloat16).float().numpy()
+        target_h = torch.from_numpy(target_h).to(torch.bfloat16).float().numpy()
     draft, target = torch.from_numpy(draft_h).to(dev), torch.from_numpy(target_h).to(dev)
     built = dy.build_tree(draft, batch, cfg.temps, cfg.seed)
     if args.dfs_order:
@@ -220,6 +226,7 @@ def main() -> int:
         idx_h = idx.cpu().numpy()
         draft_h, target_h = draft_h[idx_h], target_h[idx_h]
         built = dy.BuiltTrees(re.tree, built.est_value[idx].contiguous(), re.anc_mask, built.n_built)
+    v_draft, v_target = (draft.to(torch.bfloat16), target.to(torch.bfloat16)) if args.bf16_logits else (draft, target)
     # all layers' tensors live in five stacked allocations [L, ...]; the per-layer calls take views
     stacked = None
     for l in range(cfg.layers):
@@ -248,7 +255,7 @@ def main() -> int:
                 dy.tree_attn(q, kp, vp, kt, vt, built.anc_mask, batch, scale, out=outs[l])
         if ev:
             ev[1].record()
-        dy.verify(draft, target, batch, built.tree, cfg.temps, target_temps, cfg.seed, out=vout)
+        dy.verify(v_draft, v_target, batch, built.tree, cfg.temps, target_temps, cfg.seed, out=vout)
         if ev:
             ev[2].record()
 
@@ -349,7 +356,7 @@ def main() -> int:
     elt = 4 if cfg.dtype == "f32" else 2
     bytes_attn_launch = elt * cfg.head_dim * (2 * cfg.n_kv_heads * (batch.total_prefix + n_tokens)
                                               + 2 * cfg.n_q_heads * n_tokens)
-    bytes_step = bytes_attn_launch * cfg.layers + 8.0 * n_tokens * cfg.vocab
+    bytes_step = bytes_attn_launch * cfg.layers + (4.0 if args.bf16_logits else 8.0) * n_tokens * cfg.vocab
     hbm_gbs = bytes_step / (ms_per_step * 1e-3) / 1e9
     # which roof bounds the kernel at this shape: flops per algorithmic byte against the ridge
     ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
@@ -425,6 +432,7 @@ def main() -> int:
                                f"head_dim {cfg.head_dim}, prefix {list(cfg.prefix_len)}, tree rows {list(cfg.n_nodes)}, "
                                f"vocab {cfg.vocab}, batch {batch.n_seq}",
                    "node_order": "depth-first (dyspec_dfs_reorder)" if args.dfs_order else "creation order",
+                   "logit_tables": "bf16" if args.bf16_logits else "fp32",
                    "attention_call": "dyspec_tree_attn_layers, one call per step" if args.batched_layers
                                      else "dyspec_tree_attn, one call per layer",
                    "draft_temp": [float(x) for x in cfg.temps], "target_temp": [float(x) for x in target_temps],

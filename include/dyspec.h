@@ -275,6 +275,20 @@ dyspec_status dyspec_verify(const float* draft_logits, const float* target_logit
                             void* hip_stream);
 
 /*
+ * dyspec_verify_bf16 -- dyspec_verify on bf16 logit tables (DEVICE [sum N, vocab] bf16, rows
+ * dense, base pointers 16-byte aligned): the same operation (Algorithm 3), every logit
+ * widened to fp32 as it is read, half the bytes for the statistics pass.  All other
+ * arguments, outputs and error behaviour as for dyspec_verify.
+ */
+dyspec_status dyspec_verify_bf16(const void* draft_logits, const void* target_logits,
+                                 int32_t vocab, const dyspec_batch* batch, const dyspec_tree* tree,
+                                 const float* draft_temp, const float* target_temp, uint64_t seed,
+                                 int32_t emit_bonus, float* row_stats, float* accept_ratio,
+                                 int32_t* accepted_nodes, int32_t* n_accepted, int32_t* final_token,
+                                 float* min_margin, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream);
+
+/*
  * Measurement helpers (no part of the method): ceilings to set beside the published peaks
  * of the chip, and the clock the chip runs at under load.  All only launch; the caller times
  * them (HIP events on hip_stream).

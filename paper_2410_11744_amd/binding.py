@@ -21,7 +21,7 @@ WS_BUILD_TREE, WS_TREE_ATTN, WS_VERIFY = 0, 1, 2
 EXPORTS = ("dyspec_mask_words", "dyspec_workspace_bytes", "dyspec_status_string",
            "dyspec_build_tree", "dyspec_build_tree_threshold", "dyspec_build_tree_threshold_workspace_bytes",
            "dyspec_dfs_reorder", "dyspec_tree_attn", "dyspec_tree_attn_layers",
-           "dyspec_tree_attn_layers_workspace_bytes", "dyspec_verify",
+           "dyspec_tree_attn_layers_workspace_bytes", "dyspec_verify", "dyspec_verify_bf16",
            "dyspec_probe_mfma_bf16", "dyspec_probe_clock", "dyspec_probe_hbm_read")
 
 
@@ -80,6 +80,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.dyspec_verify.restype = I32
     lib.dyspec_verify.argtypes = [V, V, I32, PB, PT, ctypes.POINTER(F), ctypes.POINTER(F), U64, I32,
                                   V, V, V, V, V, V, V, SZ, V]
+    lib.dyspec_verify_bf16.restype = I32
+    lib.dyspec_verify_bf16.argtypes = lib.dyspec_verify.argtypes
     lib.dyspec_dfs_reorder.restype = I32
     lib.dyspec_dfs_reorder.argtypes = [PB, PT, PT, V, V, V]
     lib.dyspec_probe_mfma_bf16.restype = I32
@@ -418,21 +420,27 @@ class VerifyOutput:
 
 def verify(draft_logits, target_logits, batch: Batch, tree: Tree, draft_temp, target_temp, seed: int,
            emit_bonus: bool = True, out: Optional[VerifyOutput] = None, stream=None) -> VerifyOutput:
-    """dyspec_verify: per-row vocabulary softmax + tree rejection sampling (Algorithm 3)."""
+    """dyspec_verify / dyspec_verify_bf16 (by the tables' dtype): per-row vocabulary softmax + tree
+    rejection sampling (Algorithm 3)."""
+    import torch
     lib = load_library()
     total, V = batch.total_nodes, int(draft_logits.shape[1])
     if draft_logits.shape[0] != total or target_logits.shape != draft_logits.shape:
         raise ValueError("logit tables need one row per tree node")
+    if draft_logits.dtype != target_logits.dtype or draft_logits.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("logit tables must both be float32 or both be bfloat16")
+    bf16 = draft_logits.dtype == torch.bfloat16
+    entry = lib.dyspec_verify_bf16 if bf16 else lib.dyspec_verify
     if out is None:
         out = VerifyOutput.empty(batch, draft_logits.device)
     cb, ct = batch._c(), tree._c()
     da, dp = _temps(draft_temp, batch.n_seq)
     ta, tp = _temps(target_temp, batch.n_seq)
-    st = lib.dyspec_verify(_ptr(draft_logits, "float32"), _ptr(target_logits, "float32"), V, ctypes.byref(cb),
-                           ctypes.byref(ct), dp, tp, ctypes.c_uint64(seed), int(bool(emit_bonus)),
-                           _ptr(out.row_stats), _ptr(out.accept_ratio), _ptr(out.accepted_nodes), _ptr(out.n_accepted), _ptr(out.final_token),
-                           _ptr(out.min_margin), None, 0, _stream(stream))
-    _check(st, "dyspec_verify")
+    st = entry(_ptr(draft_logits), _ptr(target_logits), V, ctypes.byref(cb), ctypes.byref(ct), dp, tp,
+               ctypes.c_uint64(seed), int(bool(emit_bonus)), _ptr(out.row_stats), _ptr(out.accept_ratio),
+               _ptr(out.accepted_nodes), _ptr(out.n_accepted), _ptr(out.final_token), _ptr(out.min_margin), None, 0,
+               _stream(stream))
+    _check(st, "dyspec_verify_bf16" if bf16 else "dyspec_verify")
     return out
 
 

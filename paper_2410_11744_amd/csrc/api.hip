@@ -244,12 +244,11 @@ dyspec_status dyspec_tree_attn_layers(const void* q, const void* k_prefix, const
                             head_dim, dtype, softmax_scale, out, workspace, workspace_bytes, hip_stream);
 }
 
-dyspec_status dyspec_verify(const float* draft_logits, const float* target_logits, int32_t vocab,
-                            const dyspec_batch* batch, const dyspec_tree* tree, const float* draft_temp,
-                            const float* target_temp, uint64_t seed, int32_t emit_bonus,
-                            float* row_stats, float* accept_ratio, int32_t* accepted_nodes,
-                            int32_t* n_accepted, int32_t* final_token, float* min_margin,
-                            void*, size_t, void* hip_stream)
+static dyspec_status verify_common(const void* draft_logits, const void* target_logits, bool bf16_logits, int32_t vocab,
+                                   const dyspec_batch* batch, const dyspec_tree* tree, const float* draft_temp,
+                                   const float* target_temp, uint64_t seed, int32_t emit_bonus,
+                                   float* row_stats, float* accept_ratio, int32_t* accepted_nodes,
+                                   int32_t* n_accepted, int32_t* final_token, float* min_margin, void* hip_stream)
 {
     SeqArgs sa;
     const dyspec_status st = check_batch(batch, false, &sa);
@@ -264,10 +263,33 @@ dyspec_status dyspec_verify(const float* draft_logits, const float* target_logit
         sa.temp_d[s] = draft_temp[s];
         sa.temp_t[s] = target_temp[s];
     }
-    const hipError_t e = launch_verify(draft_logits, target_logits, vocab, sa, *tree, seed, emit_bonus != 0,
+    const hipError_t e = launch_verify(draft_logits, target_logits, bf16_logits, vocab, sa, *tree, seed, emit_bonus != 0,
                                        row_stats, accept_ratio, accepted_nodes, n_accepted, final_token,
                                        min_margin, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
+}
+
+dyspec_status dyspec_verify(const float* draft_logits, const float* target_logits, int32_t vocab,
+                            const dyspec_batch* batch, const dyspec_tree* tree, const float* draft_temp,
+                            const float* target_temp, uint64_t seed, int32_t emit_bonus,
+                            float* row_stats, float* accept_ratio, int32_t* accepted_nodes,
+                            int32_t* n_accepted, int32_t* final_token, float* min_margin,
+                            void*, size_t, void* hip_stream)
+{
+    return verify_common(draft_logits, target_logits, false, vocab, batch, tree, draft_temp, target_temp, seed, emit_bonus,
+                         row_stats, accept_ratio, accepted_nodes, n_accepted, final_token, min_margin, hip_stream);
+}
+
+dyspec_status dyspec_verify_bf16(const void* draft_logits, const void* target_logits, int32_t vocab,
+                                 const dyspec_batch* batch, const dyspec_tree* tree, const float* draft_temp,
+                                 const float* target_temp, uint64_t seed, int32_t emit_bonus,
+                                 float* row_stats, float* accept_ratio, int32_t* accepted_nodes,
+                                 int32_t* n_accepted, int32_t* final_token, float* min_margin,
+                                 void*, size_t, void* hip_stream)
+{
+    if ((reinterpret_cast<size_t>(draft_logits) | reinterpret_cast<size_t>(target_logits)) & 1) return DYSPEC_BAD_ARG;
+    return verify_common(draft_logits, target_logits, true, vocab, batch, tree, draft_temp, target_temp, seed, emit_bonus,
+                         row_stats, accept_ratio, accepted_nodes, n_accepted, final_token, min_margin, hip_stream);
 }
 
 }  // extern "C"

@@ -44,7 +44,7 @@ __device__ __forceinline__ void row_segment_sums(const float* __restrict__ row, 
                                                  float* fred, double* m_out, double (&seg)[kMaxSeg])
 {
     float x[kMaxSeg][4];
-    load_row<VEC>(row, V, x);
+    load_row<VEC, float>(row, V, x);
     float mx[1] = { -INFINITY };
 #pragma unroll
     for (int j = 0; j < kMaxSeg; ++j)

@@ -56,7 +56,7 @@ hipError_t launch_build_threshold(const float* draft_logits, int V, const SeqArg
 size_t build_threshold_workspace_bytes(const SeqArgs& sa);
 hipError_t launch_dfs_reorder(const SeqArgs& sa, const dyspec_tree& in, const dyspec_tree& out, int* order,
                               uint64_t* mask_out, int mask_words, hipStream_t stream);
-hipError_t launch_verify(const float* draft_logits, const float* target_logits, int V,
+hipError_t launch_verify(const void* draft_logits, const void* target_logits, bool bf16_logits, int V,
                          const SeqArgs& sa, const dyspec_tree& tree, uint64_t seed, int emit_bonus,
                          float* row_stats, float* accept_ratio, int* accepted_nodes, int* n_accepted,
                          int* final_token, float* min_margin, hipStream_t stream);

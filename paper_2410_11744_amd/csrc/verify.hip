@@ -43,9 +43,9 @@ __device__ __forceinline__ void block_argmax(float& m, int& i, float* red_m, int
     }
 }
 
-template <bool VEC>
+template <bool VEC, typename T>
 __global__ __launch_bounds__(kBlock) void softmax_stats_kernel(
-    const float* __restrict__ draft_logits, const float* __restrict__ target_logits, int V,
+    const T* __restrict__ draft_logits, const T* __restrict__ target_logits, int V,
     SeqArgs sa, float* __restrict__ row_stats, float* __restrict__ accept_ratio)
 {
     __shared__ float fred[kWaves * 2];
@@ -55,8 +55,8 @@ __global__ __launch_bounds__(kBlock) void softmax_stats_kernel(
     const bool greedy = sa.temp_t[seq] == 0.0f;
     const float inv_td = 1.0f / sa.temp_d[seq], inv_tt = greedy ? 1.0f : 1.0f / sa.temp_t[seq];
     float D[kMaxSeg][4], R[kMaxSeg][4];
-    load_row<VEC>(draft_logits + (size_t)row * V, V, D);
-    load_row<VEC>(target_logits + (size_t)row * V, V, R);
+    load_row<VEC, T>(draft_logits + (size_t)row * V, V, D);
+    load_row<VEC, T>(target_logits + (size_t)row * V, V, R);
     float top = -INFINITY;
     int top_i = 0;
     if (greedy) {
@@ -110,33 +110,58 @@ __device__ __forceinline__ void merge_stat(float& m, float& s, float m2, float s
     m = M;
 }
 
+// Sixteen bytes of a logits row: four fp32 or eight bf16 values.
+template <typename T> struct Piece;
+template <> struct Piece<float> {
+    static constexpr int N = 4;
+    __device__ static __forceinline__ void unpack(const uint4& r, float (&f)[4])
+    {
+        f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+    }
+};
+template <> struct Piece<__bf16> {
+    static constexpr int N = 8;
+    __device__ static __forceinline__ void unpack(const uint4& r, float (&f)[8])
+    {
+        f[0] = bf16_bits_to_float(r.x & 0xffffu); f[1] = bf16_bits_to_float(r.x >> 16);
+        f[2] = bf16_bits_to_float(r.y & 0xffffu); f[3] = bf16_bits_to_float(r.y >> 16);
+        f[4] = bf16_bits_to_float(r.z & 0xffffu); f[5] = bf16_bits_to_float(r.z >> 16);
+        f[6] = bf16_bits_to_float(r.w & 0xffffu); f[7] = bf16_bits_to_float(r.w >> 16);
+    }
+};
+
+// For V a multiple of the values in a 16-byte piece (4 fp32, 8 bf16).
+template <typename T>
 __global__ __launch_bounds__(kStatThreads) void softmax_stats_stream_kernel(
-    const float* __restrict__ draft_logits, const float* __restrict__ target_logits, int V,
+    const T* __restrict__ draft_logits, const T* __restrict__ target_logits, int V,
     SeqArgs sa, float* __restrict__ row_stats, float* __restrict__ accept_ratio)
 {
+    constexpr int PN = Piece<T>::N;
     __shared__ float red[2 * (kStatThreads / kWave)];
     const int row = blockIdx.x, table = blockIdx.y;
     const int seq = find_seq(sa, row);
-    const float4* __restrict__ x = reinterpret_cast<const float4*>((table ? target_logits : draft_logits) + (size_t)row * V);
-    const int n4 = V / 4;
+    const uint4* __restrict__ x = reinterpret_cast<const uint4*>((table ? target_logits : draft_logits) + (size_t)row * V);
+    const int n16 = V / PN;
+    const uint4 none = Piece<T>::N == 4 ? make_uint4(0xff800000u, 0xff800000u, 0xff800000u, 0xff800000u)     // -inf
+                                        : make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u);
     if (table == 1 && sa.temp_t[seq] == 0.0f) {                  // whole workgroup takes this branch
         __shared__ int ired[kStatThreads / kWave];
         float top = -INFINITY;
         int top_i = 0;
-        for (int i0 = threadIdx.x; i0 < n4; i0 += kStatThreads * kStatUnroll) {
-            float4 v[kStatUnroll];
+        for (int i0 = threadIdx.x; i0 < n16; i0 += kStatThreads * kStatUnroll) {
+            uint4 v[kStatUnroll];
 #pragma unroll
             for (int u = 0; u < kStatUnroll; ++u) {
                 const int i = i0 + u * kStatThreads;
-                v[u] = (i < n4) ? x[i] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+                v[u] = (i < n16) ? x[i] : none;
             }
 #pragma unroll
             for (int u = 0; u < kStatUnroll; ++u) {              // ascending index per thread
-                const int i = 4 * (i0 + u * kStatThreads);
-                if (v[u].x > top) { top = v[u].x; top_i = i; }
-                if (v[u].y > top) { top = v[u].y; top_i = i + 1; }
-                if (v[u].z > top) { top = v[u].z; top_i = i + 2; }
-                if (v[u].w > top) { top = v[u].w; top_i = i + 3; }
+                const int i = PN * (i0 + u * kStatThreads);
+                float f[PN];
+                Piece<T>::unpack(v[u], f);
+#pragma unroll
+                for (int e = 0; e < PN; ++e) if (f[e] > top) { top = f[e]; top_i = i + e; }
             }
         }
         block_argmax<kStatThreads / kWave>(top, top_i, red, ired);
@@ -147,25 +172,30 @@ __global__ __launch_bounds__(kStatThreads) void softmax_stats_stream_kernel(
     const float inv_t = 1.0f / (table ? sa.temp_t[seq] : sa.temp_d[seq]);
     const float c = inv_t * 1.4426950408889634f;
     float m = -INFINITY, s = 0.0f;
-    for (int i0 = threadIdx.x; i0 < n4; i0 += kStatThreads * kStatUnroll) {
-        float4 v[kStatUnroll];
+    for (int i0 = threadIdx.x; i0 < n16; i0 += kStatThreads * kStatUnroll) {
+        uint4 v[kStatUnroll];
 #pragma unroll
         for (int u = 0; u < kStatUnroll; ++u) {
             const int i = i0 + u * kStatThreads;
-            v[u] = (i < n4) ? x[i] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            v[u] = (i < n16) ? x[i] : none;
         }
+        float f[kStatUnroll][PN];
         float cm = -INFINITY;
 #pragma unroll
-        for (int u = 0; u < kStatUnroll; ++u) cm = fmaxf(fmaxf(cm, fmaxf(v[u].x, v[u].y)), fmaxf(v[u].z, v[u].w));
+        for (int u = 0; u < kStatUnroll; ++u) {
+            Piece<T>::unpack(v[u], f[u]);
+#pragma unroll
+            for (int e = 0; e < PN; e += 2) cm = fmaxf(cm, fmaxf(f[u][e], f[u][e + 1]));
+        }
         const float M = fmaxf(m, cm);
         if (M == -INFINITY) continue;                            // nothing but -inf logits so far
         float acc = s * __builtin_amdgcn_exp2f((m - M) * c);
         const float Mc = M * c;
 #pragma unroll
-        for (int u = 0; u < kStatUnroll; ++u) {
-            acc += __builtin_amdgcn_exp2f(fmaf(v[u].x, c, -Mc)) + __builtin_amdgcn_exp2f(fmaf(v[u].y, c, -Mc));
-            acc += __builtin_amdgcn_exp2f(fmaf(v[u].z, c, -Mc)) + __builtin_amdgcn_exp2f(fmaf(v[u].w, c, -Mc));
-        }
+        for (int u = 0; u < kStatUnroll; ++u)
+#pragma unroll
+            for (int e = 0; e < PN; e += 2)
+                acc += __builtin_amdgcn_exp2f(fmaf(f[u][e], c, -Mc)) + __builtin_amdgcn_exp2f(fmaf(f[u][e + 1], c, -Mc));
         s = acc;
         m = M;
     }
@@ -193,9 +223,9 @@ struct WalkShared {
     float bcast[2];
 };
 
-template <bool VEC>
+template <bool VEC, typename T>
 __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
-    const float* __restrict__ draft_logits, const float* __restrict__ target_logits, int V,
+    const T* __restrict__ draft_logits, const T* __restrict__ target_logits, int V,
     SeqArgs sa, dyspec_tree tree, uint64_t seed, int emit_bonus,
     const float* __restrict__ row_stats, float* __restrict__ accept_ratio,
     int* __restrict__ accepted_nodes, int* __restrict__ n_accepted,
@@ -219,9 +249,9 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
     // probability of token y under row `node`: draft (.x) and target (.y)
     auto prob_pair = [&](int node, int y) {
         const float4 st = sh.stats[node];
-        const float d = expf(draft_logits[(size_t)(base + node) * V + y] * inv_td - st.x) / st.y;
+        const float d = expf(logit_to_float(draft_logits[(size_t)(base + node) * V + y]) * inv_td - st.x) / st.y;
         const float r = greedy ? ((float)y == st.w ? 1.0f : 0.0f)
-                               : expf(target_logits[(size_t)(base + node) * V + y] * inv_tt - st.z) / st.w;
+                               : expf(logit_to_float(target_logits[(size_t)(base + node) * V + y]) * inv_tt - st.z) / st.w;
         return make_float2(d, r);
     };
     auto ratio_of = [](float d, float r) { return (d > 0.0f) ? r / d : (r > 0.0f ? INFINITY : 0.0f); };
@@ -238,8 +268,8 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
         float D[kMaxSeg][4], R[kMaxSeg][4];
         auto load_rows = [&](bool want_draft) {
             const float4 st = sh.stats[cur];
-            if (!greedy) load_row<VEC>(target_logits + (size_t)(base + cur) * V, V, R);
-            if (want_draft) load_row<VEC>(draft_logits + (size_t)(base + cur) * V, V, D);
+            if (!greedy) load_row<VEC, T>(target_logits + (size_t)(base + cur) * V, V, R);
+            if (want_draft) load_row<VEC, T>(draft_logits + (size_t)(base + cur) * V, V, D);
             const float id = 1.0f / st.y, it = greedy ? 0.0f : 1.0f / st.w;
             const int top = greedy ? (int)st.w : -1;
 #pragma unroll
@@ -350,24 +380,41 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
     }
 }
 
-hipError_t launch_verify(const float* draft_logits, const float* target_logits, int V,
+template <typename T>
+static hipError_t launch_verify_t(const T* draft_logits, const T* target_logits, int V,
+                                  const SeqArgs& sa, const dyspec_tree& tree, uint64_t seed, int emit_bonus,
+                                  float* row_stats, float* accept_ratio, int* accepted_nodes, int* n_accepted,
+                                  int* final_token, float* min_margin, hipStream_t stream)
+{
+    const int rows = sa.node_off[sa.n_seq];
+    // statistics: the streaming form wants whole 16-byte pieces; the walk's row loads four tokens per thread
+    if (V % Piece<T>::N == 0)
+        softmax_stats_stream_kernel<T><<<dim3(rows, 2), kStatThreads, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
+    else if (V % 4 == 0)
+        softmax_stats_kernel<true, T><<<rows, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
+    else
+        softmax_stats_kernel<false, T><<<rows, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
+    if (V % 4 == 0)
+        verify_walk_kernel<true, T><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, tree, seed, emit_bonus,
+                                                                     row_stats, accept_ratio, accepted_nodes, n_accepted,
+                                                                     final_token, min_margin);
+    else
+        verify_walk_kernel<false, T><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, tree, seed, emit_bonus,
+                                                                      row_stats, accept_ratio, accepted_nodes, n_accepted,
+                                                                      final_token, min_margin);
+    return hipGetLastError();
+}
+
+hipError_t launch_verify(const void* draft_logits, const void* target_logits, bool bf16_logits, int V,
                          const SeqArgs& sa, const dyspec_tree& tree, uint64_t seed, int emit_bonus,
                          float* row_stats, float* accept_ratio, int* accepted_nodes, int* n_accepted,
                          int* final_token, float* min_margin, hipStream_t stream)
 {
-    const int rows = sa.node_off[sa.n_seq];
-    if (V % 4 == 0) {
-        softmax_stats_stream_kernel<<<dim3(rows, 2), kStatThreads, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
-        verify_walk_kernel<true><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, tree, seed, emit_bonus,
-                                                                  row_stats, accept_ratio, accepted_nodes, n_accepted,
-                                                                  final_token, min_margin);
-    } else {
-        softmax_stats_kernel<false><<<rows, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
-        verify_walk_kernel<false><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, tree, seed, emit_bonus,
-                                                                   row_stats, accept_ratio, accepted_nodes, n_accepted,
-                                                                   final_token, min_margin);
-    }
-    return hipGetLastError();
+    if (bf16_logits)
+        return launch_verify_t(static_cast<const __bf16*>(draft_logits), static_cast<const __bf16*>(target_logits), V, sa, tree,
+                               seed, emit_bonus, row_stats, accept_ratio, accepted_nodes, n_accepted, final_token, min_margin, stream);
+    return launch_verify_t(static_cast<const float*>(draft_logits), static_cast<const float*>(target_logits), V, sa, tree,
+                           seed, emit_bonus, row_stats, accept_ratio, accepted_nodes, n_accepted, final_token, min_margin, stream);
 }
 
 }  // namespace dyspec

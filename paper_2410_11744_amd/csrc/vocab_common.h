@@ -11,23 +11,35 @@ namespace dyspec {
 
 __device__ __forceinline__ int tok_index(int j, int e) { return j * kSeg + 4 * (int)threadIdx.x + e; }
 
-// Load one logits row; positions >= V read as -inf.  VEC: V % 4 == 0 (row is 16-byte aligned).
-template <bool VEC>
-__device__ __forceinline__ void load_row(const float* __restrict__ row, int V, float (&x)[kMaxSeg][4])
+// Logit tables are fp32 or bf16.  A bf16 value is the upper half of the fp32 with the same value.
+__device__ __forceinline__ float logit_to_float(float x) { return x; }
+__device__ __forceinline__ float logit_to_float(__bf16 x) { return (float)x; }
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+// Load one logits row; positions >= V read as -inf.  VEC: V % 4 == 0 (a thread's four tokens are
+// one aligned 16-byte (fp32) or 8-byte (bf16) load).
+template <bool VEC, typename T>
+__device__ __forceinline__ void load_row(const T* __restrict__ row, int V, float (&x)[kMaxSeg][4])
 {
 #pragma unroll
     for (int j = 0; j < kMaxSeg; ++j) {
         const int i0 = tok_index(j, 0);
         if (VEC) {
             if (i0 < V) {
-                const float4 v = *reinterpret_cast<const float4*>(row + i0);
-                x[j][0] = v.x; x[j][1] = v.y; x[j][2] = v.z; x[j][3] = v.w;
+                if constexpr (sizeof(T) == 4) {
+                    const float4 v = *reinterpret_cast<const float4*>(row + i0);
+                    x[j][0] = v.x; x[j][1] = v.y; x[j][2] = v.z; x[j][3] = v.w;
+                } else {
+                    const uint2 v = *reinterpret_cast<const uint2*>(row + i0);
+                    x[j][0] = bf16_bits_to_float(v.x & 0xffffu); x[j][1] = bf16_bits_to_float(v.x >> 16);
+                    x[j][2] = bf16_bits_to_float(v.y & 0xffffu); x[j][3] = bf16_bits_to_float(v.y >> 16);
+                }
             } else {
                 x[j][0] = x[j][1] = x[j][2] = x[j][3] = -INFINITY;
             }
         } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) x[j][e] = (i0 + e < V) ? row[i0 + e] : -INFINITY;
+            for (int e = 0; e < 4; ++e) x[j][e] = (i0 + e < V) ? logit_to_float(row[i0 + e]) : -INFINITY;
         }
     }
 }
