@@ -110,6 +110,79 @@ __device__ __forceinline__ void merge_stat(float& m, float& s, float m2, float s
     m = M;
 }
 
+__global__ __launch_bounds__(kStatThreads) void softmax_stats_stream_kernel(
+    const float* __restrict__ draft_logits, const float* __restrict__ target_logits, int V,
+    SeqArgs sa, float* __restrict__ row_stats, float* __restrict__ accept_ratio)
+{
+    __shared__ float red[2 * (kStatThreads / kWave)];
+    const int row = blockIdx.x, table = blockIdx.y;
+    const int seq = find_seq(sa, row);
+    const float4* __restrict__ x = reinterpret_cast<const float4*>((table ? target_logits : draft_logits) + (size_t)row * V);
+    const int n4 = V / 4;
+    if (table == 1 && sa.temp_t[seq] == 0.0f) {                  // whole workgroup takes this branch
+        __shared__ int ired[kStatThreads / kWave];
+        float top = -INFINITY;
+        int top_i = 0;
+        for (int i0 = threadIdx.x; i0 < n4; i0 += kStatThreads * kStatUnroll) {
+            float4 v[kStatUnroll];
+#pragma unroll
+            for (int u = 0; u < kStatUnroll; ++u) {
+                const int i = i0 + u * kStatThreads;
+                v[u] = (i < n4) ? x[i] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            }
+#pragma unroll
+            for (int u = 0; u < kStatUnroll; ++u) {              // ascending index per thread
+                const int i = 4 * (i0 + u * kStatThreads);
+                if (v[u].x > top) { top = v[u].x; top_i = i; }
+                if (v[u].y > top) { top = v[u].y; top_i = i + 1; }
+                if (v[u].z > top) { top = v[u].z; top_i = i + 2; }
+                if (v[u].w > top) { top = v[u].w; top_i = i + 3; }
+            }
+        }
+        block_argmax<kStatThreads / kWave>(top, top_i, red, ired);
+        if (threadIdx.x == 0)
+            *reinterpret_cast<float2*>(row_stats + 4 * (size_t)row + 2) = make_float2(top, (float)top_i);
+        return;
+    }
+    const float inv_t = 1.0f / (table ? sa.temp_t[seq] : sa.temp_d[seq]);
+    const float c = inv_t * 1.4426950408889634f;
+    float m = -INFINITY, s = 0.0f;
+    for (int i0 = threadIdx.x; i0 < n4; i0 += kStatThreads * kStatUnroll) {
+        float4 v[kStatUnroll];
+#pragma unroll
+        for (int u = 0; u < kStatUnroll; ++u) {
+            const int i = i0 + u * kStatThreads;
+            v[u] = (i < n4) ? x[i] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        }
+        float cm = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < kStatUnroll; ++u) cm = fmaxf(fmaxf(cm, fmaxf(v[u].x, v[u].y)), fmaxf(v[u].z, v[u].w));
+        const float M = fmaxf(m, cm);
+        if (M == -INFINITY) continue;                            // nothing but -inf logits so far
+        float acc = s * __builtin_amdgcn_exp2f((m - M) * c);
+        const float Mc = M * c;
+#pragma unroll
+        for (int u = 0; u < kStatUnroll; ++u) {
+            acc += __builtin_amdgcn_exp2f(fmaf(v[u].x, c, -Mc)) + __builtin_amdgcn_exp2f(fmaf(v[u].y, c, -Mc));
+            acc += __builtin_amdgcn_exp2f(fmaf(v[u].z, c, -Mc)) + __builtin_amdgcn_exp2f(fmaf(v[u].w, c, -Mc));
+        }
+        s = acc;
+        m = M;
+    }
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) merge_stat(m, s, __shfl_xor(m, o, kWave), __shfl_xor(s, o, kWave), c);
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) { red[2 * wave] = m; red[2 * wave + 1] = s; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = red[0]; s = red[1];
+#pragma unroll
+        for (int w = 1; w < kStatThreads / kWave; ++w) merge_stat(m, s, red[2 * w], red[2 * w + 1], c);
+        *reinterpret_cast<float2*>(row_stats + 4 * (size_t)row + 2 * table) = make_float2(m * inv_t, s);
+        if (table == 0) accept_ratio[row] = (row == sa.node_off[seq]) ? 0.0f : -2.0f;   // -2: not tested by the walk
+    }
+}
+
 // Sixteen bytes of a logits row: four fp32 or eight bf16 values.
 template <typename T> struct Piece;
 template <> struct Piece<float> {
@@ -130,9 +203,10 @@ template <> struct Piece<__bf16> {
     }
 };
 
-// For V a multiple of the values in a 16-byte piece (4 fp32, 8 bf16).
+// The streaming form for tables of type T read in 16-byte pieces; V a multiple of the values in
+// a piece.  (fp32 tables take the kernel above, written out for four values per piece.)
 template <typename T>
-__global__ __launch_bounds__(kStatThreads) void softmax_stats_stream_kernel(
+__global__ __launch_bounds__(kStatThreads) void softmax_stats_stream_pieces_kernel(
     const T* __restrict__ draft_logits, const T* __restrict__ target_logits, int V,
     SeqArgs sa, float* __restrict__ row_stats, float* __restrict__ accept_ratio)
 {
@@ -140,26 +214,29 @@ __global__ __launch_bounds__(kStatThreads) void softmax_stats_stream_kernel(
     __shared__ float red[2 * (kStatThreads / kWave)];
     const int row = blockIdx.x, table = blockIdx.y;
     const int seq = find_seq(sa, row);
-    const uint4* __restrict__ x = reinterpret_cast<const uint4*>((table ? target_logits : draft_logits) + (size_t)row * V);
+    // pieces are fetched as float4 (one 16-byte load each; the bits are taken apart afterwards)
+    const float4* __restrict__ x = reinterpret_cast<const float4*>((table ? target_logits : draft_logits) + (size_t)row * V);
     const int n16 = V / PN;
-    const uint4 none = Piece<T>::N == 4 ? make_uint4(0xff800000u, 0xff800000u, 0xff800000u, 0xff800000u)     // -inf
-                                        : make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u);
+    // a piece past the end re-reads the last piece and is then set to -inf
+    auto fetch = [&](int i) __attribute__((always_inline)) { return x[min(i, n16 - 1)]; };
+    auto open_piece = [&](const float4& r, bool valid, float (&f)[PN]) __attribute__((always_inline)) {
+        Piece<T>::unpack(make_uint4(__float_as_uint(r.x), __float_as_uint(r.y), __float_as_uint(r.z), __float_as_uint(r.w)), f);
+#pragma unroll
+        for (int e = 0; e < PN; ++e) f[e] = valid ? f[e] : -INFINITY;
+    };
     if (table == 1 && sa.temp_t[seq] == 0.0f) {                  // whole workgroup takes this branch
         __shared__ int ired[kStatThreads / kWave];
         float top = -INFINITY;
         int top_i = 0;
         for (int i0 = threadIdx.x; i0 < n16; i0 += kStatThreads * kStatUnroll) {
-            uint4 v[kStatUnroll];
+            float4 v[kStatUnroll];
 #pragma unroll
-            for (int u = 0; u < kStatUnroll; ++u) {
-                const int i = i0 + u * kStatThreads;
-                v[u] = (i < n16) ? x[i] : none;
-            }
+            for (int u = 0; u < kStatUnroll; ++u) v[u] = fetch(i0 + u * kStatThreads);
 #pragma unroll
             for (int u = 0; u < kStatUnroll; ++u) {              // ascending index per thread
                 const int i = PN * (i0 + u * kStatThreads);
                 float f[PN];
-                Piece<T>::unpack(v[u], f);
+                open_piece(v[u], i0 + u * kStatThreads < n16, f);
 #pragma unroll
                 for (int e = 0; e < PN; ++e) if (f[e] > top) { top = f[e]; top_i = i + e; }
             }
@@ -173,17 +250,14 @@ __global__ __launch_bounds__(kStatThreads) void softmax_stats_stream_kernel(
     const float c = inv_t * 1.4426950408889634f;
     float m = -INFINITY, s = 0.0f;
     for (int i0 = threadIdx.x; i0 < n16; i0 += kStatThreads * kStatUnroll) {
-        uint4 v[kStatUnroll];
+        float4 v[kStatUnroll];
 #pragma unroll
-        for (int u = 0; u < kStatUnroll; ++u) {
-            const int i = i0 + u * kStatThreads;
-            v[u] = (i < n16) ? x[i] : none;
-        }
+        for (int u = 0; u < kStatUnroll; ++u) v[u] = fetch(i0 + u * kStatThreads);
         float f[kStatUnroll][PN];
         float cm = -INFINITY;
 #pragma unroll
         for (int u = 0; u < kStatUnroll; ++u) {
-            Piece<T>::unpack(v[u], f[u]);
+            open_piece(v[u], i0 + u * kStatThreads < n16, f[u]);
 #pragma unroll
             for (int e = 0; e < PN; e += 2) cm = fmaxf(cm, fmaxf(f[u][e], f[u][e + 1]));
         }
@@ -388,8 +462,12 @@ static hipError_t launch_verify_t(const T* draft_logits, const T* target_logits,
 {
     const int rows = sa.node_off[sa.n_seq];
     // statistics: the streaming form wants whole 16-byte pieces; the walk's row loads four tokens per thread
-    if (V % Piece<T>::N == 0)
-        softmax_stats_stream_kernel<T><<<dim3(rows, 2), kStatThreads, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
+    if (V % Piece<T>::N == 0) {
+        if constexpr (sizeof(T) == 4)
+            softmax_stats_stream_kernel<<<dim3(rows, 2), kStatThreads, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
+        else
+            softmax_stats_stream_pieces_kernel<T><<<dim3(rows, 2), kStatThreads, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
+    }
     else if (V % 4 == 0)
         softmax_stats_kernel<true, T><<<rows, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
     else
