@@ -1,0 +1,105 @@
+"""GPU parity on seeded random shapes: ragged batches, odd sizes and mixed options drawn from the
+ranges the library accepts, each checked against the oracle like the hand-picked cases."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import compare_trees, compare_verify, oracle_trees
+from test_gpu_tree_attn import run_and_compare
+from test_gpu_tree_attn_layers import check_layers, stacked_case
+from test_gpu_threshold import compare_threshold_trees
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def dy():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2410_11744_amd as m
+    m.load_library()
+    return m
+
+
+HEADS = [(8, 8), (8, 2), (4, 1), (6, 2), (16, 4), (12, 12), (5, 5)]
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_attention_random_shapes(dy, seed):
+    rng = np.random.default_rng(9000 + seed)
+    n_seq = int(rng.integers(1, 6))
+    nodes = tuple(int(x) for x in rng.integers(1, 260, n_seq))
+    prefix = tuple(int(x) for x in rng.choice([0, 1, 17, 64, 65, 127, 128, 300, 513, 700], n_seq))
+    Hq, Hkv = HEADS[int(rng.integers(0, len(HEADS)))]
+    d = int(rng.choice([64, 128]))
+    run_and_compare(dy, nodes, prefix, Hq, Hkv, d, "bf16", 9100 + seed, max_rows=1200,
+                    shallow=bool(rng.integers(0, 2)))
+    if seed % 4 == 0:                                   # the stacked call on the same kind of shape
+        L = int(rng.integers(2, 4))
+        batch = dy.Batch.from_sizes(nodes, prefix)
+        stack, mask = stacked_case(L, nodes, prefix, Hq, Hkv, d, "bf16", 9200 + seed)
+        dev = [t.cuda() if t.numel() else torch.empty(t.shape, dtype=t.dtype, device="cuda") for t in stack]
+        out = dy.tree_attn_layers(*dev, torch.from_numpy(mask.view(np.int64)).cuda(), batch, 1.0 / math.sqrt(d))
+        torch.cuda.synchronize()
+        check_layers(dy, out, stack, mask, batch, nodes, Hq, "bf16", 1.0 / math.sqrt(d), seed, max_rows=600)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_build_and_verify_random_shapes(dy, seed):
+    rng = np.random.default_rng(9500 + seed)
+    n_seq = int(rng.integers(1, 6))
+    nodes = tuple(int(x) for x in rng.integers(1, 130, n_seq))
+    V = int(rng.choice([5, 77, 1000, 4096, 5003, 12000]))
+    td = tuple(float(x) for x in rng.choice([0.5, 0.7, 1.0, 1.3], n_seq))
+    tt = tuple(float(x) for x in rng.choice([0.0, 0.6, 1.0], n_seq))
+    sigma, tsigma = float(rng.choice([1.0, 2.5, 4.0])), float(rng.choice([0.3, 1.0, 2.0]))
+    print(f"random build/verify nodes={nodes} V={V} td={td} tt={tt}", flush=True)
+    d = (rng.standard_normal((sum(nodes), V)) * sigma).astype(np.float32)
+    t = (d + rng.standard_normal((sum(nodes), V)) * tsigma).astype(np.float32)
+    bf16 = seed % 3 == 2
+    if bf16:                                            # bf16 tables for verification: everyone reads the rounded values
+        d = torch.from_numpy(d).to(torch.bfloat16).float().numpy()
+        t = torch.from_numpy(t).to(torch.bfloat16).float().numpy()
+    batch = dy.Batch.from_sizes(nodes)
+    dd, tg = torch.from_numpy(d).cuda(), torch.from_numpy(t).cuda()
+    built = dy.build_tree(dd, batch, td, seed)
+    torch.cuda.synchronize()
+    full = compare_trees(built, batch, oracle_trees(d, nodes, td, seed))
+    assert full >= n_seq - (2 if bf16 else 1)           # sequences with a margin below 1e-9 are not compared
+    g = {k: getattr(built.tree, k).cpu().numpy() for k in ("token", "first_child", "next_sibling")}
+    trees = [tuple(g[k][int(batch.node_offset[s]):int(batch.node_offset[s + 1])] for k in ("token", "first_child", "next_sibling"))
+             for s in range(n_seq)]
+    vd, vt = (dd.to(torch.bfloat16), tg.to(torch.bfloat16)) if bf16 else (dd, tg)
+    for bonus in (True, False):
+        out = dy.verify(vd, vt, batch, built.tree, td, tt, 77 + seed, emit_bonus=bonus)
+        torch.cuda.synchronize()
+        compared, skipped = compare_verify(out, batch, trees, d, t, td, tt, 77 + seed, emit_bonus=bonus)
+        assert compared + skipped == n_seq and compared >= max(1, n_seq - 2)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_threshold_builder_random_shapes(dy, seed):
+    rng = np.random.default_rng(9800 + seed)
+    n_seq = int(rng.integers(1, 5))
+    nodes = tuple(int(x) for x in rng.integers(1, 200, n_seq))
+    V = int(rng.choice([9, 130, 1000, 4096, 5003]))
+    temps = tuple(float(x) for x in rng.choice([0.5, 0.7, 1.0], n_seq))
+    thr = tuple(float(x) for x in rng.choice([0.3, 0.1, 0.03, 0.01, 0.003], n_seq))
+    print(f"random threshold nodes={nodes} V={V} t={thr}", flush=True)
+    d = (rng.standard_normal((sum(nodes), V)) * float(rng.choice([2.0, 4.0]))).astype(np.float32)
+    batch = dy.Batch.from_sizes(nodes)
+    built, levels = dy.build_tree_threshold(torch.from_numpy(d).cuda(), batch, temps, thr, seed)
+    assert compare_threshold_trees(built, batch, d, temps, thr, seed) >= n_seq - 1
+    # and a depth-first renaming of whatever was built keeps verification's outcome
+    re = dy.dfs_reorder(built.tree, batch)
+    torch.cuda.synchronize()
+    par = built.tree.parent.cpu().numpy()
+    fc, ns = built.tree.first_child.cpu().numpy(), built.tree.next_sibling.cpu().numpy()
+    order = re.order.cpu().numpy()
+    for s in range(n_seq):
+        a, b = int(batch.node_offset[s]), int(batch.node_offset[s + 1])
+        np.testing.assert_array_equal(order[a:b], oracle.dfs_order(par[a:b], fc[a:b], ns[a:b]))
