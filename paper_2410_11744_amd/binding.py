@@ -54,6 +54,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     p = path or _build.LIB
     if not os.path.exists(p):
         _build.build(force=True)
+    # torch brings its own copy of the HIP runtime; it has to be the one in the process before
+    # this library is mapped, or the two would run on separate runtimes and every pointer torch
+    # hands over would be foreign to the kernels' launches
+    import torch  # noqa: F401
     lib = ctypes.CDLL(p)
     V, I32, U64, SZ, F = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint64, ctypes.c_size_t, ctypes.c_float
     PB, PT = ctypes.POINTER(_Batch), ctypes.POINTER(_Tree)
