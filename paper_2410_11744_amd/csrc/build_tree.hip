@@ -69,6 +69,11 @@ struct BuildShared {
     int depth[DYSPEC_MAX_NODES];
     uint2 pk[DYSPEC_MAX_NODES];
     CdfScratch cdf;
+    double wave_tot[kWaves];            // per draw (cached form): the waves' sums of the picked segment
+    double w4[4];                       // weights of the four tokens of the thread that owns the crossing
+    double excl;                        // weight in front of those four
+    int first_hit[kWaves];
+    int last_live[kWaves];
     double best_v[kWaves];
     int best_i[kWaves];
     float fred[kWaves];
@@ -157,26 +162,72 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
             W = pk.W;
             if (!(W > 0.0)) break;                     // nothing left to sample under p
             const double mine = S[pk.js * kBlock + tid];
-            // weights of this thread's four tokens of segment js (they share one word of the
-            // drawn-already bits); only the thread that owns the crossing asks
-            uint32_t* const gone_word = ws_gone(ws, base + p) + tok_index(pk.js, 0) / 32;
-            const int gone_shift = tok_index(pk.js, 0) % 32;
-            auto weight_at = [&](int e, uint32_t gone) -> double {
-                const int idx = tok_index(pk.js, e);
-                if (idx >= V || ((gone >> (gone_shift + e)) & 1u)) return 0.0;
-                return token_weight(row[idx], inv_temp, m);
-            };
-            y = finish_inverse_cdf(pk, mine, &sh.cdf, &wy, [&](int, int e) { return weight_at(e, *gone_word); });
-            // the sum that held y and the total of its segment lose y's weight
-            double t1[1] = { mine };
-            if (((y % kSeg) >> 2) == tid) {
-                const uint32_t gone = *gone_word | (1u << (gone_shift + (y & 3)));
-                *gone_word = gone;
-                t1[0] = (weight_at(0, gone) + weight_at(1, gone)) + (weight_at(2, gone) + weight_at(3, gone));
-                S[pk.js * kBlock + tid] = t1[0];
+            // ---- inclusive scan of the 512 sums of segment js in thread order (the arithmetic of
+            //      block_scan_inclusive), then a ballot for the first thread past u * W
+            double inc = mine;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const double up = __shfl_up(inc, o, kWave);
+                if (lane >= o) inc += up;
             }
-            block_sum<double, 1>(t1, sh.cdf.red);
-            if (tid == 0) T[pk.js] = t1[0];
+            if (lane == kWave - 1) sh.wave_tot[wave] = inc;
+            __syncthreads();
+            double before = 0.0;
+            for (int k = 0; k < wave; ++k) before += sh.wave_tot[k];
+            const double incl = before + inc;
+            const unsigned long long hit = __ballot(mine > 0.0 && pk.cum_js + incl > pk.target);
+            const unsigned long long live = __ballot(mine > 0.0);
+            if (lane == 0) {
+                sh.first_hit[wave] = hit ? wave * kWave + __builtin_ctzll(hit) : -1;
+                sh.last_live[wave] = live ? wave * kWave + 63 - __builtin_clzll(live) : -1;
+            }
+            __syncthreads();
+            int owner = -1, last = -1;
+#pragma unroll
+            for (int k = 0; k < kWaves; ++k) {
+                if (owner < 0 && sh.first_hit[k] >= 0) owner = sh.first_hit[k];
+                if (sh.last_live[k] >= 0) last = sh.last_live[k];
+            }
+            if (owner < 0) owner = last;                  // rounding at the very top: the last thread with weight left
+            if (owner < 0) break;                         // nothing left to sample under p
+            // ---- the owner's four tokens share one word of the drawn-already bits; four threads
+            //      compute one weight each
+            const int tok0 = pk.js * kSeg + 4 * owner;
+            uint32_t* const gone_word = ws_gone(ws, base + p) + tok0 / 32;
+            const int gone_shift = tok0 % 32;
+            uint32_t gone = 0u;
+            if (tid == owner) sh.excl = pk.cum_js + (incl - mine);
+            if (tid < 4) {
+                gone = *gone_word;
+                const int idx = tok0 + tid;
+                const bool there = idx < V && !((gone >> (gone_shift + tid)) & 1u);
+                sh.w4[tid] = there ? token_weight(row[idx], inv_temp, m) : 0.0;
+            }
+            __syncthreads();
+            // ---- every thread finishes the draw: the token among the four, what is left of their sum
+            const double w4v[4] = { sh.w4[0], sh.w4[1], sh.w4[2], sh.w4[3] };
+            double run = sh.excl, wlast = 0.0;
+            int ylast = -1;
+            y = -1; wy = 0.0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                run += w4v[e];
+                if (w4v[e] > 0.0) { ylast = tok0 + e; wlast = w4v[e]; }
+                if (y < 0 && w4v[e] > 0.0 && run > pk.target) { y = tok0 + e; wy = w4v[e]; }
+            }
+            if (y < 0) { y = ylast; wy = wlast; }
+            if (y >= 0) {
+                const int ey = y - tok0;
+                // the sum that held y and the total of its segment lose y's weight
+                double t1[1] = { mine };
+                if (tid == owner) {
+                    t1[0] = ((ey == 0 ? 0.0 : w4v[0]) + (ey == 1 ? 0.0 : w4v[1])) + ((ey == 2 ? 0.0 : w4v[2]) + (ey == 3 ? 0.0 : w4v[3]));
+                    S[pk.js * kBlock + tid] = t1[0];
+                }
+                if (tid == 0) *gone_word = gone | (1u << (gone_shift + ey));
+                block_sum<double, 1>(t1, sh.cdf.red);
+                if (tid == 0) T[pk.js] = t1[0];
+            }
         } else {
             // bit k of `gone` marks this thread's k-th token as already drawn at this position
             uint64_t gone = 0ull;
