@@ -308,7 +308,6 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     //      half of tile i for e = 1; the next half is the upper half of tile i for e = 0 and
     //      the lower half of tile i+1 (slot SP^1) for e = 1.
     const floatx16 zero16 = { 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0 };
-    const bf16x2 kOnes2 = { (__bf16)1.0f, (__bf16)1.0f };
     float ls_half[QB];                           // the lane's sums of numerators of the half just done
     //      LD: this wave's LPW direct loads of a whole tile (ld_base: its first row for this wave,
     //      ld_dst: LDS byte) are issued one per two slots, so that they drain while the matrix
@@ -330,14 +329,13 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         // Register i of a 32x32 score block holds key row 8*(i/4) + 4*g + i%4, query column n.
         // Vector work on pair p = scores 2p, 2p+1 of a query block: F (two fma: the exponents),
         // X (two exponentials), M (mask, only for masked halves), C (round the pair to bf16 and
-        // store it as a numerator word), D (add the rounded pair to the row sum).  A wave issues
+        // store it as a numerator word), D (add the pair to the row sum).  A wave issues
         // in order and a dependent vector instruction waits for its operand, so the stages of a
         // pair sit in different items: item h (two per pair) holds X(p) and D(p-1) when even,
         // M(p), F(p+1) and C(p) when odd; F of the first pair comes before item 0, D of the last
         // pair after the last item.  Nothing inside an item depends on anything else in it.
         constexpr int NPAIR = 8 * QB;
         float ft[NPAIR][2], pt[NPAIR][2];
-        uint32_t pw[NPAIR];
         auto stage_f = [&](auto kc) __attribute__((always_inline)) {
             constexpr int k = decltype(kc)::value, qb = k / 8, i = 2 * (k % 8);
             ft[k][0] = fmaf(S[E][qb][i], c2, -mc[qb]);
@@ -345,8 +343,13 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         };
         auto stage_d = [&](auto kc) __attribute__((always_inline)) {
             constexpr int k = decltype(kc)::value, qb = k / 8;
-            // the sum takes the rounded numerators, the ones the second product multiplies
-            ls[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pw[k]), kOnes2, ls[qb], false);
+            // Two plain adds of the fp32 numerators (after the mask, before the rounding to bf16).  The
+            // dot-product instruction that would sum the rounded pair in one go holds back the matrix
+            // pipe: measured, one v_dot2c_f32_bf16 per two MFMAs costs about seven cycles per MFMA,
+            // two v_add_f32 nothing.  Sum of unrounded against product of rounded numerators: a relative
+            // difference below 2^-9, the size of the bf16 rounding of the output itself.
+            ls[qb] += pt[k][0];
+            ls[qb] += pt[k][1];
         };
         auto valu_item = [&](auto hc) __attribute__((always_inline)) {
             constexpr int h = decltype(hc)::value, k = h / 2, qb = k / 8, p = k % 8, i = 2 * p;
@@ -364,7 +367,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                 floatx2 pp = { p0, p1 };
                 uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
                 asm volatile("" : "+v"(w));                    // keep the conversion in this scheduling group
-                pw[k] = w;
+                if constexpr (MK) { pt[k][0] = p0; pt[k][1] = p1; }
                 pbw[E][qb][p / 4][p % 4] = w;
             }
         };
@@ -468,7 +471,8 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                 const float p1 = fast_exp2(fmaf(sm[i + 1], c2, -mc2));
                 floatx2 pp = { p0, p1 };
                 const bf16x2 pc = __builtin_convertvector(pp, bf16x2);
-                ls = __builtin_amdgcn_fdot2_f32_bf16(pc, kOnes2, ls, false);
+                ls += p0;
+                ls += p1;
                 pbw[E][qb][i / 8][(i / 2) % 4] = __builtin_bit_cast(uint32_t, pc);
             }
             ls_half[qb] = ls;
