@@ -17,8 +17,9 @@
 // numerators, and O^T += V^T P^T.
 //
 // Software pipeline.  The vector work of the softmax and the matrix work run in different
-// pipes of a SIMD, but only instructions that are adjacent in one wave's stream overlap
-// reliably, so the loop is skewed by half tiles: a half step runs the exponentials of half
+// pipes of a SIMD, but they overlap reliably only when both waves of the SIMD interleave them
+// finely (a few vector instructions per MFMA: a wave's vector work runs behind the other
+// wave's MFMA), so the loop is skewed by half tiles: a half step runs the exponentials of half
 // h while the matrix pipe does the second product of half h-1 and the first product of half
 // h+1; one scheduling group holds one MFMA, the LDS reads of an MFMA a few slots ahead, and
 // a few vector instructions.
