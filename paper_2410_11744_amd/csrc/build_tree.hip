@@ -10,11 +10,13 @@
 // token) equal to an fp64 evaluation of the algorithm except at relative margins near 1e-13.
 //
 // With a workspace the O(vocabulary) part leaves the serial loop: draft_row_sums_kernel (one
-// workgroup per row, all rows at once) stores every row's segment sums, and the builder keeps
-// them current -- a draw changes the one sum that held the drawn token and the total of its
-// segment -- so a draw reads 16 totals and one 4 KB line of sums instead of a whole row of
-// logits.  Without a workspace the builder recomputes the sums of the parent's row for every
-// draw; both ways do the same arithmetic and build the same tree.
+// workgroup per row, all rows at once) stores every row's segment sums, and the builder
+// (build_tree_cached_kernel) keeps them current -- a draw changes the one sum that held the
+// drawn token and the total of its segment.  The rows' segment totals live in LDS, so a draw
+// makes one trip to global memory (each thread fetches its sum, its four logits and its
+// drawn-already bits of the picked segment together) and passes three barriers.  Without a
+// workspace the builder (build_tree_kernel) recomputes the sums of the parent's row for every
+// draw; both ways take the same decisions and build the same tree.
 #include "draft_row.h"
 
 namespace dyspec {
@@ -72,6 +74,7 @@ struct BuildShared {
     double wave_tot[kWaves];            // per draw (cached form): the waves' sums of the picked segment
     double w4[4];                       // weights of the four tokens of the thread that owns the crossing
     double excl;                        // weight in front of those four
+    int owner;                          // the thread that holds the crossing
     int first_hit[kWaves];
     int last_live[kWaves];
     double best_v[kWaves];
@@ -81,21 +84,11 @@ struct BuildShared {
     int pick;
 };
 
-// CACHED: the rows' segment sums come from (and are kept current in) the workspace ws.
-template <bool VEC, bool CACHED>
-__global__ __launch_bounds__(kBlock) void build_tree_kernel(
-    const float* __restrict__ draft_logits, int V, SeqArgs sa, uint64_t seed,
-    dyspec_tree tree, float* __restrict__ est_value, uint64_t* __restrict__ anc_mask,
-    int mask_words, int* __restrict__ n_built, double* ws)
+// Initial state of a sequence's tree: every row unbuilt, the root's slot open.  Ends with a barrier.
+__device__ __forceinline__ void init_tree_state(BuildShared& sh, int seq, int base, int N, const dyspec_tree& tree,
+                                                float* __restrict__ est_value, uint64_t* __restrict__ anc_mask, int mask_words)
 {
-    __shared__ BuildShared sh;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int seq = blockIdx.x;
-    const int base = sa.node_off[seq];
-    const int N = sa.node_off[seq + 1] - base;
-    const double inv_temp = 1.0 / (double)sa.temp_d[seq];
-
-    // ---- initial state: every row unbuilt, root slot open
+    const int tid = threadIdx.x;
     for (int i = tid; i < N; i += kBlock) {
         sh.n_children[i] = 0; sh.last_child[i] = -1; sh.token[i] = -1;
         sh.first_child[i] = -1; sh.next_sibling[i] = -1; sh.depth[i] = 0;
@@ -112,6 +105,37 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
         sh.pk[0] = root_key((uint32_t)seq);
     }
     __syncthreads();
+}
+
+// Thread 0's bookkeeping for new node i = child number `rank` of p with token y, taken from a slot
+// of value v (Algorithm 1: the node's estimated acceptance rate).
+__device__ __forceinline__ void append_node(BuildShared& sh, const dyspec_tree& tree, float* __restrict__ est_value,
+                                            uint64_t seed, int base, int p, int i, int rank, int y, double v)
+{
+    sh.token[i] = y; sh.depth[i] = sh.depth[p] + 1;
+    if (sh.last_child[p] < 0) { sh.first_child[p] = i; tree.first_child[base + p] = i; }
+    else { sh.next_sibling[sh.last_child[p]] = i; tree.next_sibling[base + sh.last_child[p]] = i; }
+    sh.last_child[p] = i; sh.n_children[p] = rank + 1;
+    sh.pk[i] = child_key(seed, sh.pk[p], (uint32_t)rank);
+    tree.parent[base + i] = p; tree.token[base + i] = y; tree.sib_rank[base + i] = rank;
+    tree.depth[base + i] = sh.depth[i];
+    est_value[base + i] = (float)v;
+}
+
+// The form without a workspace: the sums of the parent's row are recomputed for every draw.
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void build_tree_kernel(
+    const float* __restrict__ draft_logits, int V, SeqArgs sa, uint64_t seed,
+    dyspec_tree tree, float* __restrict__ est_value, uint64_t* __restrict__ anc_mask,
+    int mask_words, int* __restrict__ n_built)
+{
+    __shared__ BuildShared sh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int seq = blockIdx.x;
+    const int base = sa.node_off[seq];
+    const int N = sa.node_off[seq + 1] - base;
+    const double inv_temp = 1.0 / (double)sa.temp_d[seq];
+    init_tree_state(sh, seq, base, N, tree, est_value, anc_mask, mask_words);
 
     int n = 1;
     while (n < N) {
@@ -147,102 +171,19 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
         //      the earlier children's tokens removed)
         const double u = (double)u01(seed, sh.pk[p], (uint32_t)rank, KIND_BUILD);
         const float* __restrict__ row = draft_logits + (size_t)(base + p) * V;
-        double W, wy;
-        int y;
-        if constexpr (CACHED) {
-            // (ws is written by this kernel and not declared restrict or const, so these are
-            //  ordinary vector loads and stores, ordered by the barriers of the loop)
-            double* const S = ws_sums(ws, base + p);
-            double* const T = ws_totals(ws, base + p);
-            const double m = *ws_rowmax(ws, base + p);
-            double tot[kMaxSeg];
-#pragma unroll
-            for (int j = 0; j < kMaxSeg; ++j) tot[j] = T[j];
-            const SegPick pk = pick_segment(tot, u);
-            W = pk.W;
-            if (!(W > 0.0)) break;                     // nothing left to sample under p
-            const double mine = S[pk.js * kBlock + tid];
-            // ---- inclusive scan of the 512 sums of segment js in thread order (the arithmetic of
-            //      block_scan_inclusive), then a ballot for the first thread past u * W
-            double inc = mine;
-#pragma unroll
-            for (int o = 1; o < kWave; o <<= 1) {
-                const double up = __shfl_up(inc, o, kWave);
-                if (lane >= o) inc += up;
-            }
-            if (lane == kWave - 1) sh.wave_tot[wave] = inc;
-            __syncthreads();
-            double before = 0.0;
-            for (int k = 0; k < wave; ++k) before += sh.wave_tot[k];
-            const double incl = before + inc;
-            const unsigned long long hit = __ballot(mine > 0.0 && pk.cum_js + incl > pk.target);
-            const unsigned long long live = __ballot(mine > 0.0);
-            if (lane == 0) {
-                sh.first_hit[wave] = hit ? wave * kWave + __builtin_ctzll(hit) : -1;
-                sh.last_live[wave] = live ? wave * kWave + 63 - __builtin_clzll(live) : -1;
-            }
-            __syncthreads();
-            int owner = -1, last = -1;
-#pragma unroll
-            for (int k = 0; k < kWaves; ++k) {
-                if (owner < 0 && sh.first_hit[k] >= 0) owner = sh.first_hit[k];
-                if (sh.last_live[k] >= 0) last = sh.last_live[k];
-            }
-            if (owner < 0) owner = last;                  // rounding at the very top: the last thread with weight left
-            if (owner < 0) break;                         // nothing left to sample under p
-            // ---- the owner's four tokens share one word of the drawn-already bits; four threads
-            //      compute one weight each
-            const int tok0 = pk.js * kSeg + 4 * owner;
-            uint32_t* const gone_word = ws_gone(ws, base + p) + tok0 / 32;
-            const int gone_shift = tok0 % 32;
-            uint32_t gone = 0u;
-            if (tid == owner) sh.excl = pk.cum_js + (incl - mine);
-            if (tid < 4) {
-                gone = *gone_word;
-                const int idx = tok0 + tid;
-                const bool there = idx < V && !((gone >> (gone_shift + tid)) & 1u);
-                sh.w4[tid] = there ? token_weight(row[idx], inv_temp, m) : 0.0;
-            }
-            __syncthreads();
-            // ---- every thread finishes the draw: the token among the four, what is left of their sum
-            const double w4v[4] = { sh.w4[0], sh.w4[1], sh.w4[2], sh.w4[3] };
-            double run = sh.excl, wlast = 0.0;
-            int ylast = -1;
-            y = -1; wy = 0.0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                run += w4v[e];
-                if (w4v[e] > 0.0) { ylast = tok0 + e; wlast = w4v[e]; }
-                if (y < 0 && w4v[e] > 0.0 && run > pk.target) { y = tok0 + e; wy = w4v[e]; }
-            }
-            if (y < 0) { y = ylast; wy = wlast; }
-            if (y >= 0) {
-                const int ey = y - tok0;
-                // the sum that held y and the total of its segment lose y's weight
-                double t1[1] = { mine };
-                if (tid == owner) {
-                    t1[0] = ((ey == 0 ? 0.0 : w4v[0]) + (ey == 1 ? 0.0 : w4v[1])) + ((ey == 2 ? 0.0 : w4v[2]) + (ey == 3 ? 0.0 : w4v[3]));
-                    S[pk.js * kBlock + tid] = t1[0];
-                }
-                if (tid == 0) *gone_word = gone | (1u << (gone_shift + ey));
-                block_sum<double, 1>(t1, sh.cdf.red);
-                if (tid == 0) T[pk.js] = t1[0];
-            }
-        } else {
-            // bit k of `gone` marks this thread's k-th token as already drawn at this position
-            uint64_t gone = 0ull;
-            for (int c = sh.first_child[p]; c >= 0; c = sh.next_sibling[c]) {
-                const int yc = sh.token[c];
-                if (((yc % kSeg) >> 2) == tid) gone |= 1ull << (4 * (yc / kSeg) + (yc & 3));
-            }
-            double m, seg[kMaxSeg];
-            row_segment_sums<VEC>(row, V, inv_temp, gone, sh.fred, &m, seg);
-            y = block_inverse_cdf_seg(seg, u, &sh.cdf, &W, &wy, [&](int j, int e) -> double {
-                const int idx = tok_index(j, e);
-                const bool live = idx < V && !((gone >> (4 * j + e)) & 1ull);
-                return live ? token_weight(row[idx], inv_temp, m) : 0.0;
-            });
+        // bit k of `gone` marks this thread's k-th token as already drawn at this position
+        uint64_t gone = 0ull;
+        for (int c = sh.first_child[p]; c >= 0; c = sh.next_sibling[c]) {
+            const int yc = sh.token[c];
+            if (((yc % kSeg) >> 2) == tid) gone |= 1ull << (4 * (yc / kSeg) + (yc & 3));
         }
+        double m, seg[kMaxSeg], W, wy;
+        row_segment_sums<VEC>(row, V, inv_temp, gone, sh.fred, &m, seg);
+        const int y = block_inverse_cdf_seg(seg, u, &sh.cdf, &W, &wy, [&](int j, int e) -> double {
+            const int idx = tok_index(j, e);
+            const bool live = idx < V && !((gone >> (4 * j + e)) & 1ull);
+            return live ? token_weight(row[idx], inv_temp, m) : 0.0;
+        });
         if (y < 0) break;                              // nothing left to sample under p
 
         // ---- append node n, open its two slots
@@ -250,14 +191,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
         if (tid == 0) {
             const double Ry = wy / W;
             sh.slot_value[pick] = -1.0;
-            sh.token[i] = y; sh.depth[i] = sh.depth[p] + 1;
-            if (sh.last_child[p] < 0) { sh.first_child[p] = i; tree.first_child[base + p] = i; }
-            else { sh.next_sibling[sh.last_child[p]] = i; tree.next_sibling[base + sh.last_child[p]] = i; }
-            sh.last_child[p] = i; sh.n_children[p] = rank + 1;
-            sh.pk[i] = child_key(seed, sh.pk[p], (uint32_t)rank);
-            tree.parent[base + i] = p; tree.token[base + i] = y; tree.sib_rank[base + i] = rank;
-            tree.depth[base + i] = sh.depth[i];
-            est_value[base + i] = (float)v;
+            append_node(sh, tree, est_value, seed, base, p, i, rank, y, v);
             const double v0 = v * Ry, v1 = v * (1.0 - Ry);
             int ns = sh.n_slots;
             if (v1 > 0.0) { sh.slot_value[ns] = v1; sh.slot_parent[ns] = p; ++ns; }   // next sampling at this position
@@ -274,7 +208,214 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
     if (tid == 0) n_built[seq] = n;
 }
 
+// The form with a workspace.  State of a row in LDS (rows below lds_rows; the others stay in the
+// workspace): its kMaxSeg segment totals and its maximum, kRowState doubles that follow each
+// other in the workspace as well.
+//
+// A draw, for the picked slot of parent p: every thread reads p's totals (LDS) and picks the
+// segment; fetches, in one trip to global memory, its own sum of that segment, its four logits
+// and the word with its drawn-already bits; the sums are scanned (barrier 2).  The waves' totals
+// tell every thread which wave holds the crossing; that wave finds the thread (the owner) with
+// a ballot, hands the owner's logits to its first four lanes with shuffles, and those compute
+// the four weights (barrier 3), after which every thread finishes the draw on its own.  The
+// owner stores its new sum and bits, its wave the segment's new total.  Every thread also knows
+// the two slots the draw opens and the one it closes, so the next pop (barrier 1) does not wait
+// for thread 0's bookkeeping: the three slots it is changing are taken from registers.
+constexpr int kRowState = kMaxSeg + 1;
+
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
+    const float* __restrict__ draft_logits, int V, SeqArgs sa, uint64_t seed,
+    dyspec_tree tree, float* __restrict__ est_value, uint64_t* __restrict__ anc_mask,
+    int mask_words, int* __restrict__ n_built, double* ws, int lds_rows)
+{
+    __shared__ BuildShared sh;
+    extern __shared__ double row_state[];              // [min(N, lds_rows)][kRowState]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int seq = blockIdx.x;
+    const int base = sa.node_off[seq];
+    const int N = sa.node_off[seq + 1] - base;
+    const double inv_temp = 1.0 / (double)sa.temp_d[seq];
+    const int n_lds = min(N, lds_rows);
+    for (int x = tid; x < n_lds * kRowState; x += kBlock)
+        row_state[x] = ws_totals(ws, base + x / kRowState)[x % kRowState];
+    init_tree_state(sh, seq, base, N, tree, est_value, anc_mask, mask_words);
+
+    int n = 1, n_slots = 1;
+    // what the previous draw did to the slots (thread 0 may still be writing it to LDS)
+    int closed = -1, open_a = -1, open_b = -1;
+    double open_a_v = 0.0, open_b_v = 0.0;
+    while (n < N) {
+        // ---- pop: open slot of largest value, earliest-opened on ties
+        double bv = -1.0; int bi = 0x7fffffff;
+        for (int s = tid; s < n_slots; s += kBlock) {
+            double v = sh.slot_value[s];
+            if (s == closed) v = -1.0;
+            else if (s == open_a) v = open_a_v;
+            else if (s == open_b) v = open_b_v;
+            if (v > bv) { bv = v; bi = s; }           // s ascends: ties keep the earlier slot
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double ov = __shfl_xor(bv, o, kWave);
+            const int oi = __shfl_xor(bi, o, kWave);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        if (lane == 0) { sh.best_v[wave] = bv; sh.best_i[wave] = bi; }
+        __syncthreads();                               // barrier 1
+        double v = sh.best_v[0]; int pick = sh.best_i[0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) {
+            const double wv = sh.best_v[w]; const int wi = sh.best_i[w];
+            if (wv > v || (wv == v && wi < pick)) { v = wv; pick = wi; }
+        }
+        if (!(v > 0.0)) break;                         // frontier is empty
+        const int p = sh.slot_parent[pick];
+        const int rank = sh.n_children[p];
+        // the parent's mask word, needed when the node is appended: on its way during the draw
+        uint64_t up = 0ull;
+        if (tid < mask_words) up = anc_mask[(size_t)(base + p) * mask_words + tid];
+
+        // ---- draw the token from the residual draft distribution of p
+        const double u = (double)u01(seed, sh.pk[p], (uint32_t)rank, KIND_BUILD);
+        const float* __restrict__ row = draft_logits + (size_t)(base + p) * V;
+        // (ws is written by this kernel and not declared restrict or const, so these are
+        //  ordinary vector loads and stores; a sum or a bit word is only ever re-read by the
+        //  wave that wrote it, totals kept in the workspace are ordered by the barriers)
+        double* const S = ws_sums(ws, base + p);
+        double* const T = ws_totals(ws, base + p);
+        const bool in_lds = p < n_lds;
+        double tot[kMaxSeg], m;
+        if (in_lds) {
+#pragma unroll
+            for (int j = 0; j < kMaxSeg; ++j) tot[j] = row_state[p * kRowState + j];
+            m = row_state[p * kRowState + kMaxSeg];
+        } else {
+#pragma unroll
+            for (int j = 0; j < kMaxSeg; ++j) tot[j] = T[j];
+            m = T[kMaxSeg];
+        }
+        const SegPick pk = pick_segment(tot, u);
+        const double W = pk.W;
+        if (!(W > 0.0)) break;                         // nothing left to sample under p
+        const int tok_mine = pk.js * kSeg + 4 * tid;   // this thread's four tokens of the segment
+        const double mine = S[pk.js * kBlock + tid];
+        uint32_t* const gone_word = ws_gone(ws, base + p) + tok_mine / 32;
+        const uint32_t gone = *gone_word;
+        float lg[4];
+        if constexpr (VEC) {
+            const float4 x = tok_mine < V ? *reinterpret_cast<const float4*>(row + tok_mine) : make_float4(0.f, 0.f, 0.f, 0.f);
+            lg[0] = x.x; lg[1] = x.y; lg[2] = x.z; lg[3] = x.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) lg[e] = tok_mine + e < V ? row[tok_mine + e] : 0.f;
+        }
+        // ---- inclusive scan of the 512 sums in thread order
+        double inc = mine;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const double below = __shfl_up(inc, o, kWave);
+            if (lane >= o) inc += below;
+        }
+        if (lane == kWave - 1) sh.wave_tot[wave] = inc;
+        __syncthreads();                               // barrier 2
+        double wt[kWaves], before = 0.0, cum = 0.0;
+        int kw = -1;                                   // first wave whose last thread is past u * W
+#pragma unroll
+        for (int k = 0; k < kWaves; ++k) {
+            wt[k] = sh.wave_tot[k];
+            if (k == wave) before = cum;
+            cum += wt[k];
+            if (kw < 0 && pk.cum_js + cum > pk.target) kw = k;
+        }
+        const double incl = before + inc;
+        const unsigned long long live = __ballot(mine > 0.0);
+        int fixed_owner = -1;
+        if (kw < 0) {
+            // rounding at the very top: the last thread with weight left (the same in every thread)
+            if (lane == 0) sh.last_live[wave] = live ? wave * kWave + 63 - __builtin_clzll(live) : -1;
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < kWaves; ++k) if (sh.last_live[k] >= 0) fixed_owner = sh.last_live[k];
+            if (fixed_owner < 0) break;                // nothing left to sample under p
+            kw = fixed_owner / kWave;
+        }
+        if (wave == kw) {
+            // the wave's total is positive (it moved the running sum past the target), so a thread
+            // with weight exists; after the first one past the target, else (the scan's rounding
+            // can put the crossing on a thread without weight) the last one with weight
+            const unsigned long long hit = __ballot(mine > 0.0 && pk.cum_js + incl > pk.target);
+            const int ol = fixed_owner >= 0 ? fixed_owner % kWave : hit ? __builtin_ctzll(hit) : 63 - __builtin_clzll(live);
+            const float l0 = __shfl(lg[0], ol, kWave), l1 = __shfl(lg[1], ol, kWave);
+            const float l2 = __shfl(lg[2], ol, kWave), l3 = __shfl(lg[3], ol, kWave);
+            const uint32_t g = __shfl(gone, ol, kWave);
+            const int tok0 = pk.js * kSeg + 4 * (kw * kWave + ol);
+            if (lane < 4) {
+                const float l = lane == 0 ? l0 : lane == 1 ? l1 : lane == 2 ? l2 : l3;
+                const bool there = tok0 + lane < V && !((g >> (tok0 % 32 + lane)) & 1u);
+                sh.w4[lane] = there ? token_weight(l, inv_temp, m) : 0.0;
+            }
+            if (lane == ol) { sh.excl = pk.cum_js + (incl - mine); sh.owner = kw * kWave + ol; }
+        }
+        __syncthreads();                               // barrier 3
+        // ---- every thread finishes the draw: the token among the four, what is left of their sum
+        const int owner = sh.owner;
+        const int tok0 = pk.js * kSeg + 4 * owner;
+        const double w4v[4] = { sh.w4[0], sh.w4[1], sh.w4[2], sh.w4[3] };
+        double run = sh.excl, wy = 0.0, wlast = 0.0;
+        int y = -1, ylast = -1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            run += w4v[e];
+            if (w4v[e] > 0.0) { ylast = tok0 + e; wlast = w4v[e]; }
+            if (y < 0 && w4v[e] > 0.0 && run > pk.target) { y = tok0 + e; wy = w4v[e]; }
+        }
+        if (y < 0) { y = ylast; wy = wlast; }
+        if (y < 0) break;                              // nothing left to sample under p
+        const int ey = y - tok0;
+        // the sum that held y and the total of its segment lose y's weight
+        const double left = ((ey == 0 ? 0.0 : w4v[0]) + (ey == 1 ? 0.0 : w4v[1])) + ((ey == 2 ? 0.0 : w4v[2]) + (ey == 3 ? 0.0 : w4v[3]));
+        if (wave == kw) {
+            if (tid == owner) {
+                S[pk.js * kBlock + tid] = left;
+                *gone_word = gone | (1u << (tok0 % 32 + ey));
+            }
+            double wsum = tid == owner ? left : mine;  // the wave's sums again, the owner's replaced
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) wsum += __shfl_xor(wsum, o, kWave);
+            if (lane == 0) {
+                double t = 0.0;
+#pragma unroll
+                for (int k = 0; k < kWaves; ++k) t += k == kw ? wsum : wt[k];
+                if (in_lds) row_state[p * kRowState + pk.js] = t; else T[pk.js] = t;
+            }
+        }
+
+        // ---- append node n, open its two slots (every thread knows them; thread 0 writes them down)
+        const int i = n;
+        const double Ry = wy / W;
+        const double v0 = v * Ry, v1 = v * (1.0 - Ry);
+        closed = pick; open_a = -1; open_b = -1;
+        if (v1 > 0.0) { open_a = n_slots++; open_a_v = v1; }      // next sampling at this position
+        if (v0 > 0.0) { open_b = n_slots++; open_b_v = v0; }      // first child of the new node
+        if (tid == 0) {
+            sh.slot_value[pick] = -1.0;
+            append_node(sh, tree, est_value, seed, base, p, i, rank, y, v);
+            if (open_a >= 0) { sh.slot_value[open_a] = v1; sh.slot_parent[open_a] = p; }
+            if (open_b >= 0) { sh.slot_value[open_b] = v0; sh.slot_parent[open_b] = i; }
+        }
+        if (tid < mask_words)
+            anc_mask[(size_t)(base + i) * mask_words + tid] = up | ((tid == i / 64) ? (1ull << (i % 64)) : 0ull);
+        ++n;
+    }
+    if (tid == 0) n_built[seq] = n;
+}
+
 size_t build_tree_workspace_bytes(int total_rows) { return (size_t)total_rows * kRowSumDoubles * sizeof(double); }
+
+// LDS a workgroup may use on gfx950, less a margin; what BuildShared leaves of it holds row states.
+constexpr size_t kLdsPerWorkgroup = 160 * 1024 - 1024;
+constexpr int kLdsRowsMax = (int)((kLdsPerWorkgroup - sizeof(BuildShared)) / (kRowState * sizeof(double)));
 
 hipError_t launch_build_tree(const float* draft_logits, int V, const SeqArgs& sa, uint64_t seed,
                              const dyspec_tree& tree, float* est_value, uint64_t* anc_mask,
@@ -284,21 +425,29 @@ hipError_t launch_build_tree(const float* draft_logits, int V, const SeqArgs& sa
     double* ws = static_cast<double*>(workspace);
     const bool cached = ws != nullptr && workspace_bytes >= build_tree_workspace_bytes(rows);
     if (cached) {
+        int widest = 0;
+        for (int s = 0; s < sa.n_seq; ++s) widest = max(widest, sa.node_off[s + 1] - sa.node_off[s]);
+        const int lds_rows = min(widest, kLdsRowsMax);
+        const size_t dyn_bytes = (size_t)lds_rows * kRowState * sizeof(double);
+        const void* fn = V % 4 == 0 ? reinterpret_cast<const void*>(&build_tree_cached_kernel<true>)
+                                    : reinterpret_cast<const void*>(&build_tree_cached_kernel<false>);
+        hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_bytes);
+        if (ea != hipSuccess) return ea;
         if (V % 4 == 0) {
             draft_row_sums_kernel<true><<<rows, kBlock, 0, stream>>>(draft_logits, V, sa, ws);
-            build_tree_kernel<true, true><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
-                                                                           anc_mask, mask_words, n_built, ws);
+            build_tree_cached_kernel<true><<<sa.n_seq, kBlock, dyn_bytes, stream>>>(draft_logits, V, sa, seed, tree, est_value,
+                                                                                     anc_mask, mask_words, n_built, ws, lds_rows);
         } else {
             draft_row_sums_kernel<false><<<rows, kBlock, 0, stream>>>(draft_logits, V, sa, ws);
-            build_tree_kernel<false, true><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
-                                                                            anc_mask, mask_words, n_built, ws);
+            build_tree_cached_kernel<false><<<sa.n_seq, kBlock, dyn_bytes, stream>>>(draft_logits, V, sa, seed, tree, est_value,
+                                                                                      anc_mask, mask_words, n_built, ws, lds_rows);
         }
     } else if (V % 4 == 0) {
-        build_tree_kernel<true, false><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
-                                                                        anc_mask, mask_words, n_built, nullptr);
+        build_tree_kernel<true><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
+                                                                 anc_mask, mask_words, n_built);
     } else {
-        build_tree_kernel<false, false><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
-                                                                         anc_mask, mask_words, n_built, nullptr);
+        build_tree_kernel<false><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
+                                                                  anc_mask, mask_words, n_built);
     }
     return hipGetLastError();
 }
