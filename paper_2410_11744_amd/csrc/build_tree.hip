@@ -60,9 +60,71 @@ __global__ __launch_bounds__(kBlock) void draft_row_sums_kernel(const float* __r
     for (int w = threadIdx.x; w < kGoneWords; w += kBlock) ws_gone(ws, row)[w] = 0u;
 }
 
+// Cross-lane moves of the vector ALU (DPP) for the serial builder's reductions and scan; a
+// shuffle would go through the LDS crossbar and wait for it at every step.
+constexpr int kDppXor1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;   // lane i of a group of 8 <-> lane 7-i
+constexpr int kDppMirror = 0x140;       // lane i of a row of 16 <-> lane 15-i
+constexpr int kDppBcast15 = 0x142;      // lane 15 of a row to the next row
+constexpr int kDppBcast31 = 0x143;      // lane 31 to rows 2 and 3
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ int dpp_or_zero(int x)   // the picked lane's x; 0 where there is none or the row is masked off
+{
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ double dpp_or_zero(double x)
+{
+    return __hiloint2double(dpp_or_zero<CTRL, ROW_MASK>(__double2hiint(x)), dpp_or_zero<CTRL, ROW_MASK>(__double2loint(x)));
+}
+// Largest value of the wave and, among equals, the smallest index; the same in every lane.
+__device__ __forceinline__ void wave_argmax(double& bv, int& bi)
+{
+    auto take = [&](double ov, int oi) { if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; } };
+    // values are >= -1 and a picked lane always exists for these four patterns
+    take(dpp_or_zero<kDppXor1>(bv), dpp_or_zero<kDppXor1>(bi));
+    take(dpp_or_zero<kDppXor2>(bv), dpp_or_zero<kDppXor2>(bi));
+    take(dpp_or_zero<kDppHalfMirror>(bv), dpp_or_zero<kDppHalfMirror>(bi));
+    take(dpp_or_zero<kDppMirror>(bv), dpp_or_zero<kDppMirror>(bi));
+    // every row of 16 lanes agrees now: combine the four rows
+    const double v0 = bv; const int i0 = bi;
+    bv = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v0), 0), __builtin_amdgcn_readlane(__double2loint(v0), 0));
+    bi = __builtin_amdgcn_readlane(i0, 0);
+#pragma unroll
+    for (int r = 1; r < 4; ++r)
+        take(__hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v0), 16 * r), __builtin_amdgcn_readlane(__double2loint(v0), 16 * r)),
+             __builtin_amdgcn_readlane(i0, 16 * r));
+}
+// Sum over the wave, the same in every lane.
+__device__ __forceinline__ double wave_sum_dpp(double x)
+{
+    x += dpp_or_zero<kDppXor1>(x);
+    x += dpp_or_zero<kDppXor2>(x);
+    x += dpp_or_zero<kDppHalfMirror>(x);
+    x += dpp_or_zero<kDppMirror>(x);
+    double r[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        r[k] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), 16 * k), __builtin_amdgcn_readlane(__double2loint(x), 16 * k));
+    return (r[0] + r[1]) + (r[2] + r[3]);
+}
+// Inclusive scan over the wave in lane order.
+__device__ __forceinline__ double wave_scan_dpp(double x)
+{
+    x += dpp_or_zero<0x111>(x);                  // row_shr:1, 2, 4, 8: scan inside each row of 16
+    x += dpp_or_zero<0x112>(x);
+    x += dpp_or_zero<0x114>(x);
+    x += dpp_or_zero<0x118>(x);
+    x += dpp_or_zero<kDppBcast15, 0xa>(x);       // rows 1 and 3 add the total of the row before
+    x += dpp_or_zero<kDppBcast31, 0xc>(x);       // rows 2 and 3 add the total of the first two rows
+    return x;
+}
+
 struct BuildShared {
     double slot_value[kMaxSlots];       // < 0: closed
     int slot_parent[kMaxSlots];
+    float slot_u[kMaxSlots];            // the uniform draw of the slot's sampling (cached form)
     int n_children[DYSPEC_MAX_NODES];
     int last_child[DYSPEC_MAX_NODES];
     int token[DYSPEC_MAX_NODES];
@@ -75,6 +137,8 @@ struct BuildShared {
     double w4[4];                       // weights of the four tokens of the thread that owns the crossing
     double excl;                        // weight in front of those four
     int owner;                          // the thread that holds the crossing
+    uint2 next_key;                     // path key of the node this draw makes
+    float next_u[2];                    // draws of the two slots it opens
     int first_hit[kWaves];
     int last_live[kWaves];
     double best_v[kWaves];
@@ -85,7 +149,7 @@ struct BuildShared {
 };
 
 // Initial state of a sequence's tree: every row unbuilt, the root's slot open.  Ends with a barrier.
-__device__ __forceinline__ void init_tree_state(BuildShared& sh, int seq, int base, int N, const dyspec_tree& tree,
+__device__ __forceinline__ void init_tree_state(BuildShared& sh, uint64_t seed, int seq, int base, int N, const dyspec_tree& tree,
                                                 float* __restrict__ est_value, uint64_t* __restrict__ anc_mask, int mask_words)
 {
     const int tid = threadIdx.x;
@@ -103,6 +167,7 @@ __device__ __forceinline__ void init_tree_state(BuildShared& sh, int seq, int ba
     if (tid == 0) {
         sh.slot_value[0] = 1.0; sh.slot_parent[0] = 0; sh.n_slots = 1;
         sh.pk[0] = root_key((uint32_t)seq);
+        sh.slot_u[0] = u01(seed, sh.pk[0], 0u, KIND_BUILD);
     }
     __syncthreads();
 }
@@ -110,13 +175,13 @@ __device__ __forceinline__ void init_tree_state(BuildShared& sh, int seq, int ba
 // Thread 0's bookkeeping for new node i = child number `rank` of p with token y, taken from a slot
 // of value v (Algorithm 1: the node's estimated acceptance rate).
 __device__ __forceinline__ void append_node(BuildShared& sh, const dyspec_tree& tree, float* __restrict__ est_value,
-                                            uint64_t seed, int base, int p, int i, int rank, int y, double v)
+                                            uint2 key, int base, int p, int i, int rank, int y, double v)
 {
     sh.token[i] = y; sh.depth[i] = sh.depth[p] + 1;
     if (sh.last_child[p] < 0) { sh.first_child[p] = i; tree.first_child[base + p] = i; }
     else { sh.next_sibling[sh.last_child[p]] = i; tree.next_sibling[base + sh.last_child[p]] = i; }
     sh.last_child[p] = i; sh.n_children[p] = rank + 1;
-    sh.pk[i] = child_key(seed, sh.pk[p], (uint32_t)rank);
+    sh.pk[i] = key;
     tree.parent[base + i] = p; tree.token[base + i] = y; tree.sib_rank[base + i] = rank;
     tree.depth[base + i] = sh.depth[i];
     est_value[base + i] = (float)v;
@@ -135,7 +200,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
     const int base = sa.node_off[seq];
     const int N = sa.node_off[seq + 1] - base;
     const double inv_temp = 1.0 / (double)sa.temp_d[seq];
-    init_tree_state(sh, seq, base, N, tree, est_value, anc_mask, mask_words);
+    init_tree_state(sh, seed, seq, base, N, tree, est_value, anc_mask, mask_words);
 
     int n = 1;
     while (n < N) {
@@ -191,7 +256,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
         if (tid == 0) {
             const double Ry = wy / W;
             sh.slot_value[pick] = -1.0;
-            append_node(sh, tree, est_value, seed, base, p, i, rank, y, v);
+            append_node(sh, tree, est_value, child_key(seed, sh.pk[p], (uint32_t)rank), base, p, i, rank, y, v);
             const double v0 = v * Ry, v1 = v * (1.0 - Ry);
             int ns = sh.n_slots;
             if (v1 > 0.0) { sh.slot_value[ns] = v1; sh.slot_parent[ns] = p; ++ns; }   // next sampling at this position
@@ -239,7 +304,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
     const int n_lds = min(N, lds_rows);
     for (int x = tid; x < n_lds * kRowState; x += kBlock)
         row_state[x] = ws_totals(ws, base + x / kRowState)[x % kRowState];
-    init_tree_state(sh, seq, base, N, tree, est_value, anc_mask, mask_words);
+    init_tree_state(sh, seed, seq, base, N, tree, est_value, anc_mask, mask_words);
 
     int n = 1, n_slots = 1;
     // what the previous draw did to the slots (thread 0 may still be writing it to LDS)
@@ -255,12 +320,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
             else if (s == open_b) v = open_b_v;
             if (v > bv) { bv = v; bi = s; }           // s ascends: ties keep the earlier slot
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const double ov = __shfl_xor(bv, o, kWave);
-            const int oi = __shfl_xor(bi, o, kWave);
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-        }
+        wave_argmax(bv, bi);
         if (lane == 0) { sh.best_v[wave] = bv; sh.best_i[wave] = bi; }
         __syncthreads();                               // barrier 1
         double v = sh.best_v[0]; int pick = sh.best_i[0];
@@ -277,7 +337,8 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         if (tid < mask_words) up = anc_mask[(size_t)(base + p) * mask_words + tid];
 
         // ---- draw the token from the residual draft distribution of p
-        const double u = (double)u01(seed, sh.pk[p], (uint32_t)rank, KIND_BUILD);
+        const double u = (double)sh.slot_u[pick];
+        const uint2 key_p = sh.pk[p];
         const float* __restrict__ row = draft_logits + (size_t)(base + p) * V;
         // (ws is written by this kernel and not declared restrict or const, so these are
         //  ordinary vector loads and stores; a sum or a bit word is only ever re-read by the
@@ -310,13 +371,16 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
 #pragma unroll
             for (int e = 0; e < 4; ++e) lg[e] = tok_mine + e < V ? row[tok_mine + e] : 0.f;
         }
-        // ---- inclusive scan of the 512 sums in thread order
-        double inc = mine;
-#pragma unroll
-        for (int o = 1; o < kWave; o <<= 1) {
-            const double below = __shfl_up(inc, o, kWave);
-            if (lane >= o) inc += below;
+        // ---- while the loads are on their way: the path key of the node this draw makes and the
+        //      uniform draws of the two slots it opens depend on (p, rank) only.  One wave each.
+        if (wave == 1 && lane == 0) sh.next_u[0] = u01(seed, key_p, (uint32_t)rank + 1u, KIND_BUILD);
+        if (wave == 2 && lane == 0) {
+            const uint2 key_i = child_key(seed, key_p, (uint32_t)rank);
+            sh.next_key = key_i;
+            sh.next_u[1] = u01(seed, key_i, 0u, KIND_BUILD);
         }
+        // ---- inclusive scan of the 512 sums in thread order
+        const double inc = wave_scan_dpp(mine);
         if (lane == kWave - 1) sh.wave_tot[wave] = inc;
         __syncthreads();                               // barrier 2
         double wt[kWaves], before = 0.0, cum = 0.0;
@@ -380,9 +444,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
                 S[pk.js * kBlock + tid] = left;
                 *gone_word = gone | (1u << (tok0 % 32 + ey));
             }
-            double wsum = tid == owner ? left : mine;  // the wave's sums again, the owner's replaced
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) wsum += __shfl_xor(wsum, o, kWave);
+            const double wsum = wave_sum_dpp(tid == owner ? left : mine);   // the wave's sums again, the owner's replaced
             if (lane == 0) {
                 double t = 0.0;
 #pragma unroll
@@ -400,9 +462,9 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         if (v0 > 0.0) { open_b = n_slots++; open_b_v = v0; }      // first child of the new node
         if (tid == 0) {
             sh.slot_value[pick] = -1.0;
-            append_node(sh, tree, est_value, seed, base, p, i, rank, y, v);
-            if (open_a >= 0) { sh.slot_value[open_a] = v1; sh.slot_parent[open_a] = p; }
-            if (open_b >= 0) { sh.slot_value[open_b] = v0; sh.slot_parent[open_b] = i; }
+            append_node(sh, tree, est_value, sh.next_key, base, p, i, rank, y, v);
+            if (open_a >= 0) { sh.slot_value[open_a] = v1; sh.slot_parent[open_a] = p; sh.slot_u[open_a] = sh.next_u[0]; }
+            if (open_b >= 0) { sh.slot_value[open_b] = v0; sh.slot_parent[open_b] = i; sh.slot_u[open_b] = sh.next_u[1]; }
         }
         if (tid < mask_words)
             anc_mask[(size_t)(base + i) * mask_words + tid] = up | ((tid == i / 64) ? (1ull << (i % 64)) : 0ull);
