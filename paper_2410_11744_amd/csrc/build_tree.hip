@@ -143,6 +143,8 @@ struct BuildShared {
     int last_live[kWaves];
     double best_v[kWaves];
     int best_i[kWaves];
+    int best_pr[kWaves];                // the winning slot's parent | rank << 10 and draw (cached form)
+    float best_u[kWaves];
     float fred[kWaves];
     int n_slots;
     int pick;
@@ -277,16 +279,65 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
 // workspace): its kMaxSeg segment totals and its maximum, kRowState doubles that follow each
 // other in the workspace as well.
 //
-// A draw, for the picked slot of parent p: every thread reads p's totals (LDS) and picks the
-// segment; fetches, in one trip to global memory, its own sum of that segment, its four logits
-// and the word with its drawn-already bits; the sums are scanned (barrier 2).  The waves' totals
-// tell every thread which wave holds the crossing; that wave finds the thread (the owner) with
-// a ballot, hands the owner's logits to its first four lanes with shuffles, and those compute
-// the four weights (barrier 3), after which every thread finishes the draw on its own.  The
-// owner stores its new sum and bits, its wave the segment's new total.  Every thread also knows
-// the two slots the draw opens and the one it closes, so the next pop (barrier 1) does not wait
-// for thread 0's bookkeeping: the three slots it is changing are taken from registers.
+// The open slots live in registers: slot s belongs to thread s % kBlock, which keeps its value,
+// its (parent, rank) and the uniform draw of its sampling.  The pop is a maximum over each
+// thread's few slots, over the wave (DPP) and over the waves' winners (barrier 1); every thread
+// then knows the slot, its parent p, the rank of the child to draw and the draw u.
+//
+// A draw: lanes read p's segment totals from LDS (one each) and pick the segment with a 16-lane
+// scan; every thread fetches, in one trip to global memory, its own sum of that segment, its
+// four logits and the word with its drawn-already bits; the sums are scanned (barrier 2).  The
+// waves' totals tell every thread which wave holds the crossing; that wave finds the thread
+// (the owner) with a ballot, hands the owner's logits to its first four lanes, and those
+// compute the four weights (barrier 3), after which every thread finishes the draw on its own:
+// token, weight, the values of the two slots the draw opens.  The owner stores its new sum and
+// bits, its wave the segment's new total; single lanes of different waves write the node down.
+// While the loads are in flight two otherwise idle waves compute the path key of the new node
+// and the draws of the two new slots, which depend on (p, rank) only.
 constexpr int kRowState = kMaxSeg + 1;
+constexpr int kSlotsPerThread = (kMaxSlots + kBlock - 1) / kBlock;
+static_assert(DYSPEC_MAX_NODES <= 1024 && DYSPEC_MAX_VOCAB <= (1 << 21), "a slot's parent and rank share one word");
+
+__device__ __forceinline__ double readlane_f64(double x, int l)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), l), __builtin_amdgcn_readlane(__double2loint(x), l));
+}
+__device__ __forceinline__ float readlane_f32(float x, int l)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
+}
+// Among the lanes of `lanes` (a ballot, not empty) the one with the smallest idx; idx of that lane.
+__device__ __forceinline__ int first_of_equals(unsigned long long lanes, int idx, int* lane_out)
+{
+    int l = __builtin_ctzll(lanes);
+    int best = __builtin_amdgcn_readlane(idx, l);
+    for (unsigned long long rest = lanes & (lanes - 1); rest; rest &= rest - 1) {    // ties only
+        const int l2 = __builtin_ctzll(rest);
+        const int i2 = __builtin_amdgcn_readlane(idx, l2);
+        if (i2 < best) { best = i2; l = l2; }
+    }
+    *lane_out = l;
+    return best;
+}
+// The segment pick of pick_segment() with total j in lanes j, j + 16, ... (t: this lane's
+// total): an inclusive scan over each row of 16 lanes, a ballot for the first segment with
+// weight whose running sum is past u * W, the last segment with weight if rounding leaves none.
+__device__ __forceinline__ SegPick pick_segment_lanes(double t, double u)
+{
+    double c = t;
+    c += dpp_or_zero<0x111>(c);
+    c += dpp_or_zero<0x112>(c);
+    c += dpp_or_zero<0x114>(c);
+    c += dpp_or_zero<0x118>(c);
+    SegPick pk;
+    pk.W = readlane_f64(c, 15);
+    pk.target = u * pk.W;
+    const uint32_t hit = (uint32_t)__ballot(t > 0.0 && c > pk.target) & 0xffffu;
+    const uint32_t live = (uint32_t)__ballot(t > 0.0) & 0xffffu;
+    pk.js = hit ? __builtin_ctz(hit) : live ? 31 - __builtin_clz(live) : 0;
+    pk.cum_js = readlane_f64(c - t, pk.js);
+    return pk;
+}
 
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
@@ -306,39 +357,63 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         row_state[x] = ws_totals(ws, base + x / kRowState)[x % kRowState];
     init_tree_state(sh, seed, seq, base, N, tree, est_value, anc_mask, mask_words);
 
+    // this thread's slots tid, tid + kBlock, ...: value (< 0: closed), parent | rank << 10, draw
+    double my_v[kSlotsPerThread];
+    int my_pr[kSlotsPerThread];
+    float my_u[kSlotsPerThread];
+#pragma unroll
+    for (int k = 0; k < kSlotsPerThread; ++k) { my_v[k] = -1.0; my_pr[k] = 0; my_u[k] = 0.f; }
+    if (tid == 0) { my_v[0] = 1.0; my_u[0] = sh.slot_u[0]; }        // the root's slot
+    auto set_slot = [&](int s, double v, int pr, float u) {
+        if (tid == s % kBlock) {
+#pragma unroll
+            for (int k = 0; k < kSlotsPerThread; ++k)
+                if (k == s / kBlock) { my_v[k] = v; my_pr[k] = pr; my_u[k] = u; }
+        }
+    };
+
     int n = 1, n_slots = 1;
-    // what the previous draw did to the slots (thread 0 may still be writing it to LDS)
-    int closed = -1, open_a = -1, open_b = -1;
-    double open_a_v = 0.0, open_b_v = 0.0;
     while (n < N) {
         // ---- pop: open slot of largest value, earliest-opened on ties
-        double bv = -1.0; int bi = 0x7fffffff;
-        for (int s = tid; s < n_slots; s += kBlock) {
-            double v = sh.slot_value[s];
-            if (s == closed) v = -1.0;
-            else if (s == open_a) v = open_a_v;
-            else if (s == open_b) v = open_b_v;
-            if (v > bv) { bv = v; bi = s; }           // s ascends: ties keep the earlier slot
-        }
-        wave_argmax(bv, bi);
-        if (lane == 0) { sh.best_v[wave] = bv; sh.best_i[wave] = bi; }
-        __syncthreads();                               // barrier 1
-        double v = sh.best_v[0]; int pick = sh.best_i[0];
+        double bv = my_v[0]; int bi = tid, bpr = my_pr[0]; float bu = my_u[0];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) {
-            const double wv = sh.best_v[w]; const int wi = sh.best_i[w];
-            if (wv > v || (wv == v && wi < pick)) { v = wv; pick = wi; }
+        for (int k = 1; k < kSlotsPerThread; ++k)
+            if (my_v[k] > bv) { bv = my_v[k]; bi = tid + k * kBlock; bpr = my_pr[k]; bu = my_u[k]; }
+        {
+            double wv = bv;                            // largest value of the wave
+            wv = fmax(wv, dpp_or_zero<kDppXor1>(wv));
+            wv = fmax(wv, dpp_or_zero<kDppXor2>(wv));
+            wv = fmax(wv, dpp_or_zero<kDppHalfMirror>(wv));
+            wv = fmax(wv, dpp_or_zero<kDppMirror>(wv));
+            wv = fmax(fmax(readlane_f64(wv, 0), readlane_f64(wv, 16)), fmax(readlane_f64(wv, 32), readlane_f64(wv, 48)));
+            int wl;                                    // (a wave without an open slot: every lane holds -1, any will do)
+            const int wi = first_of_equals(wv > 0.0 ? __ballot(bv == wv) : 1ull, bi, &wl);
+            const int wpr = __builtin_amdgcn_readlane(bpr, wl);
+            const float wu = readlane_f32(bu, wl);
+            if (lane == 0) { sh.best_v[wave] = wv; sh.best_i[wave] = wi; sh.best_pr[wave] = wpr; sh.best_u[wave] = wu; }
         }
+        __syncthreads();                               // barrier 1
+        // the winner among the waves: lane l looks at wave l % 8
+        const double cv = sh.best_v[lane & 7];
+        const int ci = sh.best_i[lane & 7], cpr = sh.best_pr[lane & 7];
+        const float cu = sh.best_u[lane & 7];
+        double v = cv;
+        v = fmax(v, dpp_or_zero<kDppXor1>(v));
+        v = fmax(v, dpp_or_zero<kDppXor2>(v));
+        v = fmax(v, dpp_or_zero<kDppHalfMirror>(v));
+        v = readlane_f64(v, 0);
         if (!(v > 0.0)) break;                         // frontier is empty
-        const int p = sh.slot_parent[pick];
-        const int rank = sh.n_children[p];
+        int el;
+        const int pick = first_of_equals(__ballot(cv == v) & 0xffull, ci, &el);
+        const int pr = __builtin_amdgcn_readlane(cpr, el);
+        const int p = pr & 1023, rank = pr >> 10;
+        const double u = (double)readlane_f32(cu, el);
         // the parent's mask word, needed when the node is appended: on its way during the draw
+        const int mtid = tid - 4 * kWave;              // a wave that writes nothing else down
         uint64_t up = 0ull;
-        if (tid < mask_words) up = anc_mask[(size_t)(base + p) * mask_words + tid];
+        if (mtid >= 0 && mtid < mask_words) up = anc_mask[(size_t)(base + p) * mask_words + mtid];
 
         // ---- draw the token from the residual draft distribution of p
-        const double u = (double)sh.slot_u[pick];
-        const uint2 key_p = sh.pk[p];
         const float* __restrict__ row = draft_logits + (size_t)(base + p) * V;
         // (ws is written by this kernel and not declared restrict or const, so these are
         //  ordinary vector loads and stores; a sum or a bit word is only ever re-read by the
@@ -346,17 +421,9 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         double* const S = ws_sums(ws, base + p);
         double* const T = ws_totals(ws, base + p);
         const bool in_lds = p < n_lds;
-        double tot[kMaxSeg], m;
-        if (in_lds) {
-#pragma unroll
-            for (int j = 0; j < kMaxSeg; ++j) tot[j] = row_state[p * kRowState + j];
-            m = row_state[p * kRowState + kMaxSeg];
-        } else {
-#pragma unroll
-            for (int j = 0; j < kMaxSeg; ++j) tot[j] = T[j];
-            m = T[kMaxSeg];
-        }
-        const SegPick pk = pick_segment(tot, u);
+        const double my_tot = in_lds ? row_state[p * kRowState + (lane & 15)] : T[lane & 15];
+        const double m = in_lds ? row_state[p * kRowState + kMaxSeg] : T[kMaxSeg];
+        const SegPick pk = pick_segment_lanes(my_tot, u);
         const double W = pk.W;
         if (!(W > 0.0)) break;                         // nothing left to sample under p
         const int tok_mine = pk.js * kSeg + 4 * tid;   // this thread's four tokens of the segment
@@ -373,9 +440,9 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         }
         // ---- while the loads are on their way: the path key of the node this draw makes and the
         //      uniform draws of the two slots it opens depend on (p, rank) only.  One wave each.
-        if (wave == 1 && lane == 0) sh.next_u[0] = u01(seed, key_p, (uint32_t)rank + 1u, KIND_BUILD);
+        if (wave == 1 && lane == 0) sh.next_u[0] = u01(seed, sh.pk[p], (uint32_t)rank + 1u, KIND_BUILD);
         if (wave == 2 && lane == 0) {
-            const uint2 key_i = child_key(seed, key_p, (uint32_t)rank);
+            const uint2 key_i = child_key(seed, sh.pk[p], (uint32_t)rank);
             sh.next_key = key_i;
             sh.next_u[1] = u01(seed, key_i, 0u, KIND_BUILD);
         }
@@ -410,9 +477,9 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
             // can put the crossing on a thread without weight) the last one with weight
             const unsigned long long hit = __ballot(mine > 0.0 && pk.cum_js + incl > pk.target);
             const int ol = fixed_owner >= 0 ? fixed_owner % kWave : hit ? __builtin_ctzll(hit) : 63 - __builtin_clzll(live);
-            const float l0 = __shfl(lg[0], ol, kWave), l1 = __shfl(lg[1], ol, kWave);
-            const float l2 = __shfl(lg[2], ol, kWave), l3 = __shfl(lg[3], ol, kWave);
-            const uint32_t g = __shfl(gone, ol, kWave);
+            const float l0 = readlane_f32(lg[0], ol), l1 = readlane_f32(lg[1], ol);
+            const float l2 = readlane_f32(lg[2], ol), l3 = readlane_f32(lg[3], ol);
+            const uint32_t g = (uint32_t)__builtin_amdgcn_readlane((int)gone, ol);
             const int tok0 = pk.js * kSeg + 4 * (kw * kWave + ol);
             if (lane < 4) {
                 const float l = lane == 0 ? l0 : lane == 1 ? l1 : lane == 2 ? l2 : l3;
@@ -426,6 +493,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         const int owner = sh.owner;
         const int tok0 = pk.js * kSeg + 4 * owner;
         const double w4v[4] = { sh.w4[0], sh.w4[1], sh.w4[2], sh.w4[3] };
+        const float u_a = sh.next_u[0], u_b = sh.next_u[1];
         double run = sh.excl, wy = 0.0, wlast = 0.0;
         int y = -1, ylast = -1;
 #pragma unroll
@@ -437,6 +505,13 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         if (y < 0) { y = ylast; wy = wlast; }
         if (y < 0) break;                              // nothing left to sample under p
         const int ey = y - tok0;
+        // ---- node n: close the slot, open its two slots
+        const int i = n;
+        const double Ry = wy / W;
+        const double v0 = v * Ry, v1 = v * (1.0 - Ry);
+        set_slot(pick, -1.0, 0, 0.f);
+        if (v1 > 0.0) set_slot(n_slots++, v1, p | ((rank + 1) << 10), u_a);     // next sampling at this position
+        if (v0 > 0.0) set_slot(n_slots++, v0, i, u_b);                          // first child of the new node
         // the sum that held y and the total of its segment lose y's weight
         const double left = ((ey == 0 ? 0.0 : w4v[0]) + (ey == 1 ? 0.0 : w4v[1])) + ((ey == 2 ? 0.0 : w4v[2]) + (ey == 3 ? 0.0 : w4v[3]));
         if (wave == kw) {
@@ -452,22 +527,23 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
                 if (in_lds) row_state[p * kRowState + pk.js] = t; else T[pk.js] = t;
             }
         }
-
-        // ---- append node n, open its two slots (every thread knows them; thread 0 writes them down)
-        const int i = n;
-        const double Ry = wy / W;
-        const double v0 = v * Ry, v1 = v * (1.0 - Ry);
-        closed = pick; open_a = -1; open_b = -1;
-        if (v1 > 0.0) { open_a = n_slots++; open_a_v = v1; }      // next sampling at this position
-        if (v0 > 0.0) { open_b = n_slots++; open_b_v = v0; }      // first child of the new node
-        if (tid == 0) {
-            sh.slot_value[pick] = -1.0;
-            append_node(sh, tree, est_value, sh.next_key, base, p, i, rank, y, v);
-            if (open_a >= 0) { sh.slot_value[open_a] = v1; sh.slot_parent[open_a] = p; sh.slot_u[open_a] = sh.next_u[0]; }
-            if (open_b >= 0) { sh.slot_value[open_b] = v0; sh.slot_parent[open_b] = i; sh.slot_u[open_b] = sh.next_u[1]; }
+        // ---- the node is written down by single lanes of waves with nothing else to store
+        if (tid == 0) {                                // links in LDS and their copies
+            sh.token[i] = y;
+            if (sh.last_child[p] < 0) { sh.first_child[p] = i; tree.first_child[base + p] = i; }
+            else { sh.next_sibling[sh.last_child[p]] = i; tree.next_sibling[base + sh.last_child[p]] = i; }
+            sh.last_child[p] = i; sh.n_children[p] = rank + 1;
+            sh.pk[i] = sh.next_key;
         }
-        if (tid < mask_words)
-            anc_mask[(size_t)(base + i) * mask_words + tid] = up | ((tid == i / 64) ? (1ull << (i % 64)) : 0ull);
+        if (tid == 3 * kWave) {                        // the node's own row
+            const int dep = sh.depth[p] + 1;
+            sh.depth[i] = dep;
+            tree.parent[base + i] = p; tree.token[base + i] = y; tree.sib_rank[base + i] = rank;
+            tree.depth[base + i] = dep;
+            est_value[base + i] = (float)v;
+        }
+        if (mtid >= 0 && mtid < mask_words)
+            anc_mask[(size_t)(base + i) * mask_words + mtid] = up | ((mtid == i / 64) ? (1ull << (i % 64)) : 0ull);
         ++n;
     }
     if (tid == 0) n_built[seq] = n;
