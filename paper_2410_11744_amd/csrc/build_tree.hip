@@ -438,27 +438,22 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
 #pragma unroll
             for (int e = 0; e < 4; ++e) lg[e] = tok_mine + e < V ? row[tok_mine + e] : 0.f;
         }
-        // ---- while the loads are on their way: the path key of the node this draw makes and the
-        //      uniform draws of the two slots it opens depend on (p, rank) only.  One wave each.
-        if (wave == 1 && lane == 0) sh.next_u[0] = u01(seed, sh.pk[p], (uint32_t)rank + 1u, KIND_BUILD);
-        if (wave == 2 && lane == 0) {
-            const uint2 key_i = child_key(seed, sh.pk[p], (uint32_t)rank);
-            sh.next_key = key_i;
-            sh.next_u[1] = u01(seed, key_i, 0u, KIND_BUILD);
-        }
+        // 1 / W for the slot values, out of the way of the loads (see below)
+        const double inv_W = 1.0 / W;
         // ---- inclusive scan of the 512 sums in thread order
         const double inc = wave_scan_dpp(mine);
         if (lane == kWave - 1) sh.wave_tot[wave] = inc;
         __syncthreads();                               // barrier 2
-        double wt[kWaves], before = 0.0, cum = 0.0;
-        int kw = -1;                                   // first wave whose last thread is past u * W
-#pragma unroll
-        for (int k = 0; k < kWaves; ++k) {
-            wt[k] = sh.wave_tot[k];
-            if (k == wave) before = cum;
-            cum += wt[k];
-            if (kw < 0 && pk.cum_js + cum > pk.target) kw = k;
-        }
+        // the waves' totals, one per lane (lanes 0..7 of every row of 16), scanned like the totals
+        const double wt = (lane & 8) ? 0.0 : sh.wave_tot[lane & 7];
+        double wc = wt;
+        wc += dpp_or_zero<0x111>(wc);
+        wc += dpp_or_zero<0x112>(wc);
+        wc += dpp_or_zero<0x114>(wc);
+        const double before = readlane_f64(dpp_or_zero<0x111>(wc), __builtin_amdgcn_readfirstlane(wave));
+        // first wave whose running total is past u * W
+        const uint32_t past = (uint32_t)__ballot(pk.cum_js + wc > pk.target) & 0xffu;
+        int kw = past ? __builtin_ctz(past) : -1;
         const double incl = before + inc;
         const unsigned long long live = __ballot(mine > 0.0);
         int fixed_owner = -1;
@@ -470,6 +465,14 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
             for (int k = 0; k < kWaves; ++k) if (sh.last_live[k] >= 0) fixed_owner = sh.last_live[k];
             if (fixed_owner < 0) break;                // nothing left to sample under p
             kw = fixed_owner / kWave;
+        }
+        // ---- two waves that do not hold the crossing: the path key of the node this draw makes
+        //      and the uniform draws of the two slots it opens (functions of p and rank only)
+        if (wave == ((kw + 1) & 7) && lane == 0) sh.next_u[0] = u01(seed, sh.pk[p], (uint32_t)rank + 1u, KIND_BUILD);
+        if (wave == ((kw + 2) & 7) && lane == 0) {
+            const uint2 key_i = child_key(seed, sh.pk[p], (uint32_t)rank);
+            sh.next_key = key_i;
+            sh.next_u[1] = u01(seed, key_i, 0u, KIND_BUILD);
         }
         if (wave == kw) {
             // the wave's total is positive (it moved the running sum past the target), so a thread
@@ -507,7 +510,11 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         const int ey = y - tok0;
         // ---- node n: close the slot, open its two slots
         const int i = n;
-        const double Ry = wy / W;
+        // R[y] = wy / W: with the correctly rounded 1 / W at hand, a product and one correction step
+        // give the correctly rounded quotient; the last token of a row has R[y] = 1 exactly
+        double Ry = wy * inv_W;
+        Ry = fma(fma(-W, Ry, wy), inv_W, Ry);
+        if (wy == W) Ry = 1.0;
         const double v0 = v * Ry, v1 = v * (1.0 - Ry);
         set_slot(pick, -1.0, 0, 0.f);
         if (v1 > 0.0) set_slot(n_slots++, v1, p | ((rank + 1) << 10), u_a);     // next sampling at this position
@@ -520,10 +527,10 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
                 *gone_word = gone | (1u << (tok0 % 32 + ey));
             }
             const double wsum = wave_sum_dpp(tid == owner ? left : mine);   // the wave's sums again, the owner's replaced
-            if (lane == 0) {
-                double t = 0.0;
+            double t = 0.0;
 #pragma unroll
-                for (int k = 0; k < kWaves; ++k) t += k == kw ? wsum : wt[k];
+            for (int k = 0; k < kWaves; ++k) t += k == kw ? wsum : readlane_f64(wt, k);
+            if (lane == 0) {
                 if (in_lds) row_state[p * kRowState + pk.js] = t; else T[pk.js] = t;
             }
         }
