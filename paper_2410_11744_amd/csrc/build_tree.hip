@@ -527,9 +527,10 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
                 *gone_word = gone | (1u << (tok0 % 32 + ey));
             }
             const double wsum = wave_sum_dpp(tid == owner ? left : mine);   // the wave's sums again, the owner's replaced
-            double t = 0.0;
-#pragma unroll
-            for (int k = 0; k < kWaves; ++k) t += k == kw ? wsum : readlane_f64(wt, k);
+            double t = (lane & 15) == kw ? wsum : wt;                       // lanes 0..7: the waves' totals now
+            t += dpp_or_zero<kDppXor1>(t);
+            t += dpp_or_zero<kDppXor2>(t);
+            t += dpp_or_zero<kDppHalfMirror>(t);
             if (lane == 0) {
                 if (in_lds) row_state[p * kRowState + pk.js] = t; else T[pk.js] = t;
             }
