@@ -145,6 +145,11 @@ struct BuildShared {
     int best_i[kWaves];
     int best_pr[kWaves];                // the winning slot's parent | rank << 10 and draw (cached form)
     float best_u[kWaves];
+    double rest_v;                      // the best open slot outside the current draw (cached form)
+    int rest_i, rest_pr;
+    float rest_u;
+    double draw_wy;                     // the drawn token and its weight
+    int draw_y;
     float fred[kWaves];
     int n_slots;
     int pick;
@@ -280,20 +285,22 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
 // other in the workspace as well.
 //
 // The open slots live in registers: slot s belongs to thread s % kBlock, which keeps its value,
-// its (parent, rank) and the uniform draw of its sampling.  The pop is a maximum over each
-// thread's few slots, over the wave (DPP) and over the waves' winners (barrier 1); every thread
-// then knows the slot, its parent p, the rank of the child to draw and the draw u.
+// its (parent, rank) and the uniform draw of its sampling.  Every thread knows the slot being
+// drawn from, its parent p, the rank of the child to draw and the draw u.
 //
-// A draw: lanes read p's segment totals from LDS (one each) and pick the segment with a 16-lane
-// scan; every thread fetches, in one trip to global memory, its own sum of that segment, its
-// four logits and the word with its drawn-already bits; the sums are scanned (barrier 2).  The
-// waves' totals tell every thread which wave holds the crossing; that wave finds the thread
-// (the owner) with a ballot, hands the owner's logits to its first four lanes, and those
-// compute the four weights (barrier 3), after which every thread finishes the draw on its own:
-// token, weight, the values of the two slots the draw opens.  The owner stores its new sum and
-// bits, its wave the segment's new total; single lanes of different waves write the node down.
-// While the loads are in flight two otherwise idle waves compute the path key of the new node
-// and the draws of the two new slots, which depend on (p, rank) only.
+// A draw takes two barriers.  Lanes read p's segment totals from LDS (one each) and pick the
+// segment with a 16-lane scan; every thread fetches, in one trip to global memory, its own sum of
+// that segment, its four logits and the word with its drawn-already bits.  While those loads
+// are in flight each wave finds the best of its other open slots (DPP maximum and a ballot).
+// The sums are scanned (barrier 1).  The waves' totals tell every thread which wave holds the
+// crossing; that wave finds the thread (the owner) with a ballot, takes the owner's logits to
+// its first four lanes, which compute the four weights, finishes the draw (token, weight), has
+// the owner store its new sum and bits and writes the segment's new total.  Meanwhile three
+// other waves compute the path key of the new node and the draws of the two slots the draw
+// opens (functions of p and rank only) and reduce the waves' bests to the best open slot outside
+// this draw (barrier 2).  Every thread then computes the values of the two new slots, keeps them
+// if they are its own, and picks the next slot among those two and the best of the rest; single
+// lanes of different waves write the node down.
 constexpr int kRowState = kMaxSeg + 1;
 constexpr int kSlotsPerThread = (kMaxSlots + kBlock - 1) / kBlock;
 static_assert(DYSPEC_MAX_NODES <= 1024 && DYSPEC_MAX_VOCAB <= (1 << 21), "a slot's parent and rank share one word");
@@ -373,41 +380,10 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
     };
 
     int n = 1, n_slots = 1;
+    // the slot to draw from (known to every thread): the root's at first
+    int pick = 0, p = 0, rank = 0;
+    double v = 1.0, u = (double)sh.slot_u[0];
     while (n < N) {
-        // ---- pop: open slot of largest value, earliest-opened on ties
-        double bv = my_v[0]; int bi = tid, bpr = my_pr[0]; float bu = my_u[0];
-#pragma unroll
-        for (int k = 1; k < kSlotsPerThread; ++k)
-            if (my_v[k] > bv) { bv = my_v[k]; bi = tid + k * kBlock; bpr = my_pr[k]; bu = my_u[k]; }
-        {
-            double wv = bv;                            // largest value of the wave
-            wv = fmax(wv, dpp_or_zero<kDppXor1>(wv));
-            wv = fmax(wv, dpp_or_zero<kDppXor2>(wv));
-            wv = fmax(wv, dpp_or_zero<kDppHalfMirror>(wv));
-            wv = fmax(wv, dpp_or_zero<kDppMirror>(wv));
-            wv = fmax(fmax(readlane_f64(wv, 0), readlane_f64(wv, 16)), fmax(readlane_f64(wv, 32), readlane_f64(wv, 48)));
-            int wl;                                    // (a wave without an open slot: every lane holds -1, any will do)
-            const int wi = first_of_equals(wv > 0.0 ? __ballot(bv == wv) : 1ull, bi, &wl);
-            const int wpr = __builtin_amdgcn_readlane(bpr, wl);
-            const float wu = readlane_f32(bu, wl);
-            if (lane == 0) { sh.best_v[wave] = wv; sh.best_i[wave] = wi; sh.best_pr[wave] = wpr; sh.best_u[wave] = wu; }
-        }
-        __syncthreads();                               // barrier 1
-        // the winner among the waves: lane l looks at wave l % 8
-        const double cv = sh.best_v[lane & 7];
-        const int ci = sh.best_i[lane & 7], cpr = sh.best_pr[lane & 7];
-        const float cu = sh.best_u[lane & 7];
-        double v = cv;
-        v = fmax(v, dpp_or_zero<kDppXor1>(v));
-        v = fmax(v, dpp_or_zero<kDppXor2>(v));
-        v = fmax(v, dpp_or_zero<kDppHalfMirror>(v));
-        v = readlane_f64(v, 0);
-        if (!(v > 0.0)) break;                         // frontier is empty
-        int el;
-        const int pick = first_of_equals(__ballot(cv == v) & 0xffull, ci, &el);
-        const int pr = __builtin_amdgcn_readlane(cpr, el);
-        const int p = pr & 1023, rank = pr >> 10;
-        const double u = (double)readlane_f32(cu, el);
         // the parent's mask word, needed when the node is appended: on its way during the draw
         const int mtid = tid - 4 * kWave;              // a wave that writes nothing else down
         uint64_t up = 0ull;
@@ -416,8 +392,8 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         // ---- draw the token from the residual draft distribution of p
         const float* __restrict__ row = draft_logits + (size_t)(base + p) * V;
         // (ws is written by this kernel and not declared restrict or const, so these are
-        //  ordinary vector loads and stores; a sum or a bit word is only ever re-read by the
-        //  wave that wrote it, totals kept in the workspace are ordered by the barriers)
+        //  ordinary vector loads and stores; a sum, a bit word or a mask word is only ever re-read
+        //  by the wave that wrote it, totals kept in the workspace are ordered by the barriers)
         double* const S = ws_sums(ws, base + p);
         double* const T = ws_totals(ws, base + p);
         const bool in_lds = p < n_lds;
@@ -438,12 +414,30 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
 #pragma unroll
             for (int e = 0; e < 4; ++e) lg[e] = tok_mine + e < V ? row[tok_mine + e] : 0.f;
         }
-        // 1 / W for the slot values, out of the way of the loads (see below)
+        // ---- while the loads are on their way: 1 / W for the slot values, and the best of this
+        //      wave's open slots other than the one being drawn from (for the next pop)
         const double inv_W = 1.0 / W;
+        {
+            double bv = -1.0; int bi = 0x7fffffff, bpr = 0; float bu = 0.f;
+#pragma unroll
+            for (int k = 0; k < kSlotsPerThread; ++k)
+                if (my_v[k] > bv && tid + k * kBlock != pick) { bv = my_v[k]; bi = tid + k * kBlock; bpr = my_pr[k]; bu = my_u[k]; }
+            double wv = bv;                            // largest value of the wave
+            wv = fmax(wv, dpp_or_zero<kDppXor1>(wv));
+            wv = fmax(wv, dpp_or_zero<kDppXor2>(wv));
+            wv = fmax(wv, dpp_or_zero<kDppHalfMirror>(wv));
+            wv = fmax(wv, dpp_or_zero<kDppMirror>(wv));
+            wv = fmax(fmax(readlane_f64(wv, 0), readlane_f64(wv, 16)), fmax(readlane_f64(wv, 32), readlane_f64(wv, 48)));
+            int wl;                                    // (a wave without an open slot: every lane holds -1, any will do)
+            const int wi = first_of_equals(wv > 0.0 ? __ballot(bv == wv) : 1ull, bi, &wl);
+            const int wpr = __builtin_amdgcn_readlane(bpr, wl);
+            const float wu = readlane_f32(bu, wl);
+            if (lane == 0) { sh.best_v[wave] = wv; sh.best_i[wave] = wi; sh.best_pr[wave] = wpr; sh.best_u[wave] = wu; }
+        }
         // ---- inclusive scan of the 512 sums in thread order
         const double inc = wave_scan_dpp(mine);
         if (lane == kWave - 1) sh.wave_tot[wave] = inc;
-        __syncthreads();                               // barrier 2
+        __syncthreads();                               // barrier 1 of 2
         // the waves' totals, one per lane (lanes 0..7 of every row of 16), scanned like the totals
         const double wt = (lane & 8) ? 0.0 : sh.wave_tot[lane & 7];
         double wc = wt;
@@ -466,13 +460,29 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
             if (fixed_owner < 0) break;                // nothing left to sample under p
             kw = fixed_owner / kWave;
         }
-        // ---- two waves that do not hold the crossing: the path key of the node this draw makes
-        //      and the uniform draws of the two slots it opens (functions of p and rank only)
+        // ---- three waves that do not hold the crossing: the path key of the node this draw makes
+        //      and the uniform draws of the two slots it opens (functions of p and rank only); the
+        //      best open slot outside this draw (the winner among the waves' bests)
         if (wave == ((kw + 1) & 7) && lane == 0) sh.next_u[0] = u01(seed, sh.pk[p], (uint32_t)rank + 1u, KIND_BUILD);
         if (wave == ((kw + 2) & 7) && lane == 0) {
             const uint2 key_i = child_key(seed, sh.pk[p], (uint32_t)rank);
             sh.next_key = key_i;
             sh.next_u[1] = u01(seed, key_i, 0u, KIND_BUILD);
+        }
+        if (wave == ((kw + 3) & 7)) {
+            const double cv = sh.best_v[lane & 7];     // lane l looks at wave l % 8
+            const int ci = sh.best_i[lane & 7], cpr = sh.best_pr[lane & 7];
+            const float cu = sh.best_u[lane & 7];
+            double rv = cv;
+            rv = fmax(rv, dpp_or_zero<kDppXor1>(rv));
+            rv = fmax(rv, dpp_or_zero<kDppXor2>(rv));
+            rv = fmax(rv, dpp_or_zero<kDppHalfMirror>(rv));
+            rv = readlane_f64(rv, 0);
+            int el;
+            const int ri = first_of_equals(rv > 0.0 ? __ballot(cv == rv) & 0xffull : 1ull, ci, &el);
+            const int rpr = __builtin_amdgcn_readlane(cpr, el);
+            const float ru = readlane_f32(cu, el);
+            if (lane == 0) { sh.rest_v = rv; sh.rest_i = ri; sh.rest_pr = rpr; sh.rest_u = ru; }
         }
         if (wave == kw) {
             // the wave's total is positive (it moved the running sum past the target), so a thread
@@ -484,30 +494,49 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
             const float l2 = readlane_f32(lg[2], ol), l3 = readlane_f32(lg[3], ol);
             const uint32_t g = (uint32_t)__builtin_amdgcn_readlane((int)gone, ol);
             const int tok0 = pk.js * kSeg + 4 * (kw * kWave + ol);
+            // the first four lanes compute one weight each; then every lane of the wave finishes the
+            // draw: the token among the four, what is left of their sum
+            double w = 0.0;
             if (lane < 4) {
                 const float l = lane == 0 ? l0 : lane == 1 ? l1 : lane == 2 ? l2 : l3;
                 const bool there = tok0 + lane < V && !((g >> (tok0 % 32 + lane)) & 1u);
-                sh.w4[lane] = there ? token_weight(l, inv_temp, m) : 0.0;
+                if (there) w = token_weight(l, inv_temp, m);
             }
-            if (lane == ol) { sh.excl = pk.cum_js + (incl - mine); sh.owner = kw * kWave + ol; }
-        }
-        __syncthreads();                               // barrier 3
-        // ---- every thread finishes the draw: the token among the four, what is left of their sum
-        const int owner = sh.owner;
-        const int tok0 = pk.js * kSeg + 4 * owner;
-        const double w4v[4] = { sh.w4[0], sh.w4[1], sh.w4[2], sh.w4[3] };
-        const float u_a = sh.next_u[0], u_b = sh.next_u[1];
-        double run = sh.excl, wy = 0.0, wlast = 0.0;
-        int y = -1, ylast = -1;
+            const double w4v[4] = { readlane_f64(w, 0), readlane_f64(w, 1), readlane_f64(w, 2), readlane_f64(w, 3) };
+            double run = readlane_f64(pk.cum_js + (incl - mine), ol), wy = 0.0, wlast = 0.0;
+            int y = -1, ylast = -1;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            run += w4v[e];
-            if (w4v[e] > 0.0) { ylast = tok0 + e; wlast = w4v[e]; }
-            if (y < 0 && w4v[e] > 0.0 && run > pk.target) { y = tok0 + e; wy = w4v[e]; }
+            for (int e = 0; e < 4; ++e) {
+                run += w4v[e];
+                if (w4v[e] > 0.0) { ylast = tok0 + e; wlast = w4v[e]; }
+                if (y < 0 && w4v[e] > 0.0 && run > pk.target) { y = tok0 + e; wy = w4v[e]; }
+            }
+            if (y < 0) { y = ylast; wy = wlast; }
+            if (lane == 0) { sh.draw_y = y; sh.draw_wy = wy; }
+            if (y >= 0) {
+                // the sum that held y and the total of its segment lose y's weight
+                const int ey = y - tok0;
+                const double left = ((ey == 0 ? 0.0 : w4v[0]) + (ey == 1 ? 0.0 : w4v[1])) + ((ey == 2 ? 0.0 : w4v[2]) + (ey == 3 ? 0.0 : w4v[3]));
+                if (lane == ol) {
+                    S[pk.js * kBlock + tid] = left;
+                    *gone_word = gone | (1u << (tok0 % 32 + ey));
+                }
+                const double wsum = wave_sum_dpp(lane == ol ? left : mine);     // the wave's sums again, the owner's replaced
+                double t = (lane & 15) == kw ? wsum : wt;                       // lanes 0..7: the waves' totals now
+                t += dpp_or_zero<kDppXor1>(t);
+                t += dpp_or_zero<kDppXor2>(t);
+                t += dpp_or_zero<kDppHalfMirror>(t);
+                if (lane == 0) {
+                    if (in_lds) row_state[p * kRowState + pk.js] = t; else T[pk.js] = t;
+                }
+            }
         }
-        if (y < 0) { y = ylast; wy = wlast; }
+        __syncthreads();                               // barrier 2 of 2
+        const int y = sh.draw_y;
+        const double wy = sh.draw_wy;
+        const float u_a = sh.next_u[0], u_b = sh.next_u[1];
+        double nv = sh.rest_v; int ni = sh.rest_i, npr = sh.rest_pr; float nu = sh.rest_u;
         if (y < 0) break;                              // nothing left to sample under p
-        const int ey = y - tok0;
         // ---- node n: close the slot, open its two slots
         const int i = n;
         // R[y] = wy / W: with the correctly rounded 1 / W at hand, a product and one correction step
@@ -517,24 +546,6 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         if (wy == W) Ry = 1.0;
         const double v0 = v * Ry, v1 = v * (1.0 - Ry);
         set_slot(pick, -1.0, 0, 0.f);
-        if (v1 > 0.0) set_slot(n_slots++, v1, p | ((rank + 1) << 10), u_a);     // next sampling at this position
-        if (v0 > 0.0) set_slot(n_slots++, v0, i, u_b);                          // first child of the new node
-        // the sum that held y and the total of its segment lose y's weight
-        const double left = ((ey == 0 ? 0.0 : w4v[0]) + (ey == 1 ? 0.0 : w4v[1])) + ((ey == 2 ? 0.0 : w4v[2]) + (ey == 3 ? 0.0 : w4v[3]));
-        if (wave == kw) {
-            if (tid == owner) {
-                S[pk.js * kBlock + tid] = left;
-                *gone_word = gone | (1u << (tok0 % 32 + ey));
-            }
-            const double wsum = wave_sum_dpp(tid == owner ? left : mine);   // the wave's sums again, the owner's replaced
-            double t = (lane & 15) == kw ? wsum : wt;                       // lanes 0..7: the waves' totals now
-            t += dpp_or_zero<kDppXor1>(t);
-            t += dpp_or_zero<kDppXor2>(t);
-            t += dpp_or_zero<kDppHalfMirror>(t);
-            if (lane == 0) {
-                if (in_lds) row_state[p * kRowState + pk.js] = t; else T[pk.js] = t;
-            }
-        }
         // ---- the node is written down by single lanes of waves with nothing else to store
         if (tid == 0) {                                // links in LDS and their copies
             sh.token[i] = y;
@@ -553,6 +564,19 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         if (mtid >= 0 && mtid < mask_words)
             anc_mask[(size_t)(base + i) * mask_words + mtid] = up | ((mtid == i / 64) ? (1ull << (i % 64)) : 0ull);
         ++n;
+        // ---- the two new slots, and the next pop: the best slot outside this draw or one of the
+        //      new ones (largest value, earliest-opened on ties: the new ones are the latest)
+        if (v1 > 0.0) {                                // next sampling at this position
+            const int pr_a = p | ((rank + 1) << 10);
+            if (v1 > nv) { nv = v1; ni = n_slots; npr = pr_a; nu = u_a; }
+            set_slot(n_slots++, v1, pr_a, u_a);
+        }
+        if (v0 > 0.0) {                                // first child of the new node
+            if (v0 > nv) { nv = v0; ni = n_slots; npr = i; nu = u_b; }
+            set_slot(n_slots++, v0, i, u_b);
+        }
+        if (!(nv > 0.0)) break;                        // frontier is empty
+        pick = ni; p = npr & 1023; rank = npr >> 10; v = nv; u = (double)nu;
     }
     if (tid == 0) n_built[seq] = n;
 }
