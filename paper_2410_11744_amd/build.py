@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdyspec.so")
 SOURCES = ["api.hip", "build_tree.hip", "verify.hip", "tree_attn.hip", "tree_attn_mfma.hip", "ceilings.hip", "reorder.hip", "build_threshold.hip"]
-HEADERS = ["dyspec_device.h", "vocab_common.h", "draft_row.h", os.path.join("..", "..", "include", "dyspec.h")]
+HEADERS = ["dyspec_device.h", "vocab_common.h", "draft_row.h", "lane_ops.h", os.path.join("..", "..", "include", "dyspec.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed fp32 VALU forms are kept out of the generated code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

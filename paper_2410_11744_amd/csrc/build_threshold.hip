@@ -14,6 +14,7 @@
 // ancestor masks.  The host reads the level's size back after every commit: it sizes the next
 // grid and ends the loop.  Draft row of a node = its row index, as for Algorithm 1.
 #include "draft_row.h"
+#include "lane_ops.h"
 
 namespace dyspec {
 
@@ -100,19 +101,21 @@ __global__ __launch_bounds__(256) void threshold_init_kernel(SeqArgs sa, dyspec_
 struct ExpandShared {
     double red[kWaves * kMaxSeg];       // workgroup sums at set-up
     double wave_tot[kWaves];            // per draw: the waves' sums of the picked segment
-    double w4[4];                       // weights of the four tokens of the thread that owns the crossing
-    double excl;                        // weight in front of those four
-    int first_hit[kWaves];              // first thread of each wave past the crossing, -1: none
+    double wy, old_sum, new_sum;        // per draw: the drawn token's weight, its thread's sum before and after
+    int y, owner;                       // the drawn token, the thread that held it
     int last_live[kWaves];              // last thread of each wave with weight left, -1: none
     float fred[kWaves];
+    float u_draw[DYSPEC_MAX_NODES];     // the uniform draws of this node's samplings, by child rank
 };
 
 // One workgroup per node of the current level: blockIdx.x = position in the level.  The node's
 // row of logits and a drawn-already bitmap live in LDS (dynamic: 4 bytes per token, 1 bit per
-// token), the threads' 4-token weight sums and the 16 segment totals in registers.  A draw is:
-// segment pick (registers), a scan of the 512 sums of that segment (shuffles, one barrier), a
-// ballot for the thread that holds the crossing (one barrier), the four weights of that thread
-// computed by four threads (one barrier), and then every thread finishes the draw by itself.
+// token), the threads' 4-token weight sums in registers, segment total j in lanes j, j + 16, ...
+// A draw is: segment pick (a 16-lane scan), a scan of the 512 sums of that segment (DPP, one
+// barrier); the waves' totals tell every thread which wave holds the crossing; that wave finds
+// the owning thread with a ballot, computes its four weights in four lanes and finishes the draw
+// (one barrier); every thread then updates its copy of the totals.  The uniform draws of all
+// samplings of the node (functions of its path key and the child rank) are made at set-up.
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void threshold_expand_kernel(const float* __restrict__ draft_logits, int V, SeqArgs sa,
                                                                   ThresholdArgs ta, uint64_t seed, ThresholdWs w)
@@ -143,82 +146,93 @@ __global__ __launch_bounds__(kBlock) void threshold_expand_kernel(const float* _
     for (int i = tid; i < Vpad; i += kBlock) row_lds[i] = (i < V) ? row[i] : -INFINITY;
     for (int i = tid; i < Vpad / 32; i += kBlock) gone[i] = 0u;
 
+    for (int c = tid; c < left; c += kBlock) sh.u_draw[c] = u01(seed, pk_p, (uint32_t)c, KIND_BUILD);
+
     double m, seg[kMaxSeg], tot[kMaxSeg];
     row_segment_sums<VEC>(row, V, inv_temp, 0ull, sh.fred, &m, seg);
 #pragma unroll
     for (int j = 0; j < kMaxSeg; ++j) tot[j] = seg[j];
     block_sum<double, kMaxSeg>(tot, sh.red);
-    __syncthreads();                                    // the row and the bitmap are in LDS for everyone
+    double my_tot = 0.0;                                // total of segment lane % 16
+#pragma unroll
+    for (int j = 0; j < kMaxSeg; ++j) if (j == (lane & 15)) my_tot = tot[j];
+    __syncthreads();                                    // the row, the bitmap and the draws are in LDS for everyone
 
     int count = 0;
     while (v >= t && count < left) {
-        const double u = (double)u01(seed, pk_p, (uint32_t)count, KIND_BUILD);
-        const SegPick pk = pick_segment(tot, u);
+        const double u = (double)sh.u_draw[count];
+        const SegPick pk = pick_segment_lanes(my_tot, u);
         if (!(pk.W > 0.0)) break;                       // nothing left to sample under p
         double mine = 0.0;
 #pragma unroll
         for (int j = 0; j < kMaxSeg; ++j) if (j == pk.js) mine = seg[j];
         // ---- inclusive scan of the sums of segment js in thread order
-        double inc = mine;
-#pragma unroll
-        for (int o = 1; o < kWave; o <<= 1) {
-            const double up = __shfl_up(inc, o, kWave);
-            if (lane >= o) inc += up;
-        }
+        const double inc = wave_scan_dpp(mine);
         if (lane == kWave - 1) sh.wave_tot[wave] = inc;
         __syncthreads();
-        double before = 0.0;
-        for (int k = 0; k < wave; ++k) before += sh.wave_tot[k];
+        // the waves' totals, one per lane (lanes 0..7 of every row of 16), scanned the same way
+        const double wt = (lane & 8) ? 0.0 : sh.wave_tot[lane & 7];
+        double wc = wt;
+        wc += dpp_or_zero<0x111>(wc);
+        wc += dpp_or_zero<0x112>(wc);
+        wc += dpp_or_zero<0x114>(wc);
+        const double before = readlane_f64(dpp_or_zero<0x111>(wc), wave);
+        const uint32_t past = (uint32_t)__ballot(pk.cum_js + wc > pk.target) & 0xffu;
+        int kw = past ? __builtin_ctz(past) : -1;       // first wave whose running total is past u * W
         const double incl = before + inc;
-        // ---- the first thread whose prefix passes u * W holds the drawn token
-        const unsigned long long hit = __ballot(mine > 0.0 && pk.cum_js + incl > pk.target);
         const unsigned long long live = __ballot(mine > 0.0);
-        if (lane == 0) {
-            sh.first_hit[wave] = hit ? wave * kWave + __builtin_ctzll(hit) : -1;
-            sh.last_live[wave] = live ? wave * kWave + 63 - __builtin_clzll(live) : -1;
-        }
-        __syncthreads();
-        int owner = -1, last = -1;
+        int fixed_owner = -1;
+        if (kw < 0) {
+            // rounding at the very top: the last thread with weight left (the same in every thread)
+            if (lane == 0) sh.last_live[wave] = live ? wave * kWave + 63 - __builtin_clzll(live) : -1;
+            __syncthreads();
 #pragma unroll
-        for (int k = 0; k < kWaves; ++k) {
-            if (owner < 0 && sh.first_hit[k] >= 0) owner = sh.first_hit[k];
-            if (sh.last_live[k] >= 0) last = sh.last_live[k];
+            for (int k = 0; k < kWaves; ++k) if (sh.last_live[k] >= 0) fixed_owner = sh.last_live[k];
+            if (fixed_owner < 0) break;                 // the totals held rounding dust only
+            kw = fixed_owner / kWave;
         }
-        if (owner < 0) owner = last;                    // rounding at the very top: the last thread with weight left
-        if (owner < 0) break;                           // the totals held rounding dust only
-        const int tok0 = pk.js * kSeg + 4 * owner;      // first of the owner's four tokens
-        if (tid == owner) sh.excl = pk.cum_js + (incl - mine);
-        if (tid < 4) {
-            const int idx = tok0 + tid;
-            const bool there = idx < V && !((gone[idx >> 5] >> (idx & 31)) & 1u);
-            sh.w4[tid] = there ? token_weight(row_lds[idx], inv_temp, m) : 0.0;
-        }
-        __syncthreads();
-        // ---- every thread finishes the draw: the token among the four, what is left of their sum
-        const double w0 = sh.w4[0], w1 = sh.w4[1], w2 = sh.w4[2], w3 = sh.w4[3];
-        double run = sh.excl, wy = 0.0, wlast = 0.0;
-        int y = -1, ylast = -1;
-        const double w4v[4] = { w0, w1, w2, w3 };
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            run += w4v[e];
-            if (w4v[e] > 0.0) { ylast = tok0 + e; wlast = w4v[e]; }
-            if (y < 0 && w4v[e] > 0.0 && run > pk.target) { y = tok0 + e; wy = w4v[e]; }
-        }
-        if (y < 0) { y = ylast; wy = wlast; }
-        if (y < 0) break;
-        const int ey = y - tok0;
-        const double old_sum = (w0 + w1) + (w2 + w3);
-        const double new_sum = ((ey == 0 ? 0.0 : w0) + (ey == 1 ? 0.0 : w1)) + ((ey == 2 ? 0.0 : w2) + (ey == 3 ? 0.0 : w3));
-#pragma unroll
-        for (int j = 0; j < kMaxSeg; ++j)
-            if (j == pk.js) {
-                if (tid == owner) seg[j] = new_sum;
-                tot[j] = (tot[j] - old_sum) + new_sum;  // every thread keeps the same totals
+        if (wave == kw) {
+            // the wave's total is positive, so a thread with weight exists: the first one past the
+            // target, else (the scan's rounding) the last one with weight
+            const unsigned long long hit = __ballot(mine > 0.0 && pk.cum_js + incl > pk.target);
+            const int ol = fixed_owner >= 0 ? fixed_owner % kWave : hit ? __builtin_ctzll(hit) : 63 - __builtin_clzll(live);
+            const int tok0 = pk.js * kSeg + 4 * (kw * kWave + ol);      // first of the owner's four tokens
+            double wgt = 0.0;                           // lanes 0..3: one weight each
+            if (lane < 4) {
+                const int idx = tok0 + lane;
+                const bool there = idx < V && !((gone[idx >> 5] >> (idx & 31)) & 1u);
+                if (there) wgt = token_weight(row_lds[idx], inv_temp, m);
             }
+            const double w4v[4] = { readlane_f64(wgt, 0), readlane_f64(wgt, 1), readlane_f64(wgt, 2), readlane_f64(wgt, 3) };
+            double run = readlane_f64(pk.cum_js + (incl - mine), ol), wy = 0.0, wlast = 0.0;
+            int y = -1, ylast = -1;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                run += w4v[e];
+                if (w4v[e] > 0.0) { ylast = tok0 + e; wlast = w4v[e]; }
+                if (y < 0 && w4v[e] > 0.0 && run > pk.target) { y = tok0 + e; wy = w4v[e]; }
+            }
+            if (y < 0) { y = ylast; wy = wlast; }
+            const int ey = y - tok0;
+            if (lane == 0) {
+                sh.y = y; sh.wy = wy; sh.owner = kw * kWave + ol;
+                sh.old_sum = (w4v[0] + w4v[1]) + (w4v[2] + w4v[3]);
+                sh.new_sum = ((ey == 0 ? 0.0 : w4v[0]) + (ey == 1 ? 0.0 : w4v[1])) + ((ey == 2 ? 0.0 : w4v[2]) + (ey == 3 ? 0.0 : w4v[3]));
+            }
+        }
+        __syncthreads();
+        // ---- every thread updates its copy of the state
+        const int y = sh.y;
+        if (y < 0) break;
+        const double wy = sh.wy, old_sum = sh.old_sum, new_sum = sh.new_sum;
+        if (tid == sh.owner) {
+#pragma unroll
+            for (int j = 0; j < kMaxSeg; ++j) if (j == pk.js) seg[j] = new_sum;
+        }
+        if ((lane & 15) == pk.js) my_tot = (my_tot - old_sum) + new_sum;
         const double dy = wy / pk.W;
         if (tid == 0) {
-            gone[y >> 5] |= 1u << (y & 31);             // read again two barriers from here at the earliest
+            gone[y >> 5] |= 1u << (y & 31);             // read again one barrier from here at the earliest
             w.pool_token[pool0 + count] = y;
             w.pool_v[pool0 + count] = v;
             w.pool_v0[pool0 + count] = v * dy;

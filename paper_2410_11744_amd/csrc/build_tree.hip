@@ -18,6 +18,7 @@
 // workspace the builder (build_tree_kernel) recomputes the sums of the parent's row for every
 // draw; both ways take the same decisions and build the same tree.
 #include "draft_row.h"
+#include "lane_ops.h"
 
 namespace dyspec {
 
@@ -58,67 +59,6 @@ __global__ __launch_bounds__(kBlock) void draft_row_sums_kernel(const float* __r
     }
     if (threadIdx.x == 0) *ws_rowmax(ws, row) = m;
     for (int w = threadIdx.x; w < kGoneWords; w += kBlock) ws_gone(ws, row)[w] = 0u;
-}
-
-// Cross-lane moves of the vector ALU (DPP) for the serial builder's reductions and scan; a
-// shuffle would go through the LDS crossbar and wait for it at every step.
-constexpr int kDppXor1 = 0xB1;          // quad_perm [1,0,3,2]
-constexpr int kDppXor2 = 0x4E;          // quad_perm [2,3,0,1]
-constexpr int kDppHalfMirror = 0x141;   // lane i of a group of 8 <-> lane 7-i
-constexpr int kDppMirror = 0x140;       // lane i of a row of 16 <-> lane 15-i
-constexpr int kDppBcast15 = 0x142;      // lane 15 of a row to the next row
-constexpr int kDppBcast31 = 0x143;      // lane 31 to rows 2 and 3
-template <int CTRL, int ROW_MASK = 0xf>
-__device__ __forceinline__ int dpp_or_zero(int x)   // the picked lane's x; 0 where there is none or the row is masked off
-{
-    return __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, 0xf, false);
-}
-template <int CTRL, int ROW_MASK = 0xf>
-__device__ __forceinline__ double dpp_or_zero(double x)
-{
-    return __hiloint2double(dpp_or_zero<CTRL, ROW_MASK>(__double2hiint(x)), dpp_or_zero<CTRL, ROW_MASK>(__double2loint(x)));
-}
-// Largest value of the wave and, among equals, the smallest index; the same in every lane.
-__device__ __forceinline__ void wave_argmax(double& bv, int& bi)
-{
-    auto take = [&](double ov, int oi) { if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; } };
-    // values are >= -1 and a picked lane always exists for these four patterns
-    take(dpp_or_zero<kDppXor1>(bv), dpp_or_zero<kDppXor1>(bi));
-    take(dpp_or_zero<kDppXor2>(bv), dpp_or_zero<kDppXor2>(bi));
-    take(dpp_or_zero<kDppHalfMirror>(bv), dpp_or_zero<kDppHalfMirror>(bi));
-    take(dpp_or_zero<kDppMirror>(bv), dpp_or_zero<kDppMirror>(bi));
-    // every row of 16 lanes agrees now: combine the four rows
-    const double v0 = bv; const int i0 = bi;
-    bv = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v0), 0), __builtin_amdgcn_readlane(__double2loint(v0), 0));
-    bi = __builtin_amdgcn_readlane(i0, 0);
-#pragma unroll
-    for (int r = 1; r < 4; ++r)
-        take(__hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v0), 16 * r), __builtin_amdgcn_readlane(__double2loint(v0), 16 * r)),
-             __builtin_amdgcn_readlane(i0, 16 * r));
-}
-// Sum over the wave, the same in every lane.
-__device__ __forceinline__ double wave_sum_dpp(double x)
-{
-    x += dpp_or_zero<kDppXor1>(x);
-    x += dpp_or_zero<kDppXor2>(x);
-    x += dpp_or_zero<kDppHalfMirror>(x);
-    x += dpp_or_zero<kDppMirror>(x);
-    double r[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-        r[k] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), 16 * k), __builtin_amdgcn_readlane(__double2loint(x), 16 * k));
-    return (r[0] + r[1]) + (r[2] + r[3]);
-}
-// Inclusive scan over the wave in lane order.
-__device__ __forceinline__ double wave_scan_dpp(double x)
-{
-    x += dpp_or_zero<0x111>(x);                  // row_shr:1, 2, 4, 8: scan inside each row of 16
-    x += dpp_or_zero<0x112>(x);
-    x += dpp_or_zero<0x114>(x);
-    x += dpp_or_zero<0x118>(x);
-    x += dpp_or_zero<kDppBcast15, 0xa>(x);       // rows 1 and 3 add the total of the row before
-    x += dpp_or_zero<kDppBcast31, 0xc>(x);       // rows 2 and 3 add the total of the first two rows
-    return x;
 }
 
 struct BuildShared {
@@ -305,47 +245,6 @@ constexpr int kRowState = kMaxSeg + 1;
 constexpr int kSlotsPerThread = (kMaxSlots + kBlock - 1) / kBlock;
 static_assert(DYSPEC_MAX_NODES <= 1024 && DYSPEC_MAX_VOCAB <= (1 << 21), "a slot's parent and rank share one word");
 
-__device__ __forceinline__ double readlane_f64(double x, int l)
-{
-    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), l), __builtin_amdgcn_readlane(__double2loint(x), l));
-}
-__device__ __forceinline__ float readlane_f32(float x, int l)
-{
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
-}
-// Among the lanes of `lanes` (a ballot, not empty) the one with the smallest idx; idx of that lane.
-__device__ __forceinline__ int first_of_equals(unsigned long long lanes, int idx, int* lane_out)
-{
-    int l = __builtin_ctzll(lanes);
-    int best = __builtin_amdgcn_readlane(idx, l);
-    for (unsigned long long rest = lanes & (lanes - 1); rest; rest &= rest - 1) {    // ties only
-        const int l2 = __builtin_ctzll(rest);
-        const int i2 = __builtin_amdgcn_readlane(idx, l2);
-        if (i2 < best) { best = i2; l = l2; }
-    }
-    *lane_out = l;
-    return best;
-}
-// The segment pick of pick_segment() with total j in lanes j, j + 16, ... (t: this lane's
-// total): an inclusive scan over each row of 16 lanes, a ballot for the first segment with
-// weight whose running sum is past u * W, the last segment with weight if rounding leaves none.
-__device__ __forceinline__ SegPick pick_segment_lanes(double t, double u)
-{
-    double c = t;
-    c += dpp_or_zero<0x111>(c);
-    c += dpp_or_zero<0x112>(c);
-    c += dpp_or_zero<0x114>(c);
-    c += dpp_or_zero<0x118>(c);
-    SegPick pk;
-    pk.W = readlane_f64(c, 15);
-    pk.target = u * pk.W;
-    const uint32_t hit = (uint32_t)__ballot(t > 0.0 && c > pk.target) & 0xffffu;
-    const uint32_t live = (uint32_t)__ballot(t > 0.0) & 0xffffu;
-    pk.js = hit ? __builtin_ctz(hit) : live ? 31 - __builtin_clz(live) : 0;
-    pk.cum_js = readlane_f64(c - t, pk.js);
-    return pk;
-}
-
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
     const float* __restrict__ draft_logits, int V, SeqArgs sa, uint64_t seed,
@@ -422,12 +321,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
 #pragma unroll
             for (int k = 0; k < kSlotsPerThread; ++k)
                 if (my_v[k] > bv && tid + k * kBlock != pick) { bv = my_v[k]; bi = tid + k * kBlock; bpr = my_pr[k]; bu = my_u[k]; }
-            double wv = bv;                            // largest value of the wave
-            wv = fmax(wv, dpp_or_zero<kDppXor1>(wv));
-            wv = fmax(wv, dpp_or_zero<kDppXor2>(wv));
-            wv = fmax(wv, dpp_or_zero<kDppHalfMirror>(wv));
-            wv = fmax(wv, dpp_or_zero<kDppMirror>(wv));
-            wv = fmax(fmax(readlane_f64(wv, 0), readlane_f64(wv, 16)), fmax(readlane_f64(wv, 32), readlane_f64(wv, 48)));
+            const double wv = wave_max_dpp(bv);        // largest value of the wave
             int wl;                                    // (a wave without an open slot: every lane holds -1, any will do)
             const int wi = first_of_equals(wv > 0.0 ? __ballot(bv == wv) : 1ull, bi, &wl);
             const int wpr = __builtin_amdgcn_readlane(bpr, wl);
