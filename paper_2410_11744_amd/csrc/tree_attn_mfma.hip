@@ -125,7 +125,9 @@ template <int D> struct Geo {
 
 // QB = 32-row query blocks per wave.  Every K/V fragment read from LDS feeds QB MFMAs, so
 // QB = 2 halves the LDS traffic per flop: 4 waves, one per SIMD, with up to 512 registers each.
-// QB = 1: 8 waves, two per SIMD, 256 registers each.
+// QB = 1: 8 waves, two per SIMD, 256 registers each.  QB = 1 is what the library is built with:
+// a wave alone on its SIMD does not hide its vector instructions behind its own MFMAs (measured
+// at the 70B shape: 79.5 us per launch with QB = 2 against 71.1 us with QB = 1).
 template <int D, int QB>
 __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnArgs a, SeqArgs sa)
 {
@@ -416,15 +418,16 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                 }
             };
             constexpr int IPS = 16 * QB / NS;                  // items of vector work per slot
-            static_assert(!LD || 2 * LPW <= NS, "one direct load per two slots");
+            constexpr int LEVERY = 2 * LPW <= NS ? 2 : 1;      // a direct load every second slot, or every slot
+            static_assert(!LD || LEVERY * LPW <= NS, "the loads of a step fit its upper half step");
             static_for<(kLead < NS ? kLead : NS)>([&](auto sc) { read_slot(sc); });
             static_for<NS>([&](auto sc) {
                 constexpr int s = decltype(sc)::value;
                 if constexpr (s + kLead < NS) read_slot(std::integral_constant<int, s + kLead>{});
                 mfma_slot(sc);
-                if constexpr (LD && s % 2 == 0 && s / 2 < LPW)
-                    direct_load_16(ld_base + (size_t)(L::kRowsPerLoad * (s / 2)) * kv_row_bytes, (uint32_t)ld_voff[(s / 2) & 3],
-                                   ld_dst + (s / 2) * 1024);
+                if constexpr (LD && s % LEVERY == 0 && s / LEVERY < LPW)
+                    direct_load_16(ld_base + (size_t)(L::kRowsPerLoad * (s / LEVERY)) * kv_row_bytes,
+                                   (uint32_t)ld_voff[(s / LEVERY) & 3], ld_dst + (s / LEVERY) * 1024);
                 if constexpr (HS)
                     static_for<IPS>([&](auto hc) { valu_item(std::integral_constant<int, s * IPS + decltype(hc)::value>{}); });
                 __builtin_amdgcn_sched_barrier(0);
