@@ -29,8 +29,8 @@ PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 # HBM bytes per tree-attention launch from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each
 # scaled by what the same counter reads for a 1 GiB device copy (profiles/bench_*_rocprofv3.md).
-TRAFFIC_BYTES_PER_LAUNCH = {"llama2_70b": 36344499,
-                            "llama2_70b_n32": 26385690 + 9207427}      # split kernel + combine kernel
+TRAFFIC_BYTES_PER_LAUNCH = {"llama2_70b": 36344714,
+                            "llama2_70b_n32": 26385830 + 9207441}      # split kernel + combine kernel
 
 
 def tree_only_sweep(dy, synth, torch, np, dev) -> int:
