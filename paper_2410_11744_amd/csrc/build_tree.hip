@@ -61,10 +61,10 @@ __global__ __launch_bounds__(kBlock) void draft_row_sums_kernel(const float* __r
     for (int w = threadIdx.x; w < kGoneWords; w += kBlock) ws_gone(ws, row)[w] = 0u;
 }
 
+// LDS state of the form without a workspace.
 struct BuildShared {
     double slot_value[kMaxSlots];       // < 0: closed
     int slot_parent[kMaxSlots];
-    float slot_u[kMaxSlots];            // the uniform draw of the slot's sampling (cached form)
     int n_children[DYSPEC_MAX_NODES];
     int last_child[DYSPEC_MAX_NODES];
     int token[DYSPEC_MAX_NODES];
@@ -73,48 +73,41 @@ struct BuildShared {
     int depth[DYSPEC_MAX_NODES];
     uint2 pk[DYSPEC_MAX_NODES];
     CdfScratch cdf;
-    double wave_tot[kWaves];            // per draw (cached form): the waves' sums of the picked segment
-    double w4[4];                       // weights of the four tokens of the thread that owns the crossing
-    double excl;                        // weight in front of those four
-    int owner;                          // the thread that holds the crossing
-    uint2 next_key;                     // path key of the node this draw makes
-    float next_u[2];                    // draws of the two slots it opens
-    int first_hit[kWaves];
-    int last_live[kWaves];
     double best_v[kWaves];
     int best_i[kWaves];
-    int best_pr[kWaves];                // the winning slot's parent | rank << 10 and draw (cached form)
-    float best_u[kWaves];
-    double rest_v;                      // the best open slot outside the current draw (cached form)
-    int rest_i, rest_pr;
-    float rest_u;
-    double draw_wy;                     // the drawn token and its weight
-    int draw_y;
     float fred[kWaves];
     int n_slots;
     int pick;
 };
 
-// Initial state of a sequence's tree: every row unbuilt, the root's slot open.  Ends with a barrier.
-__device__ __forceinline__ void init_tree_state(BuildShared& sh, uint64_t seed, int seq, int base, int N, const dyspec_tree& tree,
-                                                float* __restrict__ est_value, uint64_t* __restrict__ anc_mask, int mask_words)
+// Initial state of a sequence's tree in global memory: every row unbuilt.
+__device__ __forceinline__ void init_tree_rows(int base, int N, const dyspec_tree& tree, float* __restrict__ est_value,
+                                               uint64_t* __restrict__ anc_mask, int mask_words)
 {
-    const int tid = threadIdx.x;
-    for (int i = tid; i < N; i += kBlock) {
-        sh.n_children[i] = 0; sh.last_child[i] = -1; sh.token[i] = -1;
-        sh.first_child[i] = -1; sh.next_sibling[i] = -1; sh.depth[i] = 0;
+    for (int i = threadIdx.x; i < N; i += kBlock) {
         tree.parent[base + i] = -1; tree.token[base + i] = -1; tree.sib_rank[base + i] = 0;
         tree.first_child[base + i] = -1; tree.next_sibling[base + i] = -1; tree.depth[base + i] = 0;
         est_value[base + i] = (i == 0) ? 1.0f : 0.0f;
         for (int w = 0; w < mask_words; ++w)
             anc_mask[(size_t)(base + i) * mask_words + w] = (w == i / 64) ? (1ull << (i % 64)) : 0ull;
     }
+}
+
+// ... and in LDS, with the root's slot open.  Ends with a barrier.
+__device__ __forceinline__ void init_tree_state(BuildShared& sh, int seq, int base, int N, const dyspec_tree& tree,
+                                                float* __restrict__ est_value, uint64_t* __restrict__ anc_mask, int mask_words)
+{
+    const int tid = threadIdx.x;
+    init_tree_rows(base, N, tree, est_value, anc_mask, mask_words);
+    for (int i = tid; i < N; i += kBlock) {
+        sh.n_children[i] = 0; sh.last_child[i] = -1; sh.token[i] = -1;
+        sh.first_child[i] = -1; sh.next_sibling[i] = -1; sh.depth[i] = 0;
+    }
     for (int s = tid; s < kMaxSlots; s += kBlock) sh.slot_value[s] = -1.0;
     __syncthreads();
     if (tid == 0) {
         sh.slot_value[0] = 1.0; sh.slot_parent[0] = 0; sh.n_slots = 1;
         sh.pk[0] = root_key((uint32_t)seq);
-        sh.slot_u[0] = u01(seed, sh.pk[0], 0u, KIND_BUILD);
     }
     __syncthreads();
 }
@@ -147,7 +140,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
     const int base = sa.node_off[seq];
     const int N = sa.node_off[seq + 1] - base;
     const double inv_temp = 1.0 / (double)sa.temp_d[seq];
-    init_tree_state(sh, seed, seq, base, N, tree, est_value, anc_mask, mask_words);
+    init_tree_state(sh, seq, base, N, tree, est_value, anc_mask, mask_words);
 
     int n = 1;
     while (n < N) {
@@ -220,9 +213,9 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
     if (tid == 0) n_built[seq] = n;
 }
 
-// The form with a workspace.  State of a row in LDS (rows below lds_rows; the others stay in the
-// workspace): its kMaxSeg segment totals and its maximum, kRowState doubles that follow each
-// other in the workspace as well.
+// The form with a workspace.  State of a row in LDS: its kMaxSeg segment totals and its maximum,
+// kRowState doubles that follow each other in the workspace as well (the workspace's copy of the
+// totals is not kept current).
 //
 // The open slots live in registers: slot s belongs to thread s % kBlock, which keeps its value,
 // its (parent, rank) and the uniform draw of its sampling.  Every thread knows the slot being
@@ -242,6 +235,28 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
 // if they are its own, and picks the next slot among those two and the best of the rest; single
 // lanes of different waves write the node down.
 constexpr int kRowState = kMaxSeg + 1;
+struct CachedShared {
+    int last_child[DYSPEC_MAX_NODES];
+    int depth[DYSPEC_MAX_NODES];
+    uint2 pk[DYSPEC_MAX_NODES];         // path keys of the nodes
+    double wave_tot[kWaves];            // per draw: the waves' sums of the picked segment
+    int last_live[kWaves];              // last thread of each wave with weight left, -1: none
+    uint2 next_key;                     // path key of the node this draw makes
+    float next_u[2];                    // draws of the two slots it opens
+    double best_v[kWaves];              // per wave: its best open slot outside the current draw,
+    int best_i[kWaves];                 //   the slot's index,
+    int best_pr[kWaves];                //   its parent | rank << 10
+    float best_u[kWaves];               //   and its draw
+    double rest_v;                      // the best of those
+    int rest_i, rest_pr;
+    float rest_u;
+    double draw_wy;                     // the drawn token and its weight
+    int draw_y;
+};
+// LDS a workgroup may use on gfx950, less a margin; what CachedShared leaves of it holds the row states
+constexpr size_t kLdsPerWorkgroup = 160 * 1024 - 1024;
+static_assert(sizeof(CachedShared) + (size_t)DYSPEC_MAX_NODES * kRowState * sizeof(double) <= kLdsPerWorkgroup,
+              "the row states of the largest tree fit in LDS");
 constexpr int kSlotsPerThread = (kMaxSlots + kBlock - 1) / kBlock;
 static_assert(DYSPEC_MAX_NODES <= 1024 && DYSPEC_MAX_VOCAB <= (1 << 21), "a slot's parent and rank share one word");
 
@@ -249,19 +264,23 @@ template <bool VEC>
 __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
     const float* __restrict__ draft_logits, int V, SeqArgs sa, uint64_t seed,
     dyspec_tree tree, float* __restrict__ est_value, uint64_t* __restrict__ anc_mask,
-    int mask_words, int* __restrict__ n_built, double* ws, int lds_rows)
+    int mask_words, int* __restrict__ n_built, double* ws)
 {
-    __shared__ BuildShared sh;
-    extern __shared__ double row_state[];              // [min(N, lds_rows)][kRowState]
+    __shared__ CachedShared sh;
+    extern __shared__ double row_state[];              // [N][kRowState]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seq = blockIdx.x;
     const int base = sa.node_off[seq];
     const int N = sa.node_off[seq + 1] - base;
     const double inv_temp = 1.0 / (double)sa.temp_d[seq];
-    const int n_lds = min(N, lds_rows);
-    for (int x = tid; x < n_lds * kRowState; x += kBlock)
+    for (int x = tid; x < N * kRowState; x += kBlock)
         row_state[x] = ws_totals(ws, base + x / kRowState)[x % kRowState];
-    init_tree_state(sh, seed, seq, base, N, tree, est_value, anc_mask, mask_words);
+    init_tree_rows(base, N, tree, est_value, anc_mask, mask_words);
+    for (int i = tid; i < N; i += kBlock) { sh.last_child[i] = -1; sh.depth[i] = 0; }
+    const uint2 key_root = root_key((uint32_t)seq);
+    const float u_root = u01(seed, key_root, 0u, KIND_BUILD);
+    if (tid == 0) sh.pk[0] = key_root;
+    __syncthreads();
 
     // this thread's slots tid, tid + kBlock, ...: value (< 0: closed), parent | rank << 10, draw
     double my_v[kSlotsPerThread];
@@ -269,7 +288,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
     float my_u[kSlotsPerThread];
 #pragma unroll
     for (int k = 0; k < kSlotsPerThread; ++k) { my_v[k] = -1.0; my_pr[k] = 0; my_u[k] = 0.f; }
-    if (tid == 0) { my_v[0] = 1.0; my_u[0] = sh.slot_u[0]; }        // the root's slot
+    if (tid == 0) { my_v[0] = 1.0; my_u[0] = u_root; }              // the root's slot
     auto set_slot = [&](int s, double v, int pr, float u) {
         if (tid == s % kBlock) {
 #pragma unroll
@@ -281,7 +300,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
     int n = 1, n_slots = 1;
     // the slot to draw from (known to every thread): the root's at first
     int pick = 0, p = 0, rank = 0;
-    double v = 1.0, u = (double)sh.slot_u[0];
+    double v = 1.0, u = (double)u_root;
     while (n < N) {
         // the parent's mask word, needed when the node is appended: on its way during the draw
         const int mtid = tid - 4 * kWave;              // a wave that writes nothing else down
@@ -292,12 +311,10 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         const float* __restrict__ row = draft_logits + (size_t)(base + p) * V;
         // (ws is written by this kernel and not declared restrict or const, so these are
         //  ordinary vector loads and stores; a sum, a bit word or a mask word is only ever re-read
-        //  by the wave that wrote it, totals kept in the workspace are ordered by the barriers)
+        //  by the wave that wrote it)
         double* const S = ws_sums(ws, base + p);
-        double* const T = ws_totals(ws, base + p);
-        const bool in_lds = p < n_lds;
-        const double my_tot = in_lds ? row_state[p * kRowState + (lane & 15)] : T[lane & 15];
-        const double m = in_lds ? row_state[p * kRowState + kMaxSeg] : T[kMaxSeg];
+        const double my_tot = row_state[p * kRowState + (lane & 15)];
+        const double m = row_state[p * kRowState + kMaxSeg];
         const SegPick pk = pick_segment_lanes(my_tot, u);
         const double W = pk.W;
         if (!(W > 0.0)) break;                         // nothing left to sample under p
@@ -420,9 +437,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
                 t += dpp_or_zero<kDppXor1>(t);
                 t += dpp_or_zero<kDppXor2>(t);
                 t += dpp_or_zero<kDppHalfMirror>(t);
-                if (lane == 0) {
-                    if (in_lds) row_state[p * kRowState + pk.js] = t; else T[pk.js] = t;
-                }
+                if (lane == 0) row_state[p * kRowState + pk.js] = t;
             }
         }
         __syncthreads();                               // barrier 2 of 2
@@ -441,11 +456,10 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         const double v0 = v * Ry, v1 = v * (1.0 - Ry);
         set_slot(pick, -1.0, 0, 0.f);
         // ---- the node is written down by single lanes of waves with nothing else to store
-        if (tid == 0) {                                // links in LDS and their copies
-            sh.token[i] = y;
-            if (sh.last_child[p] < 0) { sh.first_child[p] = i; tree.first_child[base + p] = i; }
-            else { sh.next_sibling[sh.last_child[p]] = i; tree.next_sibling[base + sh.last_child[p]] = i; }
-            sh.last_child[p] = i; sh.n_children[p] = rank + 1;
+        if (tid == 0) {                                // links
+            const int prev = sh.last_child[p];
+            if (prev < 0) tree.first_child[base + p] = i; else tree.next_sibling[base + prev] = i;
+            sh.last_child[p] = i;
             sh.pk[i] = sh.next_key;
         }
         if (tid == 3 * kWave) {                        // the node's own row
@@ -477,10 +491,6 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
 
 size_t build_tree_workspace_bytes(int total_rows) { return (size_t)total_rows * kRowSumDoubles * sizeof(double); }
 
-// LDS a workgroup may use on gfx950, less a margin; what BuildShared leaves of it holds row states.
-constexpr size_t kLdsPerWorkgroup = 160 * 1024 - 1024;
-constexpr int kLdsRowsMax = (int)((kLdsPerWorkgroup - sizeof(BuildShared)) / (kRowState * sizeof(double)));
-
 hipError_t launch_build_tree(const float* draft_logits, int V, const SeqArgs& sa, uint64_t seed,
                              const dyspec_tree& tree, float* est_value, uint64_t* anc_mask,
                              int mask_words, int* n_built, void* workspace, size_t workspace_bytes, hipStream_t stream)
@@ -491,8 +501,7 @@ hipError_t launch_build_tree(const float* draft_logits, int V, const SeqArgs& sa
     if (cached) {
         int widest = 0;
         for (int s = 0; s < sa.n_seq; ++s) widest = max(widest, sa.node_off[s + 1] - sa.node_off[s]);
-        const int lds_rows = min(widest, kLdsRowsMax);
-        const size_t dyn_bytes = (size_t)lds_rows * kRowState * sizeof(double);
+        const size_t dyn_bytes = (size_t)widest * kRowState * sizeof(double);
         const void* fn = V % 4 == 0 ? reinterpret_cast<const void*>(&build_tree_cached_kernel<true>)
                                     : reinterpret_cast<const void*>(&build_tree_cached_kernel<false>);
         hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_bytes);
@@ -500,11 +509,11 @@ hipError_t launch_build_tree(const float* draft_logits, int V, const SeqArgs& sa
         if (V % 4 == 0) {
             draft_row_sums_kernel<true><<<rows, kBlock, 0, stream>>>(draft_logits, V, sa, ws);
             build_tree_cached_kernel<true><<<sa.n_seq, kBlock, dyn_bytes, stream>>>(draft_logits, V, sa, seed, tree, est_value,
-                                                                                     anc_mask, mask_words, n_built, ws, lds_rows);
+                                                                                     anc_mask, mask_words, n_built, ws);
         } else {
             draft_row_sums_kernel<false><<<rows, kBlock, 0, stream>>>(draft_logits, V, sa, ws);
             build_tree_cached_kernel<false><<<sa.n_seq, kBlock, dyn_bytes, stream>>>(draft_logits, V, sa, seed, tree, est_value,
-                                                                                      anc_mask, mask_words, n_built, ws, lds_rows);
+                                                                                      anc_mask, mask_words, n_built, ws);
         }
     } else if (V % 4 == 0) {
         build_tree_kernel<true><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
