@@ -103,3 +103,29 @@ def test_threshold_builder_random_shapes(dy, seed):
     for s in range(n_seq):
         a, b = int(batch.node_offset[s]), int(batch.node_offset[s + 1])
         np.testing.assert_array_equal(order[a:b], oracle.dfs_order(par[a:b], fc[a:b], ns[a:b]))
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_builders_large_random_shapes(dy, seed):
+    """Trees of 300 to 1024 rows over large vocabularies: the greedy builder against the oracle and
+    against its own form without a workspace (bit for bit), the threshold builder against the oracle."""
+    rng = np.random.default_rng(77000 + seed)
+    n_seq = int(rng.integers(1, 4))
+    nodes = tuple(int(x) for x in rng.integers(300, 1025, n_seq))
+    V = int(rng.choice([32000, 32768, 5003, 9001]))
+    td = tuple(float(x) for x in rng.choice([0.5, 0.7, 1.0], n_seq))
+    print(f"large builders nodes={nodes} V={V} td={td}", flush=True)
+    d = (rng.standard_normal((sum(nodes), V)) * float(rng.choice([1.0, 2.5, 4.0]))).astype(np.float32)
+    batch = dy.Batch.from_sizes(nodes)
+    dd = torch.from_numpy(d).cuda()
+    built = dy.build_tree(dd, batch, td, seed)
+    torch.cuda.synchronize()
+    assert compare_trees(built, batch, oracle_trees(d, nodes, td, seed)) >= n_seq - 1
+    plain = dy.build_tree(dd, batch, td, seed, use_workspace=False)
+    torch.cuda.synchronize()
+    for k in ("parent", "token", "sib_rank", "first_child", "next_sibling", "depth"):
+        assert torch.equal(getattr(built.tree, k), getattr(plain.tree, k)), k
+    assert torch.equal(built.anc_mask, plain.anc_mask)
+    thr = tuple(float(x) for x in rng.choice([0.02, 0.005, 0.002], n_seq))
+    b2, _ = dy.build_tree_threshold(dd, batch, td, thr, seed)
+    assert compare_threshold_trees(b2, batch, d, td, thr, seed) >= n_seq - 1
