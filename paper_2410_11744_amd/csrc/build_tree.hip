@@ -3,8 +3,8 @@
 //
 // One 512-thread workgroup builds one sequence's tree without leaving the GPU.  The
 // paper keeps the expandable slots in a heap on the host; here the frontier (at most two
-// new slots per node) lives in LDS and the pop is a workgroup arg-max, which costs less
-// than a heap's pointer chasing at these sizes.  A draw needs the parent's residual draft
+// new slots per node) lives in LDS or in registers and the pop is a workgroup arg-max, which
+// costs less than a heap's pointer chasing at these sizes.  A draw needs the parent's residual draft
 // distribution: fp64 softmax weights summed four tokens at a time, a workgroup sum and scan
 // of those sums for the inverse CDF.  fp64 keeps every discrete decision (which slot, which
 // token) equal to an fp64 evaluation of the algorithm except at relative margins near 1e-13.
@@ -14,7 +14,7 @@
 // (build_tree_cached_kernel) keeps them current -- a draw changes the one sum that held the
 // drawn token and the total of its segment.  The rows' segment totals live in LDS, so a draw
 // makes one trip to global memory (each thread fetches its sum, its four logits and its
-// drawn-already bits of the picked segment together) and passes three barriers.  Without a
+// drawn-already bits of the picked segment together) and passes two barriers.  Without a
 // workspace the builder (build_tree_kernel) recomputes the sums of the parent's row for every
 // draw; both ways take the same decisions and build the same tree.
 #include "draft_row.h"
