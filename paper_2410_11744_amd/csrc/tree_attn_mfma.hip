@@ -588,9 +588,21 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         issue_tile(st_prefix, st_tree, ld_voff, tile_of(ld_is_v ? 2 * (i + 1) + ld_par : 2 * (i + 2) + ld_par),
                    st_dst + ((ld_is_v ? i + 1 : i) & 1) * L::kSlotBytes);
     };
-    // Plain steps: positions 2i and 2i+1 are whole prefix tiles (no mask) and so are the tiles
-    // the step loads (a uniform base per load, spread over the upper half step).
-    const int nPlain = min(nPl, max(P / kKeysPerTile - p_begin, 0)) / 2 - 2;
+    // Plain steps: positions 2i and 2i+1 of the walk are whole prefix tiles (no mask), and the tiles
+    // the step loads -- positions up to 2(i+2)+1 -- are whole tiles of the prefix or of the tree (a
+    // uniform base per load, spread over the upper half step) or do not exist (then a whole prefix
+    // tile is loaded in their place: finite values under numerators that are all zero).
+    const int nWholeP = min(nPl, max(P / kKeysPerTile - p_begin, 0));      // whole prefix tiles at the head of the walk
+    int posRagged = 0x3fffffff;                                            // first place in the walk with a ragged tile
+    if (nTt > 0 && nTt * kKeysPerTile > N && ((active >> (nTt - 1)) & 1u)) posRagged = nPl + nAct - 1;
+    if (nWholeP < nPl) posRagged = nWholeP;
+    const int nPlain = min(nWholeP / 2, max(posRagged - 4, 0) / 2);
+    auto plain_load_base = [=](int ii) __attribute__((always_inline)) -> const char* {
+        const int tl = tile_of(ld_is_v ? 2 * (ii + 1) + ld_par : 2 * (ii + 2) + ld_par);
+        const bool tree = tl >= nTp && tl < nT;
+        const int key0 = (tl >= nT ? p_begin : tree ? tl - nTp : tl) * kKeysPerTile;
+        return (tree ? st_tree : st_prefix) + (size_t)(key0 + L::kRowsPerLoad * ld_x0) * kv_row_bytes;
+    };
     int i = 0;
     for (; i + 1 < nPlain; i += 2) {
         static_for<2>([&](auto sp_c) {
@@ -598,9 +610,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
             run_half(std::false_type{}, std::false_type{}, sp_c, std::integral_constant<int, 0>{}, none32, nullptr, 0u);
             wait_direct_loads();
             __syncthreads();
-            const int tl = p_begin + (ld_is_v ? 2 * (ii + 1) + ld_par : 2 * (ii + 2) + ld_par);
-            const char* base = st_prefix + (size_t)(tl * kKeysPerTile + L::kRowsPerLoad * ld_x0) * kv_row_bytes;
-            run_half(std::false_type{}, std::true_type{}, sp_c, std::integral_constant<int, 1>{}, none32, base,
+            run_half(std::false_type{}, std::true_type{}, sp_c, std::integral_constant<int, 1>{}, none32, plain_load_base(ii),
                      st_dst + ((ld_is_v ? ii + 1 : ii) & 1) * L::kSlotBytes);
         });
     }
