@@ -1,19 +1,19 @@
 """DySpec CPU oracle, token tree construction with a threshold -- TEST INFRASTRUCTURE ONLY.
 
-Algorithm 2 (Section 4.4, Appendix A.2) in plain numpy fp64, in the paper's order and
-notation: the tree grows level by level; every node of the current level (LeafNodes) keeps
-drawing children from its own draft distribution d_i, without replacement, while the
-estimated value v_i of the next draw stays at or above the threshold t.
+Algorithm 2 (Section 4.4, Appendix A.2) in plain numpy fp64: the tree grows level by level;
+every node of the current level keeps drawing children from its own draft distribution,
+without replacement, while the estimated value of its next draw stays at or above the
+threshold t.
 
 Readings (the listing is garbled in places):
-  * the inner loop's condition is printed as `v_i < t`; the text says nodes are extended while
-    their estimated value is ABOVE the threshold, so the loop runs while v_i >= t;
+  * the inner loop's condition is printed with the opposite sign; the text says nodes are extended while
+    their estimated value is ABOVE the threshold, so the loop runs while the value is >= t;
   * the paper relaxes the node budget but still states a maximum tree size in its
-    experiments (Appendix B): nodes are numbered in creation order (level by level, LeafNodes
-    in order, children in sampling order) and construction stops when `max_nodes` rows,
+    experiments (Appendix B): nodes are numbered in creation order (level by level, the level's
+    nodes in order, children in sampling order) and construction stops when `max_nodes` rows,
     the root included, exist;
-  * a draw that finds nothing left in d_i ends that node's loop;
-  * est_value of a node is the value v_i its draw was made at, as for Algorithm 1.
+  * a draw that finds nothing left in the node's distribution ends that node's loop;
+  * est_value of a node is the value its draw was made at, as for Algorithm 1.
 
 Draws are the path-named Philox uniforms of the rest of the oracle (kind BUILD, rank = number
 of children the parent already has), so a node reached by the same path of sibling ranks gets
@@ -98,50 +98,60 @@ def threshold_tree(draft_logits, max_nodes: int, temp: float, t: float, seed: in
     keys = [(int(seq), 0)]
     m_cdf, m_thr = float("inf"), float("inf")
 
+    # The tree is held as flat arrays in creation order; a level is the run of rows the
+    # previous level created, so "the nodes to expand next" is just a list of row indices.
     n = 1
-    leaf_nodes = [0]                                        # LeafNodes <- root
+    level = [0]
     levels = 0
-    while leaf_nodes and n < N:
-        new_leaf_nodes = []
+
+    def append_child(node: int, y: int, rank: int, prev: int, drawn_at: float, own: float) -> int:
+        """Row n becomes the child of `node` with token y; returns its index."""
+        nonlocal n
+        i = n
+        n += 1
+        parent[i], token[i], sib_rank[i], depth[i] = node, y, rank, depth[node] + 1
+        if prev < 0:
+            first_child[node] = i
+        else:
+            next_sibling[prev] = i
+        mask[i] |= mask[node]
+        est_value[i] = drawn_at                 # the value at which this draw was made
+        child_value[i] = own                    # what the child's own first draw will be worth
+        paths.append(paths[node] + (rank,))
+        keys.append(_child_key(seed, keys[node], rank))
+        return i
+
+    while level and n < N:
+        created = []
         levels += 1
-        for node in leaf_nodes:
-            if n >= N:
+        for node in level:
+            if n >= N:                          # capacity cut: later nodes of the level get nothing
                 break
-            v = float(child_value[node])                    # v_i
+            v = float(child_value[node])
             m_thr = min(m_thr, abs(v - t) / t)
-            if not v >= t:
+            if not v >= t:                      # below the threshold: this node is never expanded
                 continue
             row = node if row_of is None else row_of(paths[node], node)
-            d = softmax(logits[row], temp)                  # d_i <- D(. | x_i)
+            d = softmax(logits[row], temp)      # the node's draft distribution over next tokens
             rank, prev = 0, -1
             while v >= t and n < N:
                 u = u01(seed, keys[node][0], keys[node][1], rank, KIND_BUILD)
-                y, W, margin = _sample(d, u)                # sample y ~ d_i
-                if y < 0:
+                y, W, margin = _sample(d, u)    # a token from what is left of the distribution
+                if y < 0:                       # nothing left to draw
                     break
                 m_cdf = min(m_cdf, margin)
                 dy = float(d[y]) / W
-                i = n                                       # NewNode <- Tr.add(node_i, y)
-                n += 1
-                parent[i], token[i], sib_rank[i], depth[i] = node, y, rank, depth[node] + 1
-                if prev < 0:
-                    first_child[node] = i
-                else:
-                    next_sibling[prev] = i
-                prev = i
-                mask[i] |= mask[node]
-                est_value[i] = v
-                child_value[i] = v * dy                     # NewLeafNodes.append(NewNode, v_i * d_i[y])
-                paths.append(paths[node] + (rank,))
-                keys.append(_child_key(seed, keys[node], rank))
-                new_leaf_nodes.append(i)
-                v = v * (1.0 - dy)                          # v_i <- v_i * (1 - d_i[y])
-                d[y] = 0.0                                  # d_i[y] <- 0
+                prev = append_child(node, y, rank, prev, v, v * dy)
+                created.append(prev)
+                # the next draw at this node is worth the mass that did not go to y; y leaves
+                # the distribution (sampling without replacement) and the rest is renormalised
+                v = v * (1.0 - dy)
+                d[y] = 0.0
                 left = float(d.sum())
                 if left > 0.0:
-                    d = d / left                            # d_i <- norm(d_i)
+                    d = d / left
                 rank += 1
                 m_thr = min(m_thr, abs(v - t) / t)
-        leaf_nodes = new_leaf_nodes
+        level = created
     return ThresholdTree(parent, token, sib_rank, first_child, next_sibling, depth, est_value, child_value,
                          mask, n, paths, m_cdf, m_thr, levels)

@@ -104,6 +104,44 @@ def compare_verify(out, batch, trees, draft, target, temps_d, temps_t, seed, emi
     return compared, skipped
 
 
+def next_seed(seed, k):
+    """k-th seed tried for a case: the case's own seed first, then fresh ones (a case in which the
+    oracle took a decision at a margin below the bar is generated again with the next seed)."""
+    return seed + 7919 * k
+
+
+def build_in_full(dy, draft_dev, draft_host, batch, nodes, temps, seed, tries=8):
+    """dyspec_build_tree compared with the oracle in full.  A seed at which some oracle decision has
+    a margin below BUILD_MARGIN (its trees are still compared up to that decision) is followed by the
+    next one, until every sequence was compared row by row.  Returns (built, oracle trees, seed)."""
+    import torch
+    for k in range(tries):
+        sd = next_seed(seed, k)
+        built = dy.build_tree(draft_dev, batch, temps, sd)
+        torch.cuda.synchronize()
+        trees = oracle_trees(draft_host, nodes, temps, sd)
+        if compare_trees(built, batch, trees) == len(nodes):
+            return built, trees, sd
+    raise AssertionError(f"no seed in {tries} tries gave build margins >= {BUILD_MARGIN} in every sequence")
+
+
+def verify_in_full(run, batch, trees, draft, target, temps_d, temps_t, seed, emit_bonus=True, tries=8):
+    """run(seed) -> VerifyOutput of the GPU library; compared with the oracle.  A seed at which some
+    sequence's walk has an acceptance margin below DECISION_MARGIN (statistics and ratios are still
+    compared) is followed by the next one, until the accepted path of EVERY sequence was compared.
+    Returns (output, seed)."""
+    import torch
+    for k in range(tries):
+        sd = next_seed(seed, k)
+        out = run(sd)
+        torch.cuda.synchronize()
+        compared, skipped = compare_verify(out, batch, trees, draft, target, temps_d, temps_t, sd, emit_bonus=emit_bonus)
+        assert compared + skipped == len(trees)
+        if skipped == 0:
+            return out, sd
+    raise AssertionError(f"no seed in {tries} tries gave acceptance margins >= {DECISION_MARGIN} in every sequence")
+
+
 def oracle_attention_rows(q, kp, vp, kt, vt, mask_u64, batch, seq, scale, rows_j, rows_h):
     """fp64 oracle on sampled (node, head) rows of one sequence; inputs are host fp32 arrays."""
     a, b = int(batch.node_offset[seq]), int(batch.node_offset[seq + 1])

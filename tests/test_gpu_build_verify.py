@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import compare_trees, compare_verify, oracle_trees
+from helpers import build_in_full, compare_trees, compare_verify, oracle_trees, verify_in_full
 
 pytestmark = pytest.mark.gpu
 
@@ -50,12 +50,9 @@ def test_build_and_verify_match_oracle(dy, nodes, V, sigma, tsigma, temps, seed)
     trees = oracle_trees(d, nodes, temps, seed)
     full = compare_trees(built, batch, trees)
     assert full == len(nodes), "an oracle decision had a margin below 1e-9: pick another seed"
-    for bonus in (True, False):
-        out = dy.verify(dd, tt, batch, built.tree, temps, temps, seed, emit_bonus=bonus)
-        torch.cuda.synchronize()
-        compared, skipped = compare_verify(out, batch, trees, d, t, temps, temps, seed, emit_bonus=bonus)
-        assert compared + skipped == len(nodes)
-        assert compared >= 1
+    for bonus in (True, False):          # a seed with a small acceptance margin somewhere is followed by the next
+        verify_in_full(lambda sd: dy.verify(dd, tt, batch, built.tree, temps, temps, sd, emit_bonus=bonus),
+                       batch, trees, d, t, temps, temps, seed, emit_bonus=bonus)
 
 
 @pytest.mark.parametrize("nodes,V,sigma,tsigma,temps,seed", [CASES[2], CASES[3], CASES[6]])
@@ -127,10 +124,12 @@ def test_verify_hand_built_edge_cases(dy):
         batch = dy.Batch.from_sizes([n])
         tree, otree = _hand_tree(dy, token, parent)
         dd, tt = torch.from_numpy(d).cuda(), torch.from_numpy(t).cuda()
+        paths = 0
         for seed in range(6):
             out = dy.verify(dd, tt, batch, tree, (1.0,), (1.0,), seed)
             torch.cuda.synchronize()
-            compare_verify(out, batch, [otree], d, t, (1.0,), (1.0,), seed)
+            paths += compare_verify(out, batch, [otree], d, t, (1.0,), (1.0,), seed)[0]
+        assert paths >= 5                 # at most one seed lands within 1e-5 of an acceptance ratio
     # first case: the second child must carry the "not tried" marker
     d, t, token, parent = cases[0]
     tree, _ = _hand_tree(dy, token, parent)
@@ -167,8 +166,7 @@ def test_maximum_sizes_and_widest_batch(dy):
     trees = oracle_trees(d, nodes, (0.7,), 11)
     print(f"  oracle build {time.time() - t0:.1f} s", flush=True)
     assert compare_trees(built, batch, trees) == 1
-    out = dy.verify(dd, tt, batch, built.tree, (0.7,), (0.9,), 11)
-    compare_verify(out, batch, trees, d, t, (0.7,), (0.9,), 11)
+    verify_in_full(lambda sd: dy.verify(dd, tt, batch, built.tree, (0.7,), (0.9,), sd), batch, trees, d, t, (0.7,), (0.9,), 11)
 
     rng = np.random.default_rng(64)
     nodes = tuple(int(x) for x in rng.integers(1, 20, 64))
@@ -177,10 +175,5 @@ def test_maximum_sizes_and_widest_batch(dy):
     temps = tuple(float(x) for x in rng.choice([0.6, 0.8, 1.0], 64))
     d, t = logits(sum(nodes), 500, 2.0, 1.0, 4243)
     dd, tt = torch.from_numpy(d).cuda(), torch.from_numpy(t).cuda()
-    built = dy.build_tree(dd, batch, temps, 12)
-    torch.cuda.synchronize()
-    trees = oracle_trees(d, nodes, temps, 12)
-    assert compare_trees(built, batch, trees) >= 62
-    out = dy.verify(dd, tt, batch, built.tree, temps, temps, 12)
-    compared, skipped = compare_verify(out, batch, trees, d, t, temps, temps, 12)
-    assert compared + skipped == 64 and compared >= 60
+    built, trees, _ = build_in_full(dy, dd, d, batch, nodes, temps, 12)
+    verify_in_full(lambda sd: dy.verify(dd, tt, batch, built.tree, temps, temps, sd), batch, trees, d, t, temps, temps, 12)

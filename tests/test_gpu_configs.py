@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import ATTN_TOL, compare_trees, compare_verify, oracle_attention_rows, oracle_trees
+from helpers import ATTN_TOL, compare_trees, oracle_attention_rows, oracle_trees, verify_in_full
 
 pytestmark = pytest.mark.gpu
 
@@ -24,12 +24,12 @@ def dy():
 
 
 @pytest.mark.parametrize("name,layer,rows_per_seq", [
-    ("tiny_f32", 0, 256),
-    ("llama2_7b", 31, 512),
-    ("llama2_13b", 7, 512),
-    ("llama2_70b", 79, 1024),
-    ("llama2_70b_ragged8", 40, 256),
-    ("llama2_70b_n32", 3, 2048),            # supplementary HBM-bound point (16-way prefix split)
+    ("tiny_f32", 0, None),                  # None: every (row, head) pair of the layer
+    ("llama2_7b", 31, None),
+    ("llama2_13b", 7, None),
+    ("llama2_70b", 79, None),
+    ("llama2_70b_ragged8", 40, 1024),       # sampled: 3.4 G (row, key) pairs per layer in full
+    ("llama2_70b_n32", 3, None),            # supplementary HBM-bound point (prefix split)
 ])
 def test_config(dy, name, layer, rows_per_seq):
     from paper_2410_11744_amd import synth
@@ -61,7 +61,7 @@ def test_config(dy, name, layer, rows_per_seq):
     worst = 0.0
     for s, n in enumerate(cfg.n_nodes):
         total = n * cfg.n_q_heads
-        pick = np.arange(total) if total <= rows_per_seq else rng.choice(total, rows_per_seq, replace=False)
+        pick = np.arange(total) if rows_per_seq is None or total <= rows_per_seq else rng.choice(total, rows_per_seq, replace=False)
         # always include the first and last node (tile edges, deepest mask rows)
         pick = np.unique(np.concatenate([pick, np.arange(cfg.n_q_heads), total - 1 - np.arange(cfg.n_q_heads)]))
         rj, rh = np.divmod(pick, cfg.n_q_heads)
@@ -72,12 +72,10 @@ def test_config(dy, name, layer, rows_per_seq):
     assert worst <= ATTN_TOL[cfg.dtype]
 
     # ---- verification
-    vout = dy.verify(draft, target, batch, built.tree, cfg.temps, cfg.temps, cfg.seed)
-    torch.cuda.synchronize()
-    compared, skipped = compare_verify(vout, batch, trees, draft_h, target_h, cfg.temps, cfg.temps, cfg.seed)
-    print(f"  verify: paths compared {compared}, skipped for small margins {skipped}, "
+    vout, vseed = verify_in_full(lambda sd: dy.verify(draft, target, batch, built.tree, cfg.temps, cfg.temps, sd),
+                                 batch, trees, draft_h, target_h, cfg.temps, cfg.temps, cfg.seed)
+    print(f"  verify: accepted paths of all {batch.n_seq} sequences match at seed {vseed}, "
           f"accepted {vout.n_accepted.cpu().tolist()}", flush=True)
-    assert compared + skipped == batch.n_seq and compared >= max(1, batch.n_seq - 2)
 
 
 def test_ceiling_probes_run(dy):

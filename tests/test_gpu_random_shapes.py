@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import compare_trees, compare_verify, oracle_trees
+from helpers import build_in_full, next_seed, verify_in_full
 from test_gpu_tree_attn import run_and_compare
 from test_gpu_tree_attn_layers import check_layers, stacked_case
 from test_gpu_threshold import compare_threshold_trees
@@ -23,6 +23,18 @@ def dy():
     import paper_2410_11744_amd as m
     m.load_library()
     return m
+
+
+def threshold_in_full(dy, draft_dev, draft_host, batch, temps, thr, seed, tries=8):
+    """dyspec_build_tree_threshold against the oracle; a seed at which the oracle took a decision at a
+    margin below the bar is followed by the next one until every sequence was compared row by row."""
+    for k in range(tries):
+        sd = next_seed(seed, k)
+        built, _ = dy.build_tree_threshold(draft_dev, batch, temps, thr, sd)
+        torch.cuda.synchronize()
+        if compare_threshold_trees(built, batch, draft_host, temps, thr, sd) == batch.n_seq:
+            return built
+    raise AssertionError("no seed gave threshold-builder margins above the bar in every sequence")
 
 
 HEADS = [(8, 8), (8, 2), (4, 1), (6, 2), (16, 4), (12, 12), (5, 5)]
@@ -61,24 +73,22 @@ def test_build_and_verify_random_shapes(dy, seed):
     d = (rng.standard_normal((sum(nodes), V)) * sigma).astype(np.float32)
     t = (d + rng.standard_normal((sum(nodes), V)) * tsigma).astype(np.float32)
     bf16 = seed % 3 == 2
-    if bf16:                                            # bf16 tables for verification: everyone reads the rounded values
-        d = torch.from_numpy(d).to(torch.bfloat16).float().numpy()
-        t = torch.from_numpy(t).to(torch.bfloat16).float().numpy()
     batch = dy.Batch.from_sizes(nodes)
     dd, tg = torch.from_numpy(d).cuda(), torch.from_numpy(t).cuda()
-    built = dy.build_tree(dd, batch, td, seed)
-    torch.cuda.synchronize()
-    full = compare_trees(built, batch, oracle_trees(d, nodes, td, seed))
-    assert full >= n_seq - (2 if bf16 else 1)           # sequences with a margin below 1e-9 are not compared
+    # the builder reads the fp32 table (values rounded to bf16 tie often, and a tie between two open
+    # positions is a decision of margin 0); verification below reads the rounded tables
+    built, _, _ = build_in_full(dy, dd, d, batch, nodes, td, seed)
     g = {k: getattr(built.tree, k).cpu().numpy() for k in ("token", "first_child", "next_sibling")}
     trees = [tuple(g[k][int(batch.node_offset[s]):int(batch.node_offset[s + 1])] for k in ("token", "first_child", "next_sibling"))
              for s in range(n_seq)]
-    vd, vt = (dd.to(torch.bfloat16), tg.to(torch.bfloat16)) if bf16 else (dd, tg)
+    if bf16:                                            # bf16 tables for verification: both sides read the rounded values
+        vd, vt = dd.to(torch.bfloat16), tg.to(torch.bfloat16)
+        d, t = vd.float().cpu().numpy(), vt.float().cpu().numpy()
+    else:
+        vd, vt = dd, tg
     for bonus in (True, False):
-        out = dy.verify(vd, vt, batch, built.tree, td, tt, 77 + seed, emit_bonus=bonus)
-        torch.cuda.synchronize()
-        compared, skipped = compare_verify(out, batch, trees, d, t, td, tt, 77 + seed, emit_bonus=bonus)
-        assert compared + skipped == n_seq and compared >= n_seq - 2     # small-margin sequences are skipped
+        verify_in_full(lambda sd: dy.verify(vd, vt, batch, built.tree, td, tt, sd, emit_bonus=bonus),
+                       batch, trees, d, t, td, tt, 77 + seed, emit_bonus=bonus)
 
 
 @pytest.mark.parametrize("seed", range(8))
@@ -92,8 +102,7 @@ def test_threshold_builder_random_shapes(dy, seed):
     print(f"random threshold nodes={nodes} V={V} t={thr}", flush=True)
     d = (rng.standard_normal((sum(nodes), V)) * float(rng.choice([2.0, 4.0]))).astype(np.float32)
     batch = dy.Batch.from_sizes(nodes)
-    built, levels = dy.build_tree_threshold(torch.from_numpy(d).cuda(), batch, temps, thr, seed)
-    assert compare_threshold_trees(built, batch, d, temps, thr, seed) >= n_seq - 1
+    built = threshold_in_full(dy, torch.from_numpy(d).cuda(), d, batch, temps, thr, seed)
     # and a depth-first renaming of whatever was built keeps verification's outcome
     re = dy.dfs_reorder(built.tree, batch)
     torch.cuda.synchronize()
@@ -118,14 +127,11 @@ def test_builders_large_random_shapes(dy, seed):
     d = (rng.standard_normal((sum(nodes), V)) * float(rng.choice([1.0, 2.5, 4.0]))).astype(np.float32)
     batch = dy.Batch.from_sizes(nodes)
     dd = torch.from_numpy(d).cuda()
-    built = dy.build_tree(dd, batch, td, seed)
-    torch.cuda.synchronize()
-    assert compare_trees(built, batch, oracle_trees(d, nodes, td, seed)) >= n_seq - 1
+    built, _, seed = build_in_full(dy, dd, d, batch, nodes, td, seed)
     plain = dy.build_tree(dd, batch, td, seed, use_workspace=False)
     torch.cuda.synchronize()
     for k in ("parent", "token", "sib_rank", "first_child", "next_sibling", "depth"):
         assert torch.equal(getattr(built.tree, k), getattr(plain.tree, k)), k
     assert torch.equal(built.anc_mask, plain.anc_mask)
     thr = tuple(float(x) for x in rng.choice([0.02, 0.005, 0.002], n_seq))
-    b2, _ = dy.build_tree_threshold(dd, batch, td, thr, seed)
-    assert compare_threshold_trees(b2, batch, d, td, thr, seed) >= n_seq - 1
+    threshold_in_full(dy, dd, d, batch, td, thr, seed)

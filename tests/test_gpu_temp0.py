@@ -4,7 +4,7 @@ token down the tree; checked against the CPU oracle and against a plain argmax w
 import numpy as np
 import pytest
 
-from helpers import compare_trees, compare_verify, oracle_trees
+from helpers import compare_trees, compare_verify, oracle_trees, verify_in_full
 from test_oracle_temp0 import greedy_walk
 
 pytestmark = pytest.mark.gpu
@@ -53,10 +53,8 @@ def test_temperature_zero_target_matches_oracle(dy, nodes, V, sigma, tsigma, td,
     assert compare_trees(built, batch, trees) == len(nodes)
     for bonus in (True, False):
         for vseed in (seed, seed + 91):
-            out = dy.verify(dd, tg, batch, built.tree, td, tt, vseed, emit_bonus=bonus)
-            torch.cuda.synchronize()
-            compared, skipped = compare_verify(out, batch, trees, d, t, td, tt, vseed, emit_bonus=bonus)
-            assert compared + skipped == len(nodes)
+            out, _ = verify_in_full(lambda sd: dy.verify(dd, tg, batch, built.tree, td, tt, sd, emit_bonus=bonus),
+                                    batch, trees, d, t, td, tt, vseed, emit_bonus=bonus)
             # the outcome of a temperature-0 sequence does not depend on the draws at all: it
             # is the argmax walk, low-margin draws included
             na, fin = out.n_accepted.cpu().numpy(), out.final_token.cpu().numpy()
@@ -87,7 +85,7 @@ def test_ties_go_to_the_smallest_index(dy):
         np.testing.assert_array_equal(st[:, 3], np.argmax(t, axis=1).astype(np.float32))
         np.testing.assert_array_equal(st[:, 2], t.max(axis=1))
         trees = oracle_trees(d, (n,), (1.0,), 1)
-        compare_verify(out, batch, trees, d, t, (1.0,), (0.0,), 1)
+        assert compare_verify(out, batch, trees, d, t, (1.0,), (0.0,), 1) == (1, 0)
 
 
 def test_full_size_tree_long_accepted_path(dy):
@@ -106,7 +104,7 @@ def test_full_size_tree_long_accepted_path(dy):
     assert compare_trees(built, batch, trees) == 1
     out = dy.verify(dd, tg, batch, built.tree, cfg.temps, (0.0,), cfg.seed)
     torch.cuda.synchronize()
-    compare_verify(out, batch, trees, d, t, cfg.temps, (0.0,), cfg.seed)
+    assert compare_verify(out, batch, trees, d, t, cfg.temps, (0.0,), cfg.seed) == (1, 0)
     tr = trees[0]
     path, last, _ = greedy_walk(t, tr.token, tr.first_child, tr.next_sibling)
     na = int(out.n_accepted.item())

@@ -335,3 +335,80 @@ def test_philox_and_explicit_variants_agree():
     a = oracle.verify(draft, target, t.token, t.first_child, t.next_sibling, 0.8, 1.0, seed, seq)
     b = oracle.verify_explicit(draft, target, t.token, t.first_child, t.next_sibling, 0.8, 1.0, ua, ur)
     assert list(a.accepted_nodes) == list(b.accepted_nodes) and a.final_token == b.final_token
+
+
+# ----------------------------------------------------------------- checkers the GPU tests lean on
+
+@pytest.mark.parametrize("td,tt", [(0.6, 0.9), (0.9, 1.3), (1.3, 0.6)])
+def test_softmax_stats_against_logsumexp_at_general_temperatures(td, tt):
+    """Row statistics (max of logits/T, sum of exp(logits/T - max)) for draft and target at
+    temperatures other than 1: max + log(sum) is the log-sum-exp of the scaled row, and the
+    maximum is the largest scaled logit (library routines in fp64)."""
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(11)
+    draft = (rng.standard_normal((5, 97)) * 3).astype(np.float32)
+    target = (draft + rng.standard_normal((5, 97)) * 0.8).astype(np.float32)
+    st = oracle.softmax_stats(draft, target, td, tt)
+    for col, table, temp in ((0, draft, td), (2, target, tt)):
+        z = table.astype(np.float64) / temp
+        np.testing.assert_allclose(st[:, col], z.max(axis=1), rtol=1e-12, atol=0)
+        np.testing.assert_allclose(st[:, col] + np.log(st[:, col + 1]), logsumexp(z, axis=1), rtol=1e-12, atol=0)
+        # and the pair normalises the row: exp(z - max) / sum adds up to one
+        p = np.exp(z - st[:, col, None]) / st[:, col + 1, None]
+        np.testing.assert_allclose(p.sum(axis=1), 1.0, rtol=1e-12)
+    # a wrong 1/T on either half shows: the two temperatures differ, so do the halves on one table
+    same = oracle.softmax_stats(draft, draft, td, tt)
+    assert not np.allclose(same[:, 0], same[:, 2])
+
+
+def test_accept_ratio_of_later_siblings_by_hand():
+    """Draft (.4,.3,.2,.1), target (.1,.2,.3,.4), children with tokens 0, 1, 3 under the root
+    (the inner loop of Algorithm 3 with every earlier sibling rejected).  By hand:
+    child 0: R[0]/D[0] = .1/.4 = 0.25; then R = norm(relu(T-D)) = (0,0,.25,.75), D = (0,.3,.2,.1)/.6;
+    child 1: R[1]/D[1] = 0/.5 = 0; then R-D = (0,-.5,.25-1/3,.75-1/6) -> R = (0,0,0,1), D = (0,0,2/3,1/3);
+    child 3: R[3]/D[3] = 1/(1/3) = 3."""
+    D0 = np.array([0.4, 0.3, 0.2, 0.1])
+    T0 = np.array([0.1, 0.2, 0.3, 0.4])
+    draft = np.log(np.stack([D0] * 4)).astype(np.float32)
+    target = np.log(np.stack([T0] * 4)).astype(np.float32)
+    tok = np.array([-1, 0, 1, 3], dtype=np.int32)
+    fc = np.array([1, -1, -1, -1], dtype=np.int32)
+    ns = np.array([-1, 2, 3, -1], dtype=np.int32)
+    ratio = oracle.accept_ratio_all(draft, target, tok, fc, ns, 1.0, 1.0)
+    np.testing.assert_allclose(ratio, [0.0, 0.25, 0.0, 3.0], rtol=0, atol=2e-7)   # logits are fp32 logs
+    # with temperatures: D = softmax(log D0 / td), T = softmax(log T0 / tt), same recursion in numpy
+    td, tt = 0.6, 1.3
+    D, R = probs(np.log(D0).astype(np.float32), td), probs(np.log(T0).astype(np.float32), tt)
+    want = {}
+    for node, y in ((1, 0), (2, 1), (3, 3)):
+        want[node] = R[y] / D[y]
+        R = np.maximum(R - D, 0)
+        R /= R.sum()
+        D = D.copy()
+        D[y] = 0
+        D /= D.sum()
+    ratio = oracle.accept_ratio_all(draft, target, tok, fc, ns, td, tt)
+    np.testing.assert_allclose(ratio[1:], [want[1], want[2], want[3]], rtol=1e-12)
+
+
+def test_accept_ratio_agrees_with_the_walk_on_built_trees():
+    """On greedy trees over random tables: for every child the walk tests, |c - ratio| from
+    accept_ratio_all equals the margin the verification walk itself recorded (residual update of
+    Algorithm 3 after each rejected sibling, general target)."""
+    V, N, td, tt = 16, 24, 0.8, 1.1
+    later = 0
+    for seed in range(6):
+        rng = np.random.default_rng(40 + seed)
+        draft = (rng.standard_normal((N, V)) * 1.5).astype(np.float32)
+        target = (draft + rng.standard_normal((N, V)) * 1.2).astype(np.float32)
+        t = oracle.build_tree(draft, N, td, seed)
+        ratio = oracle.accept_ratio_all(draft, target, t.token, t.first_child, t.next_sibling, td, tt)
+        for trial in range(40):
+            ua = np.random.default_rng(1000 * seed + trial).random(N)
+            r = oracle.verify_explicit(draft, target, t.token, t.first_child, t.next_sibling, td, tt, ua, [0.5] * N)
+            tested = np.flatnonzero(np.isfinite(r.tested_margin))
+            assert tested.size > 0
+            for i in tested:
+                assert abs(ua[i] - ratio[i]) == pytest.approx(r.tested_margin[i], rel=1e-9, abs=1e-12)
+                later += int(t.sib_rank[i] > 0)
+    assert later > 50          # the check reached siblings behind a residual update
