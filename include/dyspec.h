@@ -12,6 +12,9 @@
  *    race unless ordered by the stream.
  *  - Errors are return codes (< 0).  Arguments are validated on the host before anything
  *    is launched; a call that returns an error has launched nothing.
+ *  - Alignment of DEVICE pointers is part of that validation (DYSPEC_BAD_ARG otherwise):
+ *    attention tensors, logit tables, row_stats and the tree-attention workspace 16 bytes;
+ *    ancestor masks and the builders' workspaces 8 bytes; every other array 4 bytes.
  *  - A batch holds n_seq independent sequences packed back to back.  Sequence s owns tree
  *    rows [node_offset[s], node_offset[s+1]) of every per-node array and prefix rows
  *    [kv_offset[s], kv_offset[s] + prefix_len[s]) of k_prefix / v_prefix.  Row 0 of each
@@ -97,7 +100,7 @@ const char* dyspec_status_string(dyspec_status s);
  * y is the smallest index whose cumulative residual weight exceeds u * (total weight),
  * u in [0,1) with 24 random bits.
  *
- *   draft_logits  DEVICE [sum N, vocab] fp32, row-major
+ *   draft_logits  DEVICE [sum N, vocab] fp32, row-major, base 16-byte aligned
  *   draft_temp    HOST   [n_seq] > 0
  *   tree          DEVICE outputs (all six arrays)
  *   est_value     DEVICE [sum N] fp32: v of the slot each node was drawn from (root: 1)
@@ -187,16 +190,21 @@ dyspec_status dyspec_dfs_reorder(const dyspec_batch* batch, const dyspec_tree* t
  *   q, out            DEVICE [sum N, n_q_heads, head_dim]
  *   k_prefix,v_prefix DEVICE [kv rows, n_kv_heads, head_dim]
  *   k_tree, v_tree    DEVICE [sum N, n_kv_heads, head_dim]
- *   anc_mask          DEVICE [sum N, mask_words] as written by dyspec_build_tree
+ *   anc_mask          DEVICE [sum N, mask_words] as written by dyspec_build_tree.  Bit i of row j
+ *                     may be set only for i <= j (an ancestor is created before its descendants,
+ *                     so its row index is smaller, in creation order and in depth-first order
+ *                     alike); the matrix-core path does not look at tree keys past the largest
+ *                     row of a tile, so bits above the diagonal are ignored there
  *   dtype             DYSPEC_F32 (any head_dim <= 256, multiple of 4) or DYSPEC_BF16
  *                     (head_dim 64 or 128; matrix-core path, fp32 accumulation)
- * All tensors are dense row-major and 16-byte aligned.
+ * All tensors are dense row-major and 16-byte aligned (checked: DYSPEC_BAD_ARG).
  *   workspace         DEVICE, 16-byte aligned, dyspec_workspace_bytes(DYSPEC_WS_TREE_ATTN, ...)
  *                     bytes, contents overwritten.  Non-zero only for batches whose (row
  *                     tiles) x (KV heads) leave most of the chip idle: the bf16 path then
  *                     splits every prefix over several workgroups, which leave partial
  *                     (max, sum, rows) there for a second, combining kernel.  NULL or fewer
- *                     bytes: no split (same result up to fp32 rounding of the combine).
+ *                     bytes: no split (same result up to fp32 rounding of the combine).  A
+ *                     non-NULL workspace that is not 16-byte aligned is DYSPEC_BAD_ARG.
  */
 dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* v_prefix,
                                const void* k_tree, const void* v_tree,
@@ -252,7 +260,8 @@ size_t dyspec_tree_attn_layers_workspace_bytes(const dyspec_batch* batch, int32_
  * winning a tie, so the walk follows the target's argmax token down the tree and the last
  * token is the argmax of the row where it stops; the draws are still taken, in the same order.
  *
- *   draft_logits, target_logits DEVICE [sum N, vocab] fp32 (row i = distribution after node i)
+ *   draft_logits, target_logits DEVICE [sum N, vocab] fp32 (row i = distribution after node i),
+ *                               rows dense, base pointers 16-byte aligned
  *   draft_temp                  HOST [n_seq] > 0
  *   target_temp                 HOST [n_seq] >= 0, independent of draft_temp
  *   tree                        DEVICE inputs (token, first_child, next_sibling are read)
@@ -264,6 +273,7 @@ size_t dyspec_tree_attn_layers_workspace_bytes(const dyspec_batch* batch, int32_
  *                  local node indices in order (root excluded); n_accepted [n_seq]
  *   final_token  DEVICE [n_seq]: token emitted where the walk stopped (-1 if none)
  *   min_margin   DEVICE [n_seq] fp32: smallest |c - accept_ratio| over tested children
+ *   workspace, workspace_bytes  not used (verification needs no scratch memory); pass NULL, 0
  * Arithmetic is fp32.  vocab <= DYSPEC_MAX_VOCAB.
  */
 dyspec_status dyspec_verify(const float* draft_logits, const float* target_logits,

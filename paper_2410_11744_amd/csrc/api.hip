@@ -29,6 +29,17 @@ static dyspec_status check_batch(const dyspec_batch* b, bool need_prefix, SeqArg
     return DYSPEC_OK;
 }
 
+// Address alignment the kernels' vector loads rely on (16-byte pieces of tensors and logit rows,
+// 8-byte mask words, 4-byte tree arrays); checked here so that a misaligned pointer is an error
+// code and never a faulting load.
+static bool aligned(const void* p, size_t n) { return (reinterpret_cast<size_t>(p) & (n - 1)) == 0; }
+
+static bool tree_aligned(const dyspec_tree* t)
+{
+    return aligned(t->parent, 4) && aligned(t->token, 4) && aligned(t->sib_rank, 4) && aligned(t->first_child, 4) &&
+           aligned(t->next_sibling, 4) && aligned(t->depth, 4);
+}
+
 static bool tree_ok(const dyspec_tree* t)
 {
     return t && t->parent && t->token && t->sib_rank && t->first_child && t->next_sibling && t->depth;
@@ -105,6 +116,9 @@ dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab, const 
     if (!draft_logits || !draft_temp || !tree_ok(tree) || !est_value || !anc_mask || !n_built) return DYSPEC_BAD_ARG;
     if (vocab < 1) return DYSPEC_BAD_ARG;
     if (vocab > DYSPEC_MAX_VOCAB) return DYSPEC_UNSUPPORTED;
+    if (!aligned(draft_logits, 16) || !tree_aligned(tree) || !aligned(est_value, 4) || !aligned(anc_mask, 8) ||
+        !aligned(n_built, 4) || (workspace && !aligned(workspace, 8)))
+        return DYSPEC_BAD_ARG;
     for (int s = 0; s < sa.n_seq; ++s) {
         if (!(draft_temp[s] > 0.0f)) return DYSPEC_BAD_ARG;
         sa.temp_d[s] = draft_temp[s];
@@ -134,12 +148,14 @@ dyspec_status dyspec_build_tree_threshold(const float* draft_logits, int32_t voc
         return DYSPEC_BAD_ARG;
     if (vocab < 1) return DYSPEC_BAD_ARG;
     if (vocab > DYSPEC_MAX_VOCAB) return DYSPEC_UNSUPPORTED;
+    if (!aligned(draft_logits, 16) || !tree_aligned(tree) || !aligned(est_value, 4) || !aligned(anc_mask, 8) ||
+        !aligned(n_built, 4) || (workspace && !aligned(workspace, 8)))
+        return DYSPEC_BAD_ARG;
     for (int s = 0; s < sa.n_seq; ++s) {
         if (!(draft_temp[s] > 0.0f) || !(threshold[s] > 0.0)) return DYSPEC_BAD_ARG;
         sa.temp_d[s] = draft_temp[s];
     }
-    if (!workspace || (reinterpret_cast<size_t>(workspace) & 7) || workspace_bytes < build_threshold_workspace_bytes(sa))
-        return DYSPEC_WORKSPACE_TOO_SMALL;
+    if (!workspace || workspace_bytes < build_threshold_workspace_bytes(sa)) return DYSPEC_WORKSPACE_TOO_SMALL;
     int levels = 0;
     const hipError_t e = launch_build_threshold(draft_logits, vocab, sa, threshold, seed, *tree, est_value, anc_mask,
                                                 mask_words_of(batch), n_built, &levels, workspace,
@@ -158,6 +174,7 @@ dyspec_status dyspec_dfs_reorder(const dyspec_batch* batch, const dyspec_tree* t
     if (tree->parent == tree_out->parent || tree->token == tree_out->token || tree->first_child == tree_out->first_child ||
         tree->next_sibling == tree_out->next_sibling || tree->sib_rank == tree_out->sib_rank || tree->depth == tree_out->depth)
         return DYSPEC_BAD_ARG;                                   // not in place
+    if (!tree_aligned(tree) || !tree_aligned(tree_out) || !aligned(order, 4) || !aligned(anc_mask_out, 8)) return DYSPEC_BAD_ARG;
     const hipError_t e = launch_dfs_reorder(sa, *tree, *tree_out, order, anc_mask_out, mask_words_of(batch),
                                             static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DYSPEC_OK : DYSPEC_HIP_ERROR;
@@ -180,6 +197,11 @@ static dyspec_status tree_attn_common(const void* q, const void* k_prefix, const
     if (any_prefix && (!k_prefix || !v_prefix)) return DYSPEC_BAD_ARG;
     if (n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads != 0) return DYSPEC_BAD_SHAPE;
     if (!(softmax_scale > 0.0f)) return DYSPEC_BAD_ARG;
+    // 16-byte pieces of every tensor are loaded at once (and moved to LDS without passing through
+    // registers); mask rows are 8-byte words; the workspace holds float4 partial rows
+    if (!aligned(q, 16) || !aligned(k_prefix, 16) || !aligned(v_prefix, 16) || !aligned(k_tree, 16) || !aligned(v_tree, 16) ||
+        !aligned(out, 16) || !aligned(anc_mask, 8) || (workspace && !aligned(workspace, 16)))
+        return DYSPEC_BAD_ARG;
     bool force_simple = false;
     if (dtype == DYSPEC_BF16 || dtype == DYSPEC_BF16_WAVE) {
         force_simple = dtype == DYSPEC_BF16_WAVE;
@@ -258,6 +280,10 @@ static dyspec_status verify_common(const void* draft_logits, const void* target_
         return DYSPEC_BAD_ARG;
     if (vocab < 1) return DYSPEC_BAD_ARG;
     if (vocab > DYSPEC_MAX_VOCAB) return DYSPEC_UNSUPPORTED;
+    if (!aligned(draft_logits, 16) || !aligned(target_logits, 16) || !tree_aligned(tree) || !aligned(row_stats, 16) ||
+        !aligned(accept_ratio, 4) || !aligned(accepted_nodes, 4) || !aligned(n_accepted, 4) || !aligned(final_token, 4) ||
+        !aligned(min_margin, 4))
+        return DYSPEC_BAD_ARG;
     for (int s = 0; s < sa.n_seq; ++s) {
         if (!(draft_temp[s] > 0.0f) || !(target_temp[s] >= 0.0f)) return DYSPEC_BAD_ARG;   // target 0 = argmax row
         sa.temp_d[s] = draft_temp[s];
@@ -287,7 +313,6 @@ dyspec_status dyspec_verify_bf16(const void* draft_logits, const void* target_lo
                                  int32_t* n_accepted, int32_t* final_token, float* min_margin,
                                  void*, size_t, void* hip_stream)
 {
-    if ((reinterpret_cast<size_t>(draft_logits) | reinterpret_cast<size_t>(target_logits)) & 1) return DYSPEC_BAD_ARG;
     return verify_common(draft_logits, target_logits, true, vocab, batch, tree, draft_temp, target_temp, seed, emit_bonus,
                          row_stats, accept_ratio, accepted_nodes, n_accepted, final_token, min_margin, hip_stream);
 }

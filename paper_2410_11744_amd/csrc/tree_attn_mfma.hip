@@ -241,15 +241,16 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                 direct_load_16(base + (size_t)(L::kRowsPerLoad * x) * kv_row_bytes, (uint32_t)voff[x & 3], dst + x * 1024);
             });
         } else {
-            // rows past the end read row 0 of the region (a key every query may see, so its
-            // values are as finite as the result itself); their scores are masked out
+            // rows past the end read the last row of the region instead (finite values, as every row
+            // of the tensor); their scores are masked out.  The tile's first row goes into the 64-bit
+            // base, so the 32-bit lane offset stays below 64 rows whatever the prefix length.
+            const char* base = region + (size_t)key0 * kv_row_bytes;
             static_for<LPW>([=](auto xc) {
                 constexpr int x = decltype(xc)::value;
                 const int rowx = L::kRowsPerLoad * (ld_x0 + x);
-                const int key = key0 + rowx + ld_lrow;
-                const uint32_t off = (key < limit) ? (uint32_t)(key0 + rowx) * (uint32_t)kv_row_bytes + (uint32_t)voff[x & 3]
-                                                   : (uint32_t)(voff[x & 3] - ld_lrow * (int)kv_row_bytes);
-                direct_load_16(region, off, dst + x * 1024);
+                const int back = max(key0 + rowx + ld_lrow - (limit - 1), 0);        // rows past the last one
+                const uint32_t off = (uint32_t)(rowx - back) * (uint32_t)kv_row_bytes + (uint32_t)voff[x & 3];
+                direct_load_16(base, off, dst + x * 1024);
             });
         }
     };

@@ -44,3 +44,48 @@ def test_host_validation_without_gpu():
     bad = binding.Batch(np.array([0, 5, 3], np.int32), np.zeros(2, np.int32), np.zeros(3, np.int64))
     cb = bad._c()
     assert lib.dyspec_build_tree(None, 100, ctypes.byref(cb), None, 0, None, None, None, None, None, 0, None) == -2
+
+
+def test_misaligned_pointers_are_refused_before_any_launch():
+    """Addresses that are not aligned as the header states give DYSPEC_BAD_ARG from the host-side
+    validation (nothing is launched, so fake addresses are enough and no GPU is needed)."""
+    from paper_2410_11744_amd import binding
+    lib = binding.load_library()
+    b = binding.Batch.from_sizes([40, 9], [100, 64])
+    c = b._c()
+    F = ctypes.c_float
+    temps = (F * 2)(1.0, 1.0)
+    A = 0x7f0000001000                                     # a well-aligned fake device address
+    tree = binding._Tree(*[A + 0x100 * k for k in range(6)])
+
+    def attn(q=A, kp=A, vp=A, kt=A, vt=A, mask=A, out=A, ws=None, dtype=binding.BF16):
+        return lib.dyspec_tree_attn(q, kp, vp, kt, vt, mask, ctypes.byref(c), 8, 2, 128, dtype, 0.1, out, ws, 0, None)
+
+    for name in ("q", "kp", "vp", "kt", "vt", "out", "ws"):
+        assert attn(**{name: A + 8}) == -1, name           # tensors and workspace: 16 bytes
+    assert attn(mask=A + 4) == -1                           # mask words: 8 bytes
+    assert attn(q=A + 8, dtype=binding.F32) == -1
+    assert lib.dyspec_tree_attn_layers(A, A, A + 2, A, A, A, ctypes.byref(c), 3, 1 << 20, 1 << 20, 1 << 20, 8, 2, 128,
+                                       binding.BF16, 0.1, A, None, 0, None) == -1
+
+    outs = [A] * 6
+
+    def verify(fn, d=A, t=A, tr=tree, outs=outs):
+        return fn(d, t, 1000, ctypes.byref(c), ctypes.byref(tr), temps, temps, 0, 1, *outs, None, 0, None)
+
+    for fn in (lib.dyspec_verify, lib.dyspec_verify_bf16):
+        assert verify(fn, d=A + 4) == -1 and verify(fn, t=A + 8) == -1            # logit tables: 16 bytes
+        assert verify(fn, outs=[A + 8] + [A] * 5) == -1                           # row_stats: 16 bytes
+        assert verify(fn, outs=[A, A + 2] + [A] * 4) == -1                        # float / int arrays: 4 bytes
+        assert verify(fn, tr=binding._Tree(A, A + 2, A, A, A, A)) == -1
+
+    def build(d=A, tr=tree, est=A, mask=A, nb=A, ws=None):
+        return lib.dyspec_build_tree(d, 1000, ctypes.byref(c), temps, 0, ctypes.byref(tr), est, mask, nb, ws, 0, None)
+
+    assert build(d=A + 4) == -1 and build(mask=A + 4) == -1 and build(est=A + 2) == -1 and build(ws=A + 4) == -1
+    thr = (ctypes.c_double * 2)(0.1, 0.1)
+    assert lib.dyspec_build_tree_threshold(A + 4, 1000, ctypes.byref(c), temps, thr, 0, ctypes.byref(tree), A, A, A,
+                                           None, A, 1 << 30, None) == -1
+    tree2 = binding._Tree(*[A + 0x1000 + 0x100 * k for k in range(6)])
+    assert lib.dyspec_dfs_reorder(ctypes.byref(c), ctypes.byref(tree), ctypes.byref(tree2), A + 2, A, None) == -1
+    assert lib.dyspec_dfs_reorder(ctypes.byref(c), ctypes.byref(tree), ctypes.byref(tree2), A, A + 4, None) == -1
