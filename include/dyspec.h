@@ -214,6 +214,27 @@ dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* 
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * dyspec_tree_attn_static_scratch -- dyspec_tree_attn for callers that cannot allocate device
+ * memory and have none to hand over as a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same operation, arguments, kernels and results as
+ * dyspec_tree_attn called with a workspace of dyspec_workspace_bytes(DYSPEC_WS_TREE_ATTN, ...)
+ * bytes; the partial results of a split prefix go to an array of DYSPEC_STATIC_SCRATCH_BYTES that
+ * is part of the library's device image (each GPU the library runs on holds its copy until the
+ * process ends).  The call allocates and frees nothing.  A batch whose split needs more than
+ * DYSPEC_STATIC_SCRATCH_BYTES is refused with DYSPEC_WORKSPACE_TOO_SMALL (nothing launched).
+ * Every call on one GPU uses the same array: calls that overlap on one GPU (two streams, two
+ * threads) race; order them, or give the overlapping ones dyspec_tree_attn with workspaces of
+ * their own.  Nothing in the array has to survive from one call to the next.
+ */
+#define DYSPEC_STATIC_SCRATCH_BYTES (16u << 20)
+dyspec_status dyspec_tree_attn_static_scratch(const void* q, const void* k_prefix, const void* v_prefix,
+                                              const void* k_tree, const void* v_tree,
+                                              const uint64_t* anc_mask, const dyspec_batch* batch,
+                                              int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                              int32_t dtype, float softmax_scale, void* out,
+                                              void* hip_stream);
+
+/*
  * dyspec_tree_attn_layers -- dyspec_tree_attn for n_layers stacked layers in one call
  * (the same operation as above, Section 2 "Tree Attention", once per layer; the tree and
  * its mask are the same in every layer of one speculative step, the tensors are not).

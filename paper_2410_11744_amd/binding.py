@@ -20,7 +20,7 @@ MAX_SEQ, MAX_NODES, MAX_VOCAB = 64, 1024, 32768
 WS_BUILD_TREE, WS_TREE_ATTN, WS_VERIFY = 0, 1, 2
 EXPORTS = ("dyspec_mask_words", "dyspec_workspace_bytes", "dyspec_status_string",
            "dyspec_build_tree", "dyspec_build_tree_threshold", "dyspec_build_tree_threshold_workspace_bytes",
-           "dyspec_dfs_reorder", "dyspec_tree_attn", "dyspec_tree_attn_layers",
+           "dyspec_dfs_reorder", "dyspec_tree_attn", "dyspec_tree_attn_static_scratch", "dyspec_tree_attn_layers",
            "dyspec_tree_attn_layers_workspace_bytes", "dyspec_verify", "dyspec_verify_bf16",
            "dyspec_probe_mfma_bf16", "dyspec_probe_clock", "dyspec_probe_hbm_read")
 
@@ -76,6 +76,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.dyspec_build_tree_threshold_workspace_bytes.argtypes = [PB]
     lib.dyspec_tree_attn.restype = I32
     lib.dyspec_tree_attn.argtypes = [V, V, V, V, V, V, PB, I32, I32, I32, I32, F, V, V, SZ, V]
+    lib.dyspec_tree_attn_static_scratch.restype = I32
+    lib.dyspec_tree_attn_static_scratch.argtypes = [V, V, V, V, V, V, PB, I32, I32, I32, I32, F, V, V]
     lib.dyspec_tree_attn_layers.restype = I32
     lib.dyspec_tree_attn_layers.argtypes = [V, V, V, V, V, V, PB, I32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                             I32, I32, I32, I32, F, V, V, SZ, V]
@@ -319,9 +321,12 @@ def _scratch(device, nbytes: int):
 
 
 def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, softmax_scale: float,
-              out=None, dtype: Optional[int] = None, stream=None, use_workspace: bool = True):
+              out=None, dtype: Optional[int] = None, stream=None, use_workspace: bool = True,
+              static_scratch: bool = False):
     """dyspec_tree_attn: one layer of tree-masked attention.  q/out [sum N, Hq, d].
-    use_workspace=False passes no workspace (then the prefix is never split over workgroups)."""
+    use_workspace=False passes no workspace (then the prefix is never split over workgroups).
+    static_scratch=True calls dyspec_tree_attn_static_scratch instead (the library's own static
+    array in place of a workspace; `out` must be given: this path allocates nothing)."""
     import torch
     lib = load_library()
     total, Hq, d = q.shape
@@ -339,8 +344,16 @@ def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, sof
         if t is not None and t.dtype != q.dtype:
             raise ValueError("q, k, v must share a dtype")
     if out is None:
+        if static_scratch:
+            raise ValueError("static_scratch=True needs the caller's `out` tensor")
         out = torch.empty_like(q)
     cb = batch._c()
+    if static_scratch:
+        st = lib.dyspec_tree_attn_static_scratch(_ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree),
+                                                 _ptr(anc_mask, "int64"), ctypes.byref(cb), int(Hq), Hkv, int(d),
+                                                 int(dtype), ctypes.c_float(softmax_scale), _ptr(out), _stream(stream))
+        _check(st, "dyspec_tree_attn_static_scratch")
+        return out
     ws, ws_bytes = None, 0
     if use_workspace and dtype == BF16:
         memo, wkey = batch._memo(), ("ws_attn", int(Hq), Hkv, int(d))

@@ -1,5 +1,7 @@
 // extern "C" boundary: host-side validation, then kernel launches.  See include/dyspec.h
 // for the contract of every entry point.
+#include <atomic>
+
 #include "dyspec_device.h"
 
 namespace dyspec {
@@ -245,6 +247,48 @@ dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* 
 {
     return tree_attn_common(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch, 1, 0, 0, 0, n_q_heads,
                             n_kv_heads, head_dim, dtype, softmax_scale, out, workspace, workspace_bytes, hip_stream);
+}
+
+// ---- the variant for callers that cannot allocate: partial results go to a static device array
+//
+// In host code the array's name is only a stand-in for the symbol; its device address comes from
+// hipGetSymbolAddress, once per device (every GPU holds its own copy at its own address), and that
+// address is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[DYSPEC_STATIC_SCRATCH_BYTES];
+
+static hipError_t static_scratch_address(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> per_device[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void* p = per_device[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // with `dev` current: this device's copy
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        per_device[dev].store(p, std::memory_order_release); // two racing first calls store the same address
+    }
+    *out = p;
+    return hipSuccess;
+}
+
+dyspec_status dyspec_tree_attn_static_scratch(const void* q, const void* k_prefix, const void* v_prefix,
+                                              const void* k_tree, const void* v_tree, const uint64_t* anc_mask,
+                                              const dyspec_batch* batch, int32_t n_q_heads, int32_t n_kv_heads,
+                                              int32_t head_dim, int32_t dtype, float softmax_scale, void* out,
+                                              void* hip_stream)
+{
+    // how much the split this batch would get needs; 0 (no split, or a dtype / shape the checks
+    // below refuse anyway) needs no scratch at all
+    const size_t need = dtype == DYSPEC_BF16 ? dyspec_workspace_bytes(DYSPEC_WS_TREE_ATTN, batch, 0, n_q_heads, n_kv_heads, head_dim) : 0;
+    if (need > DYSPEC_STATIC_SCRATCH_BYTES) return DYSPEC_WORKSPACE_TOO_SMALL;
+    void* ws = nullptr;
+    if (need > 0 && static_scratch_address(&ws) != hipSuccess) return DYSPEC_HIP_ERROR;
+    return tree_attn_common(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch, 1, 0, 0, 0, n_q_heads,
+                            n_kv_heads, head_dim, dtype, softmax_scale, out, ws, need, hip_stream);
 }
 
 dyspec_status dyspec_tree_attn_layers(const void* q, const void* k_prefix, const void* v_prefix,

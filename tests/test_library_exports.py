@@ -89,3 +89,15 @@ def test_misaligned_pointers_are_refused_before_any_launch():
     tree2 = binding._Tree(*[A + 0x1000 + 0x100 * k for k in range(6)])
     assert lib.dyspec_dfs_reorder(ctypes.byref(c), ctypes.byref(tree), ctypes.byref(tree2), A + 2, A, None) == -1
     assert lib.dyspec_dfs_reorder(ctypes.byref(c), ctypes.byref(tree), ctypes.byref(tree2), A, A + 4, None) == -1
+
+
+def test_static_scratch_entry_point_refuses_oversized_batches_on_the_host():
+    """The size check of dyspec_tree_attn_static_scratch comes before anything touches a GPU."""
+    from paper_2410_11744_amd import binding
+    lib = binding.load_library()
+    b = binding.Batch.from_sizes([128], [4096])
+    c = b._c()
+    A = 0x7f0000001000
+    assert lib.dyspec_workspace_bytes(1, ctypes.byref(c), 0, 32, 32, 128) > (16 << 20)
+    st = lib.dyspec_tree_attn_static_scratch(A, A, A, A, A, A, ctypes.byref(c), 32, 32, 128, binding.BF16, 0.1, A, None)
+    assert st == -4
