@@ -79,6 +79,7 @@ int32_t dyspec_mask_words(const dyspec_batch* batch);
 
 /* Bytes of DEVICE workspace the named call can use for this batch (0 = none). */
 enum { DYSPEC_WS_BUILD_TREE = 0, DYSPEC_WS_TREE_ATTN = 1, DYSPEC_WS_VERIFY = 2 };
+#define DYSPEC_ATTN_COUNTER_BYTES 4096   /* head of a tree-attention workspace: see dyspec_tree_attn */
 size_t dyspec_workspace_bytes(int32_t which, const dyspec_batch* batch, int32_t vocab,
                               int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim);
 
@@ -199,11 +200,15 @@ dyspec_status dyspec_dfs_reorder(const dyspec_batch* batch, const dyspec_tree* t
  *                     (head_dim 64 or 128; matrix-core path, fp32 accumulation)
  * All tensors are dense row-major and 16-byte aligned (checked: DYSPEC_BAD_ARG).
  *   workspace         DEVICE, 16-byte aligned, dyspec_workspace_bytes(DYSPEC_WS_TREE_ATTN, ...)
- *                     bytes, contents overwritten.  Non-zero only for batches whose (row
- *                     tiles) x (KV heads) leave most of the chip idle: the bf16 path then
- *                     splits every prefix over several workgroups, which leave partial
- *                     (max, sum, rows) there for a second, combining kernel.  NULL or fewer
- *                     bytes: no split (same result up to fp32 rounding of the combine).  A
+ *                     bytes.  Non-zero only for batches whose (row tiles) x (KV heads) leave most
+ *                     of the chip idle: the bf16 path then splits every prefix over several
+ *                     workgroups; each leaves its share of every row there (bf16) and the one
+ *                     that finishes last merges them, in the same launch.  The first
+ *                     DYSPEC_ATTN_COUNTER_BYTES of the workspace are the arrival counters of
+ *                     that hand-over: they must be ZERO when a call starts and every call
+ *                     leaves them zero again, so a workspace is cleared once, after it is
+ *                     allocated (hipMemset), and never again; the rest is overwritten.  NULL or
+ *                     fewer bytes: no split (same result up to the bf16 rounding of the parts).  A
  *                     non-NULL workspace that is not 16-byte aligned is DYSPEC_BAD_ARG.
  */
 dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* v_prefix,
@@ -224,9 +229,10 @@ dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* 
  * DYSPEC_STATIC_SCRATCH_BYTES is refused with DYSPEC_WORKSPACE_TOO_SMALL (nothing launched).
  * Every call on one GPU uses the same array: calls that overlap on one GPU (two streams, two
  * threads) race; order them, or give the overlapping ones dyspec_tree_attn with workspaces of
- * their own.  Nothing in the array has to survive from one call to the next.
+ * their own.  The arrival counters at the head of the array start as zeros with the device image
+ * and every call leaves them zero; nothing else in it has to survive from one call to the next.
  */
-#define DYSPEC_STATIC_SCRATCH_BYTES (16u << 20)
+#define DYSPEC_STATIC_SCRATCH_BYTES (8u << 20)
 dyspec_status dyspec_tree_attn_static_scratch(const void* q, const void* k_prefix, const void* v_prefix,
                                               const void* k_tree, const void* v_tree,
                                               const uint64_t* anc_mask, const dyspec_batch* batch,
@@ -246,7 +252,8 @@ dyspec_status dyspec_tree_attn_static_scratch(const void* q, const void* k_prefi
  * no split and pay one launch latency); other dtypes launch once per layer.  This is for
  * callers that hold all layers' tensors at once (benchmarks, layer-parallel schedules);
  * a model that computes layer l+1's Q from layer l's output calls dyspec_tree_attn.
- *   workspace  as for dyspec_tree_attn, dyspec_tree_attn_layers_workspace_bytes() bytes.
+ *   workspace  as for dyspec_tree_attn (its first DYSPEC_ATTN_COUNTER_BYTES zero when the call
+ *              starts), dyspec_tree_attn_layers_workspace_bytes() bytes.
  *   n_layers   1 .. 65535
  */
 dyspec_status dyspec_tree_attn_layers(const void* q, const void* k_prefix, const void* v_prefix,

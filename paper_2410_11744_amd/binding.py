@@ -309,13 +309,14 @@ _scratch_cache = {}
 
 
 def _scratch(device, nbytes: int):
-    """A device buffer of at least nbytes, kept between calls (calls on one stream run in order,
-    so consecutive layers can share it)."""
+    """A zero-filled device buffer of at least nbytes, kept between calls (calls on one stream run
+    in order, so consecutive layers can share it).  Tree attention wants the head of its workspace
+    zero at the first call and leaves it zero, so the buffer is cleared once, here."""
     import torch
     key = str(device)
     buf = _scratch_cache.get(key)
     if buf is None or buf.numel() * 4 < nbytes:
-        buf = torch.empty((nbytes + 3) // 4, dtype=torch.float32, device=device)
+        buf = torch.zeros((nbytes + 3) // 4, dtype=torch.float32, device=device)
         _scratch_cache[key] = buf
     return buf
 

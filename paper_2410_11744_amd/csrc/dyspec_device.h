@@ -32,15 +32,15 @@ struct AttnArgs {
     float scale;
     int tile_off[DYSPEC_MAX_SEQ + 1];      // first row tile of each sequence (matrix-core kernel)
     // prefix split of the matrix-core kernel: split z of `splits` takes every sequence's prefix
-    // tiles [z*c, (z+1)*c) (c: an even share), the last one the tree as well; with splits > 1
-    // each leaves (max, sum, unnormalised rows) in the workspace for the combine kernel
+    // tiles [z*c, (z+1)*c) (c: an even share), the last one the tree as well.  With splits > 1
+    // every workgroup leaves its normalised rows (bf16) and their (max, sum) in `part`, in the
+    // register layout of the kernel, and bumps the arrival counter of its (layer, row tile, KV
+    // head); the workgroup that arrives last merges all parts and writes the output rows.
     int splits;
-    long long part_rows;                   // total rows * Hq
-    float* part_acc;                       // [splits][total rows * Hq][d] fp32
-    float* part_ml;                        // [splits][total rows * Hq][2] fp32
+    uint32_t* part;                        // [layers * tiles * Hkv][splits][attn_part_words(d)]
+    unsigned* counters;                    // [layers * tiles * Hkv], zero between launches
     // stacked layers (matrix-core kernel): layer l = blockIdx.z reads q/out, prefix K/V and
-    // tree K/V at byte offsets l * stride from the base pointers; the mask is shared.  With
-    // layers > 1 the partial buffers are [layers][splits][...].
+    // tree K/V at byte offsets l * stride from the base pointers; the mask is shared.
     int layers;
     long long q_stride, kvp_stride, kvt_stride;
 };
@@ -63,6 +63,10 @@ hipError_t launch_verify(const void* draft_logits, const void* target_logits, bo
 hipError_t launch_tree_attn(AttnArgs a, const SeqArgs& sa, int dtype, bool per_wave, void* workspace, size_t workspace_bytes,
                             hipStream_t stream);
 hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, void* workspace, size_t workspace_bytes, hipStream_t stream);
+// 32-bit words one workgroup of the matrix-core kernel leaves per split: 4 row blocks x 64 lanes x
+// (d/4 packed bf16 pairs + max + sum)
+constexpr int attn_part_words(int d) { return 4 * 64 * (d / 4 + 2); }
+constexpr size_t kAttnCounterBytes = DYSPEC_ATTN_COUNTER_BYTES;     // arrival counters at the head of the workspace
 // splits the matrix-core kernel would like for this batch, and the workspace that takes
 int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv, int layers);
 size_t tree_attn_workspace_bytes(const SeqArgs& sa, int Hq, int Hkv, int d, int layers);

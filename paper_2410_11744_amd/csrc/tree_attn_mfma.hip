@@ -39,6 +39,7 @@
 #include <utility>
 
 #include <atomic>
+#include <cstdlib>
 #include "dyspec_device.h"
 
 namespace dyspec {
@@ -69,6 +70,15 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v* lds_short4;
 typedef __attribute__((address_space(3))) const bf16x8* lds_bf16x8;
+
+#ifdef DYSPEC_STAMPS
+// Timing build only: thread 0 of every workgroup records the 100 MHz wall clock at a few points.
+__device__ unsigned long long g_stamps[8192 * 8];
+__device__ unsigned g_stamp_slot;
+#define STAMP(k) do { if (threadIdx.x == 0) stamp_row[k] = wall_clock64(); } while (0)
+#else
+#define STAMP(k) do { } while (0)
+#endif
 
 constexpr int kRowsPerWG = 128;
 constexpr int kKeysPerTile = 64;
@@ -139,6 +149,11 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63;
+#ifdef DYSPEC_STAMPS
+    unsigned long long* stamp_row = g_stamps;
+    if (threadIdx.x == 0) { stamp_row = g_stamps + (size_t)(atomicAdd(&g_stamp_slot, 1u) % 8192u) * 8; stamp_row[7] = blockIdx.y; }
+    STAMP(0);
+#endif
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, g = lane >> 5;
     const int wq = wave % NWQ, wk = wave / NWQ;
@@ -579,6 +594,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     auto tile_of = [=](int v) __attribute__((always_inline)) -> int {
         return v < nPl ? p_begin + v : kth_tile(active, v - nPl);
     };
+    STAMP(1);
     // first product of the lower half of tile 0 (K slot 0) into S[0]
     half_step(std::false_type{}, std::true_type{}, std::false_type{}, std::false_type{}, std::false_type{},
               std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, none32, nullptr, 0u);
@@ -615,6 +631,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                      st_dst + ((ld_is_v ? ii + 1 : ii) & 1) * L::kSlotBytes);
         });
     }
+    STAMP(2);
     // The rest: ragged prefix tile, tree tiles (ancestor mask), tiles that do not exist (all
     // masked), until the second product of the last real half has run.  A half step does
     // something only if this wave's queries see a key of the half itself or of a neighbour
@@ -649,6 +666,14 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         }
     };
     bool aP1 = true;                                         // the upper half of the last plain tile
+    if (2 * i >= nPl + nAct) {
+        // nothing left to walk (a split of whole prefix tiles that the plain loop has finished; i is
+        // even here): only the second product of the last upper half is outstanding
+        half_step(std::true_type{}, std::false_type{}, std::false_type{}, std::false_type{}, std::false_type{},
+                  std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, none32, nullptr, 0u);
+        wait_direct_loads();                                 // the last plain step's loads land before LDS is reused below
+        i = nIt + 1;
+    }
     for (; i <= nIt; i += 2) {
         static_for<2>([&](auto sp_c) {
             const int ii = i + decltype(sp_c)::value;
@@ -677,6 +702,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         });
     }
     __syncthreads();                                         // every LDS read is done before the merge reuses it
+    STAMP(3);
 
     // ---- merge the two key halves of each row block through LDS, normalise, store
 #pragma unroll
@@ -698,10 +724,12 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         for (int qb = 0; qb < QB; ++qb) dst[(r++) * kWave] = l_run[qb];
     }
     __syncthreads();
+    // Row blocks are finished by the wk == 0 waves: (m_all, l_all) and the unnormalised rows, both key
+    // halves merged.  Register i of block db is head-dim index 32*db + 8*(i/4) + 4*g + i%4.
+    float m_all[QB], l_all[QB];
     if (wk == 0) {
         const float* src = xs + (size_t)wq * NR * kWave + lane;
-        const bool partial = n_split > 1;                  // leave (max, sum, unnormalised row) for the combine kernel
-        float f0[QB], f1[QB], inv[QB], m_all[QB], l_all[QB];
+        float f0[QB], f1[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const float m1 = src[(NR - 2 * QB + qb) * kWave], l1 = src[(NR - QB + qb) * kWave];
@@ -710,7 +738,6 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
             f1[qb] = exp2f((m1 - m) * c2);
             m_all[qb] = m;
             l_all[qb] = l_run[qb] * f0[qb] + l1 * f1[qb];
-            inv[qb] = partial ? 1.0f : 1.0f / l_all[qb];
         }
         int r = 0;
 #pragma unroll
@@ -720,26 +747,132 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
 #pragma unroll
                 for (int i2 = 0; i2 < 16; ++i2) {
                     const float o1 = src[(r++) * kWave];
-                    acc[db][qb][i2] = (acc[db][qb][i2] * f0[qb] + o1 * f1[qb]) * inv[qb];
+                    acc[db][qb][i2] = acc[db][qb][i2] * f0[qb] + o1 * f1[qb];
                 }
-        // register i of block db is head-dim index 32*db + 8*(i/4) + 4*g + i%4
+    }
+    STAMP(4);
+    if (n_split > 1) {
+        // Prefix split.  Every workgroup leaves its normalised rows (bf16) and their (max, sum) in the
+        // workspace, in register layout (word k of lane l at k*64 + l: each store of a wave is one
+        // 512-byte run), then arrives at the counter of its (layer, row tile, KV head).  The one that
+        // arrives last reads all parts and finishes the rows.  The counter wraps to zero with the
+        // last arrival, so the next launch finds it as this one did.
+        // Parts are written and read with device-scope atomic accesses (relaxed): they go to the
+        // level of the memory system all workgroups share, whichever XCD they run on, without the
+        // cache-wide write-back and invalidate a device-scope fence around plain accesses costs.
+        static_assert(QB == 1, "the part layout assumes one query block per wave");
+        constexpr int W2 = DB * 4;                              // 64-bit words of packed bf16 per lane
+        constexpr int PW2 = attn_part_words(D) / 2;             // 64-bit words per (group, split)
+        const size_t group = (size_t)layer * gridDim.x + blockIdx.x;
+        unsigned long long* const parts = reinterpret_cast<unsigned long long*>(a.part) + group * n_split * PW2 +
+                                          (size_t)wq * (W2 + 1) * kWave + lane;
+        auto pack2 = [](float x, float y) -> uint32_t {
+            floatx2 v = { x, y };
+            return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+        };
+        if (wk == 0) {
+            unsigned long long* const mine = parts + (size_t)split * PW2;
+            const float inv = l_all[0] > 0.0f ? 1.0f / l_all[0] : 0.0f;     // a split without keys: weight 0, rows 0
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) {
+                    const uint32_t lo = pack2(acc[db][0][4 * ib] * inv, acc[db][0][4 * ib + 1] * inv);
+                    const uint32_t hi = pack2(acc[db][0][4 * ib + 2] * inv, acc[db][0][4 * ib + 3] * inv);
+                    __hip_atomic_store(mine + (db * 4 + ib) * kWave, ((unsigned long long)hi << 32) | lo, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                }
+            __hip_atomic_store(mine + W2 * kWave, ((unsigned long long)__float_as_uint(l_all[0]) << 32) | __float_as_uint(m_all[0]),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // every store of the workgroup has been acknowledged before its arrival is counted
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned before = __builtin_amdgcn_atomic_inc32(a.counters + group, (unsigned)n_split - 1u, __ATOMIC_RELAXED, "agent");
+            *tile_flag = before == (unsigned)n_split - 1u;
+        }
+        __syncthreads();
+        STAMP(5);
+        if (*tile_flag == 0u) return;                          // uniform over the workgroup
+        // All parts come from memory, this workgroup's own too, and are summed in split order: the
+        // result does not depend on which workgroup happened to arrive last.  All eight waves take
+        // part: wave (wq, wk) finishes head-dim blocks [wk*DB/2, (wk+1)*DB/2) of row block wq, with
+        // the loads of four splits in flight at a time.
+        constexpr int HW = W2 / 2;                              // 64-bit words per lane and split in this wave's half
+        auto ld = [&](int z, int k) -> unsigned long long {
+            return __hip_atomic_load(parts + (size_t)z * PW2 + k * kWave, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        };
+        float M = -1e30f, Lsum = 0.0f;
+        float o[HW][4];
+#pragma unroll
+        for (int k = 0; k < HW; ++k)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[k][e] = 0.0f;
+        // ZB splits per trip to memory (a trip costs about as much as a step of the walk)
+        auto add_batch = [&](auto zb_c, int z0) __attribute__((always_inline)) {
+            constexpr int ZB = decltype(zb_c)::value;
+            unsigned long long w[ZB][HW + 1];
+#pragma unroll
+            for (int dz = 0; dz < ZB; ++dz) {
+                const int z = min(z0 + dz, n_split - 1);       // past the end: the last split again, weight 0 below
+#pragma unroll
+                for (int k = 0; k < HW; ++k) w[dz][k] = ld(z, wk * HW + k);
+                w[dz][HW] = ld(z, W2);
+            }
+            float Mb = M;                                      // the reference maximum moves up with the batch
+#pragma unroll
+            for (int dz = 0; dz < ZB; ++dz) Mb = fmaxf(Mb, __uint_as_float((uint32_t)w[dz][HW]));
+            const float up = exp2f((M - Mb) * c2);
+            M = Mb;
+            Lsum *= up;
+#pragma unroll
+            for (int k = 0; k < HW; ++k)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[k][e] *= up;
+#pragma unroll
+            for (int dz = 0; dz < ZB; ++dz) {
+                const float mz = __uint_as_float((uint32_t)w[dz][HW]), lz = __uint_as_float((uint32_t)(w[dz][HW] >> 32));
+                const float wz = z0 + dz < n_split ? exp2f((mz - M) * c2) * lz : 0.0f;   // normalised rows: weight times sum
+                Lsum += wz;
+#pragma unroll
+                for (int k = 0; k < HW; ++k) {
+                    const uint32_t lo = (uint32_t)w[dz][k], hi = (uint32_t)(w[dz][k] >> 32);
+                    o[k][0] = fmaf(wz, __uint_as_float(lo << 16), o[k][0]);
+                    o[k][1] = fmaf(wz, __uint_as_float(lo & 0xffff0000u), o[k][1]);
+                    o[k][2] = fmaf(wz, __uint_as_float(hi << 16), o[k][2]);
+                    o[k][3] = fmaf(wz, __uint_as_float(hi & 0xffff0000u), o[k][3]);
+                }
+            }
+        };
+        if (n_split <= 4) {
+            add_batch(std::integral_constant<int, 4>{}, 0);
+        } else {
+            for (int z0 = 0; z0 < n_split; z0 += 8) add_batch(std::integral_constant<int, 8>{}, z0);
+        }
+        if (rq[0] >= rows) return;
+        const float inv = 1.0f / Lsum;
+        const int j = rq[0] / G, h = kvh * G + rq[0] % G;
+        __bf16* orow = reinterpret_cast<__bf16*>(static_cast<char*>(a.out) + (size_t)layer * a.q_stride) +
+                       ((size_t)(node_base + j) * a.Hq + h) * D;
+#pragma unroll
+        for (int k = 0; k < HW; ++k) {
+            const int db = (wk * HW + k) / 4, ib = (wk * HW + k) % 4;
+            uint2 v;
+            v.x = pack2(o[k][0] * inv, o[k][1] * inv);
+            v.y = pack2(o[k][2] * inv, o[k][3] * inv);
+            *reinterpret_cast<uint2*>(orow + 32 * db + 8 * ib + 4 * g) = v;
+        }
+        STAMP(6);
+        return;
+    }
+    if (wk == 0) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             if (rq[qb] >= rows) continue;
+            const float inv = 1.0f / l_all[qb];
             const int j = rq[qb] / G, h = kvh * G + rq[qb] % G;
             const size_t orow_index = (size_t)(node_base + j) * a.Hq + h;
-            if (partial) {
-                const size_t prow = ((size_t)layer * n_split + split) * a.part_rows + orow_index;
-                float* prow_acc = a.part_acc + prow * D;
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int ib = 0; ib < 4; ++ib)
-                        *reinterpret_cast<float4*>(prow_acc + 32 * db + 8 * ib + 4 * g) =
-                            make_float4(acc[db][qb][4 * ib], acc[db][qb][4 * ib + 1], acc[db][qb][4 * ib + 2], acc[db][qb][4 * ib + 3]);
-                if (g == 0) *reinterpret_cast<float2*>(a.part_ml + prow * 2) = make_float2(m_all[qb], l_all[qb]);
-                continue;
-            }
             __bf16* orow = reinterpret_cast<__bf16*>(static_cast<char*>(a.out) + (size_t)layer * a.q_stride) + orow_index * D;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -748,44 +881,13 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                     union { bf16x2 p[2]; uint2 v; } o;
 #pragma unroll
                     for (int ii = 0; ii < 2; ++ii) {
-                        floatx2 pr = { acc[db][qb][4 * ib + 2 * ii], acc[db][qb][4 * ib + 2 * ii + 1] };
+                        floatx2 pr = { acc[db][qb][4 * ib + 2 * ii] * inv, acc[db][qb][4 * ib + 2 * ii + 1] * inv };
                         o.p[ii] = __builtin_convertvector(pr, bf16x2);
                     }
                     *reinterpret_cast<uint2*>(orow + 32 * db + 8 * ib + 4 * g) = o.v;
                 }
         }
     }
-}
-
-// Combine of a prefix split: out[row] = sum_z w_z acc_z[row] / sum_z w_z l_z, w_z = 2^{c (m_z - M)},
-// M = max_z m_z.  One thread per four head-dim elements of a row.
-template <int D>
-__global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnArgs a, long long total)
-{
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const size_t row = (size_t)(idx / (D / 4));
-    const int c4 = (int)(idx % (D / 4));
-    const float c2 = a.scale * 1.4426950408889634f;
-    const size_t z0 = (size_t)blockIdx.y * a.splits;            // blockIdx.y: layer
-    float M = -INFINITY;
-    for (int z = 0; z < a.splits; ++z) M = fmaxf(M, a.part_ml[((z0 + z) * a.part_rows + row) * 2]);
-    float L = 0.0f;
-    float4 o = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    for (int z = 0; z < a.splits; ++z) {
-        const size_t prow = (z0 + z) * a.part_rows + row;
-        const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + prow * 2);
-        const float w = exp2f((ml.x - M) * c2);
-        const float4 v = *reinterpret_cast<const float4*>(a.part_acc + prow * D + 4 * c4);
-        L += ml.y * w;
-        o.x += v.x * w; o.y += v.y * w; o.z += v.z * w; o.w += v.w * w;
-    }
-    const float inv = 1.0f / L;
-    union { bf16x2 p[2]; uint2 v; } out;
-    floatx2 lo = { o.x * inv, o.y * inv }, hi = { o.z * inv, o.w * inv };
-    out.p[0] = __builtin_convertvector(lo, bf16x2);
-    out.p[1] = __builtin_convertvector(hi, bf16x2);
-    *reinterpret_cast<uint2*>(reinterpret_cast<__bf16*>(static_cast<char*>(a.out) + (size_t)blockIdx.y * a.q_stride) + row * D + 4 * c4) = out.v;
 }
 
 template <int D, int QB>
@@ -804,10 +906,6 @@ static hipError_t launch_one(const AttnArgs& a, const SeqArgs& sa, int tiles, hi
         raised.fetch_or(bit, std::memory_order_release);
     }
     tree_attn_mfma_kernel<D, QB><<<dim3(tiles * a.Hkv, a.splits, a.layers), 64 * 2 * (4 / QB), Geo<D>::kLdsBytes + 16, stream>>>(a, sa);
-    if (a.splits > 1) {
-        const long long total = (long long)a.part_rows * (D / 4);
-        tree_attn_combine_kernel<D><<<dim3((unsigned)((total + 255) / 256), a.layers), 256, 0, stream>>>(a, total);
-    }
     return hipGetLastError();
 }
 
@@ -824,25 +922,31 @@ static int row_tiles(const SeqArgs& sa, int G, int* tile_off)
 
 // The kernel's parallelism is (row tiles) x (KV heads) x layers, one workgroup per CU at a time;
 // when that leaves most of the 256 CUs idle (narrow trees, few KV heads) the prefix is split
-// until the workgroups fill the chip once, as long as every split keeps at least eight 64-key
-// tiles of every sequence's prefix: below that the partial results and the combining kernel
-// cost more than the shorter walk saves (measured: 1024 keys over 32 workgroups run best in
-// two or three parts, 4096 keys over 16 workgroups in eight).
+// until the workgroups fill the chip once, as long as every split keeps at least four 64-key
+// tiles of every sequence's prefix, and into at most eight parts (what the finishing workgroup
+// fetches in one trip to memory).  Measured per layer: 1024 keys over 32 workgroups run best in 4
+// parts, 2048 keys over 80 in 3, 4096 keys over 16 in 8.
 int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv, int layers)
 {
     const int groups = row_tiles(sa, Hq / Hkv, nullptr) * Hkv * layers;
     if (groups == 0) return 1;
     int min_tiles = 1 << 30;
     for (int s = 0; s < sa.n_seq; ++s) min_tiles = min(min_tiles, (sa.prefix_len[s] + kKeysPerTile - 1) / kKeysPerTile);
-    const int by_work = 256 / groups, by_prefix = min_tiles / 8;
-    return max(1, min(min(by_work, by_prefix), 32));
+    const int by_work = 256 / groups, by_prefix = min_tiles / 4;
+    int splits = max(1, min(min(by_work, by_prefix), 8));
+#ifdef DYSPEC_TUNING
+    if (const char* e = getenv("DYSPEC_ATTN_SPLITS")) splits = max(1, min(atoi(e), min(min_tiles / 2, 32)));
+#endif
+    if ((size_t)groups * sizeof(unsigned) > kAttnCounterBytes) splits = 1;     // one arrival counter per group
+    return splits;
 }
 
 size_t tree_attn_workspace_bytes(const SeqArgs& sa, int Hq, int Hkv, int d, int layers)
 {
     const int splits = tree_attn_splits(sa, Hq, Hkv, layers);
     if (splits <= 1) return 0;
-    return (size_t)layers * splits * sa.node_off[sa.n_seq] * Hq * (d + 2) * sizeof(float);
+    const size_t groups = (size_t)row_tiles(sa, Hq / Hkv, nullptr) * Hkv * layers;
+    return kAttnCounterBytes + groups * splits * attn_part_words(d) * sizeof(uint32_t);
 }
 
 hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, void* workspace, size_t workspace_bytes, hipStream_t stream)
@@ -850,15 +954,27 @@ hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, void* workspace,
     const int tiles = row_tiles(sa, a.Hq / a.Hkv, a.tile_off);
     if (tiles == 0) return hipSuccess;
     a.splits = tree_attn_splits(sa, a.Hq, a.Hkv, a.layers);
-    a.part_rows = (long long)sa.node_off[sa.n_seq] * a.Hq;
     const size_t need = tree_attn_workspace_bytes(sa, a.Hq, a.Hkv, a.d, a.layers);
     if (a.splits > 1 && (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<size_t>(workspace) & 15)))
         a.splits = 1;                                          // no room for partial results: one workgroup walks it all
     if (a.splits > 1) {
-        a.part_acc = static_cast<float*>(workspace);
-        a.part_ml = a.part_acc + (size_t)a.layers * a.splits * a.part_rows * a.d;
+        a.counters = static_cast<unsigned*>(workspace);
+        a.part = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + kAttnCounterBytes);
     }
     return a.d == 128 ? launch_one<128, kQB>(a, sa, tiles, stream) : launch_one<64, kQB>(a, sa, tiles, stream);
 }
+
+#ifdef DYSPEC_STAMPS
+extern "C" int dyspec_debug_read(void* host_dst)
+{
+    // copies the stamps out (waits for the device) and clears them for the next run
+    unsigned zero = 0;
+    static unsigned long long z[8192 * 8];
+    hipError_t e = hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(g_stamps), sizeof(z));
+    if (e == hipSuccess) e = hipMemcpyToSymbol(HIP_SYMBOL(g_stamp_slot), &zero, sizeof(zero));
+    if (e == hipSuccess) e = hipMemcpyToSymbol(HIP_SYMBOL(g_stamps), z, sizeof(z));
+    return (int)e;
+}
+#endif
 
 }  // namespace dyspec

@@ -98,6 +98,6 @@ def test_static_scratch_entry_point_refuses_oversized_batches_on_the_host():
     b = binding.Batch.from_sizes([128], [4096])
     c = b._c()
     A = 0x7f0000001000
-    assert lib.dyspec_workspace_bytes(1, ctypes.byref(c), 0, 32, 32, 128) > (16 << 20)
+    assert lib.dyspec_workspace_bytes(1, ctypes.byref(c), 0, 32, 32, 128) > (8 << 20)
     st = lib.dyspec_tree_attn_static_scratch(A, A, A, A, A, A, ctypes.byref(c), 32, 32, 128, binding.BF16, 0.1, A, None)
     assert st == -4

@@ -84,9 +84,9 @@ def test_static_scratch_matches_workspace_call_twice_in_a_row(dy):
 
 def test_static_scratch_refuses_what_does_not_fit(dy):
     import ctypes
-    batch = dy.Batch.from_sizes((128,), (4096,))           # 8 splits x 4096 rows x 130 floats > 16 MiB
+    batch = dy.Batch.from_sizes((128,), (4096,))           # 256 workgroups x 34 KB of parts > 8 MiB
     lib = dy.load_library()
-    assert lib.dyspec_workspace_bytes(1, ctypes.byref(batch._c()), 0, 32, 32, 128) > (16 << 20)
+    assert lib.dyspec_workspace_bytes(1, ctypes.byref(batch._c()), 0, 32, 32, 128) > (8 << 20)
     z = torch.zeros((128, 32, 128), dtype=torch.bfloat16, device="cuda")
     kv = torch.zeros((4096, 32, 128), dtype=torch.bfloat16, device="cuda")
     m = torch.zeros((128, 2), dtype=torch.int64, device="cuda")
