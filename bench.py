@@ -64,11 +64,11 @@ def tree_only_sweep(dy, synth, torch, np, dev) -> int:
         return best
 
     rows = []
-    for n in (256, 512, 1024):
+    for n in (256, 512, 1024, 2048):
         batch = dy.Batch.from_sizes([n], [0])
         g = torch.Generator(device=dev).manual_seed(n)
         q, kt, vt = (torch.randn((n, H, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
-        for kind in ("random", "greedy"):
+        for kind in ("random", "greedy") if n <= dy.MAX_BUILD_NODES else ("random",):    # the builder stops at 1024 rows
             if kind == "random":           # parent of node i uniform among the earlier nodes, children in index order
                 rng = np.random.default_rng(n)
                 par = np.full(n, -1, np.int32)
@@ -165,7 +165,7 @@ def main() -> int:
                     help="also launch one plain 1 GiB device copy (a known-size reference for HBM byte counters)")
     ap.add_argument("--tree-only-sweep", action="store_true",
                     help="instead of the step benchmark: tree-only attention (64 heads, head_dim 128, no prefix) on random "
-                         "and greedy trees of 256..1024 nodes, creation order against depth-first order")
+                         "and greedy trees of 256..2048 nodes, creation order against depth-first order")
     ap.add_argument("--target-temp", type=float, default=None,
                     help="target temperature of every sequence in verification (0 = the paper's temperature-0 "
                          "target); default: the workload's own temperatures, as for the draft")

@@ -51,7 +51,8 @@ enum {
 enum { DYSPEC_F32 = 0, DYSPEC_BF16 = 1, DYSPEC_BF16_WAVE = 0x101 };
 
 #define DYSPEC_MAX_SEQ 64            /* sequences per call                                */
-#define DYSPEC_MAX_NODES 1024        /* tree rows per sequence, root included             */
+#define DYSPEC_MAX_NODES 2048        /* tree rows per sequence, root included (attention, reorder, verify) */
+#define DYSPEC_MAX_BUILD_NODES 1024  /* ... for the two tree builders, whose per-tree state lives in LDS   */
 #define DYSPEC_MAX_VOCAB 32768       /* vocabulary handled by the build / verify kernels  */
 
 /* Ragged batch description; all three arrays are HOST memory. */
@@ -115,7 +116,7 @@ const char* dyspec_status_string(dyspec_status s);
  *                 kept current by it.  NULL or fewer bytes: the expansion recomputes the
  *                 parent row's sums at every draw instead (same arithmetic, same tree,
  *                 several times slower).
- * vocab <= DYSPEC_MAX_VOCAB, N <= DYSPEC_MAX_NODES.
+ * vocab <= DYSPEC_MAX_VOCAB, N <= DYSPEC_MAX_BUILD_NODES (DYSPEC_BAD_SHAPE beyond).
  */
 dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab,
                                 const dyspec_batch* batch, const float* draft_temp,
@@ -146,7 +147,7 @@ dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab,
  *                 the paper's loop would make), the widest sequence counting
  *   workspace     DEVICE, 8-byte aligned, dyspec_build_tree_threshold_workspace_bytes()
  *                 bytes, REQUIRED (DYSPEC_WORKSPACE_TOO_SMALL otherwise)
- *   all other arguments as for dyspec_build_tree.
+ *   all other arguments, and the limits on vocab and N, as for dyspec_build_tree.
  * The call copies one small record per level back to the host and waits for it (it sizes
  * the next level's launch), so it returns with the tree complete and cannot be captured
  * in a graph.

@@ -16,7 +16,7 @@ import numpy as np
 from . import build as _build
 
 F32, BF16, BF16_WAVE = 0, 1, 0x101
-MAX_SEQ, MAX_NODES, MAX_VOCAB = 64, 1024, 32768
+MAX_SEQ, MAX_NODES, MAX_BUILD_NODES, MAX_VOCAB = 64, 2048, 1024, 32768
 WS_BUILD_TREE, WS_TREE_ATTN, WS_VERIFY = 0, 1, 2
 EXPORTS = ("dyspec_mask_words", "dyspec_workspace_bytes", "dyspec_status_string",
            "dyspec_build_tree", "dyspec_build_tree_threshold", "dyspec_build_tree_threshold_workspace_bytes",

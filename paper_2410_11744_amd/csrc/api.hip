@@ -6,7 +6,7 @@
 
 namespace dyspec {
 
-static dyspec_status check_batch(const dyspec_batch* b, bool need_prefix, SeqArgs* sa)
+static dyspec_status check_batch(const dyspec_batch* b, bool need_prefix, SeqArgs* sa, int max_nodes = DYSPEC_MAX_NODES)
 {
     if (!b || !b->node_offset) return DYSPEC_BAD_ARG;
     if (b->n_seq < 1 || b->n_seq > DYSPEC_MAX_SEQ) return DYSPEC_BAD_SHAPE;
@@ -15,7 +15,7 @@ static dyspec_status check_batch(const dyspec_batch* b, bool need_prefix, SeqArg
     sa->n_seq = b->n_seq;
     for (int s = 0; s < b->n_seq; ++s) {
         const int n = b->node_offset[s + 1] - b->node_offset[s];
-        if (n < 1 || n > DYSPEC_MAX_NODES) return DYSPEC_BAD_SHAPE;
+        if (n < 1 || n > max_nodes) return DYSPEC_BAD_SHAPE;
         sa->node_off[s] = b->node_offset[s];
         sa->prefix_len[s] = 0;
         sa->kv_off[s] = 0;
@@ -74,7 +74,7 @@ size_t dyspec_workspace_bytes(int32_t which, const dyspec_batch* batch, int32_t,
     // when it splits the prefix over several workgroups; verification needs none
     SeqArgs sa;
     if (which == DYSPEC_WS_BUILD_TREE)
-        return check_batch(batch, false, &sa) == DYSPEC_OK ? build_tree_workspace_bytes(sa.node_off[sa.n_seq]) : 0;
+        return check_batch(batch, false, &sa, DYSPEC_MAX_BUILD_NODES) == DYSPEC_OK ? build_tree_workspace_bytes(sa.node_off[sa.n_seq]) : 0;
     if (which == DYSPEC_WS_TREE_ATTN) {
         if (check_batch(batch, true, &sa) != DYSPEC_OK || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads != 0 ||
             (head_dim != 64 && head_dim != 128))
@@ -113,7 +113,7 @@ dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab, const 
                                 void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     SeqArgs sa;
-    const dyspec_status st = check_batch(batch, false, &sa);
+    const dyspec_status st = check_batch(batch, false, &sa, DYSPEC_MAX_BUILD_NODES);
     if (st != DYSPEC_OK) return st;
     if (!draft_logits || !draft_temp || !tree_ok(tree) || !est_value || !anc_mask || !n_built) return DYSPEC_BAD_ARG;
     if (vocab < 1) return DYSPEC_BAD_ARG;
@@ -134,7 +134,7 @@ dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab, const 
 size_t dyspec_build_tree_threshold_workspace_bytes(const dyspec_batch* batch)
 {
     SeqArgs sa;
-    return check_batch(batch, false, &sa) == DYSPEC_OK ? build_threshold_workspace_bytes(sa) : 0;
+    return check_batch(batch, false, &sa, DYSPEC_MAX_BUILD_NODES) == DYSPEC_OK ? build_threshold_workspace_bytes(sa) : 0;
 }
 
 dyspec_status dyspec_build_tree_threshold(const float* draft_logits, int32_t vocab, const dyspec_batch* batch,
@@ -144,7 +144,7 @@ dyspec_status dyspec_build_tree_threshold(const float* draft_logits, int32_t voc
                                           size_t workspace_bytes, void* hip_stream)
 {
     SeqArgs sa;
-    const dyspec_status st = check_batch(batch, false, &sa);
+    const dyspec_status st = check_batch(batch, false, &sa, DYSPEC_MAX_BUILD_NODES);
     if (st != DYSPEC_OK) return st;
     if (!draft_logits || !draft_temp || !threshold || !tree_ok(tree) || !est_value || !anc_mask || !n_built)
         return DYSPEC_BAD_ARG;

@@ -105,7 +105,7 @@ struct ExpandShared {
     int y, owner;                       // the drawn token, the thread that held it
     int last_live[kWaves];              // last thread of each wave with weight left, -1: none
     float fred[kWaves];
-    float u_draw[DYSPEC_MAX_NODES];     // the uniform draws of this node's samplings, by child rank
+    float u_draw[DYSPEC_MAX_BUILD_NODES];     // the uniform draws of this node's samplings, by child rank
 };
 
 // One workgroup per node of the current level: blockIdx.x = position in the level.  The node's
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(kBlock) void threshold_expand_kernel(const float* _
 }
 
 struct CommitShared {
-    int excl[DYSPEC_MAX_NODES + 1];
+    int excl[DYSPEC_MAX_BUILD_NODES + 1];
     int scan[kWaves];
 };
 

@@ -22,7 +22,7 @@
 
 namespace dyspec {
 
-constexpr int kMaxSlots = 2 * DYSPEC_MAX_NODES + 2;
+constexpr int kMaxSlots = 2 * DYSPEC_MAX_BUILD_NODES + 2;
 
 // Workspace of the cached form, per row (doubles): kMaxSeg * kBlock segment sums S[j][t],
 // kMaxSeg segment totals, the row maximum (already divided by the temperature), and one bit
@@ -65,13 +65,13 @@ __global__ __launch_bounds__(kBlock) void draft_row_sums_kernel(const float* __r
 struct BuildShared {
     double slot_value[kMaxSlots];       // < 0: closed
     int slot_parent[kMaxSlots];
-    int n_children[DYSPEC_MAX_NODES];
-    int last_child[DYSPEC_MAX_NODES];
-    int token[DYSPEC_MAX_NODES];
-    int first_child[DYSPEC_MAX_NODES];
-    int next_sibling[DYSPEC_MAX_NODES];
-    int depth[DYSPEC_MAX_NODES];
-    uint2 pk[DYSPEC_MAX_NODES];
+    int n_children[DYSPEC_MAX_BUILD_NODES];
+    int last_child[DYSPEC_MAX_BUILD_NODES];
+    int token[DYSPEC_MAX_BUILD_NODES];
+    int first_child[DYSPEC_MAX_BUILD_NODES];
+    int next_sibling[DYSPEC_MAX_BUILD_NODES];
+    int depth[DYSPEC_MAX_BUILD_NODES];
+    uint2 pk[DYSPEC_MAX_BUILD_NODES];
     CdfScratch cdf;
     double best_v[kWaves];
     int best_i[kWaves];
@@ -236,9 +236,9 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
 // lanes of different waves write the node down.
 constexpr int kRowState = kMaxSeg + 1;
 struct CachedShared {
-    int last_child[DYSPEC_MAX_NODES];
-    int depth[DYSPEC_MAX_NODES];
-    uint2 pk[DYSPEC_MAX_NODES];         // path keys of the nodes
+    int last_child[DYSPEC_MAX_BUILD_NODES];
+    int depth[DYSPEC_MAX_BUILD_NODES];
+    uint2 pk[DYSPEC_MAX_BUILD_NODES];         // path keys of the nodes
     double wave_tot[kWaves];            // per draw: the waves' sums of the picked segment
     int last_live[kWaves];              // last thread of each wave with weight left, -1: none
     uint2 next_key;                     // path key of the node this draw makes
@@ -255,10 +255,10 @@ struct CachedShared {
 };
 // LDS a workgroup may use on gfx950, less a margin; what CachedShared leaves of it holds the row states
 constexpr size_t kLdsPerWorkgroup = 160 * 1024 - 1024;
-static_assert(sizeof(CachedShared) + (size_t)DYSPEC_MAX_NODES * kRowState * sizeof(double) <= kLdsPerWorkgroup,
+static_assert(sizeof(CachedShared) + (size_t)DYSPEC_MAX_BUILD_NODES * kRowState * sizeof(double) <= kLdsPerWorkgroup,
               "the row states of the largest tree fit in LDS");
 constexpr int kSlotsPerThread = (kMaxSlots + kBlock - 1) / kBlock;
-static_assert(DYSPEC_MAX_NODES <= 1024 && DYSPEC_MAX_VOCAB <= (1 << 21), "a slot's parent and rank share one word");
+static_assert(DYSPEC_MAX_BUILD_NODES <= 1024 && DYSPEC_MAX_VOCAB <= (1 << 21), "a slot's parent and rank share one word");
 
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(

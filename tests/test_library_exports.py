@@ -101,3 +101,22 @@ def test_static_scratch_entry_point_refuses_oversized_batches_on_the_host():
     assert lib.dyspec_workspace_bytes(1, ctypes.byref(c), 0, 32, 32, 128) > (8 << 20)
     st = lib.dyspec_tree_attn_static_scratch(A, A, A, A, A, A, ctypes.byref(c), 32, 32, 128, binding.BF16, 0.1, A, None)
     assert st == -4
+
+
+def test_row_limits_per_entry_point():
+    """Attention, reorder and verification take trees of up to 2048 rows; the builders 1024."""
+    from paper_2410_11744_amd import binding
+    lib = binding.load_library()
+    A = 0x7f0000001000
+    F = ctypes.c_float
+    temps = (F * 1)(1.0)
+    tree = binding._Tree(*[A + 0x100 * k for k in range(6)])
+    ok, over = binding.Batch.from_sizes([2048], [10]), binding.Batch.from_sizes([2049], [10])
+    assert ok.mask_words == 32 and over.mask_words == 0
+    c = over._c()
+    assert lib.dyspec_tree_attn(A, A, A, A, A, A, ctypes.byref(c), 8, 2, 128, binding.BF16, 0.1, A, None, 0, None) == -2
+    assert lib.dyspec_verify(A, A, 100, ctypes.byref(c), ctypes.byref(tree), temps, temps, 0, 1, *([A] * 6), None, 0, None) == -2
+    c = binding.Batch.from_sizes([1025])._c()
+    assert lib.dyspec_build_tree(A, 100, ctypes.byref(c), temps, 0, ctypes.byref(tree), A, A, A, None, 0, None) == -2
+    assert lib.dyspec_workspace_bytes(0, ctypes.byref(c), 100, 8, 2, 128) == 0
+    assert lib.dyspec_build_tree_threshold_workspace_bytes(ctypes.byref(c)) == 0
