@@ -87,6 +87,15 @@ size_t dyspec_workspace_bytes(int32_t which, const dyspec_batch* batch, int32_t 
 const char* dyspec_status_string(dyspec_status s);
 
 /*
+ * dyspec_init -- optional one-time set-up on the CURRENT device: has the runtime load the
+ * kernels, raises their dynamic-LDS limits, takes the address of the static scratch array.
+ * Every entry point does what it needs of this at its first use; calling dyspec_init first
+ * moves those few milliseconds out of the first calls of a latency-sensitive loop.  Launches
+ * nothing, allocates nothing; idempotent and safe to call from several threads.
+ */
+dyspec_status dyspec_init(void);
+
+/*
  * dyspec_build_tree -- greedy fixed-budget construction of the draft token tree
  * (Algorithm 1; Section 4.2; Appendix A.1) plus the tree-attention mask (Section 2).
  *

@@ -4,10 +4,10 @@
 in ``include/dyspec.h``; this package only marshals arguments."""
 from .binding import (BF16, BF16_WAVE, F32, MAX_BUILD_NODES, MAX_NODES, Batch, BuiltTrees, DyspecError, ReorderedTrees, Tree, VerifyOutput,
                       dfs_reorder,
-                      build_tree, build_tree_threshold, load_library, probe_clock, probe_hbm_read, probe_mfma_bf16, status_string, tree_attn, tree_attn_layers,
+                      build_tree, build_tree_threshold, init, load_library, probe_clock, probe_hbm_read, probe_mfma_bf16, status_string, tree_attn, tree_attn_layers,
                       verify)
 
 __all__ = ["BF16", "BF16_WAVE", "F32", "MAX_BUILD_NODES", "MAX_NODES", "Batch", "BuiltTrees", "DyspecError", "ReorderedTrees", "Tree", "VerifyOutput",
            "dfs_reorder",
-           "build_tree", "build_tree_threshold", "load_library", "probe_clock", "probe_hbm_read", "probe_mfma_bf16", "status_string", "tree_attn", "tree_attn_layers",
+           "build_tree", "build_tree_threshold", "init", "load_library", "probe_clock", "probe_hbm_read", "probe_mfma_bf16", "status_string", "tree_attn", "tree_attn_layers",
            "verify"]

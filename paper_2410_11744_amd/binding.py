@@ -18,7 +18,7 @@ from . import build as _build
 F32, BF16, BF16_WAVE = 0, 1, 0x101
 MAX_SEQ, MAX_NODES, MAX_BUILD_NODES, MAX_VOCAB = 64, 2048, 1024, 32768
 WS_BUILD_TREE, WS_TREE_ATTN, WS_VERIFY = 0, 1, 2
-EXPORTS = ("dyspec_mask_words", "dyspec_workspace_bytes", "dyspec_status_string",
+EXPORTS = ("dyspec_init", "dyspec_mask_words", "dyspec_workspace_bytes", "dyspec_status_string",
            "dyspec_build_tree", "dyspec_build_tree_threshold", "dyspec_build_tree_threshold_workspace_bytes",
            "dyspec_dfs_reorder", "dyspec_tree_attn", "dyspec_tree_attn_static_scratch", "dyspec_tree_attn_layers",
            "dyspec_tree_attn_layers_workspace_bytes", "dyspec_verify", "dyspec_verify_bf16",
@@ -61,6 +61,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib = ctypes.CDLL(p)
     V, I32, U64, SZ, F = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint64, ctypes.c_size_t, ctypes.c_float
     PB, PT = ctypes.POINTER(_Batch), ctypes.POINTER(_Tree)
+    lib.dyspec_init.restype = I32
+    lib.dyspec_init.argtypes = []
     lib.dyspec_mask_words.restype = I32
     lib.dyspec_mask_words.argtypes = [PB]
     lib.dyspec_workspace_bytes.restype = SZ
@@ -99,6 +101,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     if path is None:
         _lib = lib
     return lib
+
+
+def init() -> None:
+    """dyspec_init on torch's current device: code loading and kernel attributes up front."""
+    _check(load_library().dyspec_init(), "dyspec_init")
 
 
 def status_string(status: int) -> str:

@@ -58,6 +58,32 @@ static int mask_words_of(const dyspec_batch* b)
 
 using namespace dyspec;
 
+// ---- the variant for callers that cannot allocate: partial results go to a static device array
+//
+// In host code the array's name is only a stand-in for the symbol; its device address comes from
+// hipGetSymbolAddress, once per device (every GPU holds its own copy at its own address), and that
+// address is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[DYSPEC_STATIC_SCRATCH_BYTES];
+
+static hipError_t static_scratch_address(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> per_device[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void* p = per_device[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // with `dev` current: this device's copy
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        per_device[dev].store(p, std::memory_order_release); // two racing first calls store the same address
+    }
+    *out = p;
+    return hipSuccess;
+}
+
 extern "C" {
 
 int32_t dyspec_mask_words(const dyspec_batch* batch)
@@ -92,6 +118,15 @@ size_t dyspec_tree_attn_layers_workspace_bytes(const dyspec_batch* batch, int32_
         n_q_heads % n_kv_heads != 0 || (head_dim != 64 && head_dim != 128))
         return 0;
     return tree_attn_workspace_bytes(sa, n_q_heads, n_kv_heads, head_dim, n_layers);
+}
+
+dyspec_status dyspec_init(void)
+{
+    void* scratch_address = nullptr;
+    if (prepare_tree_attn() != hipSuccess || prepare_build_tree() != hipSuccess || prepare_build_threshold() != hipSuccess ||
+        static_scratch_address(&scratch_address) != hipSuccess)
+        return DYSPEC_HIP_ERROR;
+    return DYSPEC_OK;
 }
 
 const char* dyspec_status_string(dyspec_status s)
@@ -247,32 +282,6 @@ dyspec_status dyspec_tree_attn(const void* q, const void* k_prefix, const void* 
 {
     return tree_attn_common(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch, 1, 0, 0, 0, n_q_heads,
                             n_kv_heads, head_dim, dtype, softmax_scale, out, workspace, workspace_bytes, hip_stream);
-}
-
-// ---- the variant for callers that cannot allocate: partial results go to a static device array
-//
-// In host code the array's name is only a stand-in for the symbol; its device address comes from
-// hipGetSymbolAddress, once per device (every GPU holds its own copy at its own address), and that
-// address is what the kernels receive.
-static __device__ __align__(256) unsigned char scratch[DYSPEC_STATIC_SCRATCH_BYTES];
-
-static hipError_t static_scratch_address(void** out)
-{
-    constexpr int kMaxDevices = 64;
-    static std::atomic<void*> per_device[kMaxDevices];
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
-    void* p = per_device[dev].load(std::memory_order_acquire);
-    if (!p) {
-        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // with `dev` current: this device's copy
-        if (e != hipSuccess) return e;
-        if (!p) return hipErrorInvalidSymbol;
-        per_device[dev].store(p, std::memory_order_release); // two racing first calls store the same address
-    }
-    *out = p;
-    return hipSuccess;
 }
 
 dyspec_status dyspec_tree_attn_static_scratch(const void* q, const void* k_prefix, const void* v_prefix,

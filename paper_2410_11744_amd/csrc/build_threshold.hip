@@ -307,6 +307,17 @@ __global__ __launch_bounds__(kBlock) void threshold_commit_kernel(SeqArgs sa, ui
     }
 }
 
+// the expanding workgroups keep a row of logits and a token bitmap in dynamic LDS: raised to the
+// largest vocabulary once
+hipError_t prepare_build_threshold()
+{
+    static std::atomic<unsigned long long> done_vec{0}, done_scalar{0};
+    constexpr int bytes = DYSPEC_MAX_VOCAB * 4 + DYSPEC_MAX_VOCAB / 8;
+    hipError_t e = raise_dynamic_lds_once(reinterpret_cast<const void*>(&threshold_expand_kernel<true>), bytes, done_vec);
+    if (e != hipSuccess) return e;
+    return raise_dynamic_lds_once(reinterpret_cast<const void*>(&threshold_expand_kernel<false>), bytes, done_scalar);
+}
+
 hipError_t launch_build_threshold(const float* draft_logits, int V, const SeqArgs& sa, const double* threshold,
                                   uint64_t seed, const dyspec_tree& tree, float* est_value, uint64_t* anc_mask,
                                   int mask_words, int* n_built, int* n_levels, void* workspace, hipStream_t stream)
@@ -317,9 +328,7 @@ hipError_t launch_build_threshold(const float* draft_logits, int V, const SeqArg
     // the expanding workgroups keep their row (4 bytes per token) and a bitmap (1 bit per token) in LDS
     const int Vpad = (V + 31) & ~31;
     const size_t dyn_bytes = (size_t)Vpad * 4 + Vpad / 8;
-    hipError_t ea = (V % 4 == 0)
-        ? hipFuncSetAttribute(reinterpret_cast<const void*>(&threshold_expand_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_bytes)
-        : hipFuncSetAttribute(reinterpret_cast<const void*>(&threshold_expand_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_bytes);
+    const hipError_t ea = prepare_build_threshold();
     if (ea != hipSuccess) return ea;
     threshold_init_kernel<<<sa.n_seq, 256, 0, stream>>>(sa, tree, est_value, anc_mask, mask_words, n_built, w);
     int frontier = 1, levels = 0;                       // widest level over the sequences

@@ -489,6 +489,16 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
     if (tid == 0) n_built[seq] = n;
 }
 
+// the cached builder keeps kRowState doubles per row in dynamic LDS: raised to the largest tree once
+hipError_t prepare_build_tree()
+{
+    static std::atomic<unsigned long long> done_vec{0}, done_scalar{0};
+    constexpr int bytes = DYSPEC_MAX_BUILD_NODES * kRowState * (int)sizeof(double);
+    hipError_t e = raise_dynamic_lds_once(reinterpret_cast<const void*>(&build_tree_cached_kernel<true>), bytes, done_vec);
+    if (e != hipSuccess) return e;
+    return raise_dynamic_lds_once(reinterpret_cast<const void*>(&build_tree_cached_kernel<false>), bytes, done_scalar);
+}
+
 size_t build_tree_workspace_bytes(int total_rows) { return (size_t)total_rows * kRowSumDoubles * sizeof(double); }
 
 hipError_t launch_build_tree(const float* draft_logits, int V, const SeqArgs& sa, uint64_t seed,
@@ -502,9 +512,7 @@ hipError_t launch_build_tree(const float* draft_logits, int V, const SeqArgs& sa
         int widest = 0;
         for (int s = 0; s < sa.n_seq; ++s) widest = max(widest, sa.node_off[s + 1] - sa.node_off[s]);
         const size_t dyn_bytes = (size_t)widest * kRowState * sizeof(double);
-        const void* fn = V % 4 == 0 ? reinterpret_cast<const void*>(&build_tree_cached_kernel<true>)
-                                    : reinterpret_cast<const void*>(&build_tree_cached_kernel<false>);
-        hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_bytes);
+        const hipError_t ea = prepare_build_tree();
         if (ea != hipSuccess) return ea;
         if (V % 4 == 0) {
             draft_row_sums_kernel<true><<<rows, kBlock, 0, stream>>>(draft_logits, V, sa, ws);

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/dyspec.h"
 
 namespace dyspec {
@@ -70,6 +72,26 @@ constexpr size_t kAttnCounterBytes = DYSPEC_ATTN_COUNTER_BYTES;     // arrival c
 // splits the matrix-core kernel would like for this batch, and the workspace that takes
 int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv, int layers);
 size_t tree_attn_workspace_bytes(const SeqArgs& sa, int Hq, int Hkv, int d, int layers);
+
+// Raises a kernel's dynamic-LDS limit to `bytes`, once per device (`done`: one bit per device,
+// owned by the call site).  Touching the kernel this way also makes the runtime load its code.
+inline hipError_t raise_dynamic_lds_once(const void* kernel, int bytes, std::atomic<unsigned long long>& done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
+
+// One-time set-up of each source file's kernels on the current device (what dyspec_init calls;
+// the launchers do the same at first use).
+hipError_t prepare_tree_attn();
+hipError_t prepare_build_tree();
+hipError_t prepare_build_threshold();
 
 enum : uint32_t { KIND_PATH = 0, KIND_BUILD = 1, KIND_ACCEPT = 2, KIND_RESID = 3 };
 

@@ -890,21 +890,19 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     }
 }
 
+hipError_t prepare_tree_attn()
+{
+    static std::atomic<unsigned long long> done128{0}, done64{0};
+    hipError_t e = raise_dynamic_lds_once(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<128, kQB>), Geo<128>::kLdsBytes + 16, done128);
+    if (e != hipSuccess) return e;
+    return raise_dynamic_lds_once(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<64, kQB>), Geo<64>::kLdsBytes + 16, done64);
+}
+
 template <int D, int QB>
 static hipError_t launch_one(const AttnArgs& a, const SeqArgs& sa, int tiles, hipStream_t stream)
 {
-    // the kernel needs more dynamic LDS than the default limit: raised once per device
-    static std::atomic<unsigned long long> raised{0};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    const hipError_t e = prepare_tree_attn();              // the kernel needs more dynamic LDS than the default limit
     if (e != hipSuccess) return e;
-    const unsigned long long bit = 1ull << (dev & 63);
-    if (!(raised.load(std::memory_order_acquire) & bit)) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tree_attn_mfma_kernel<D, QB>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, Geo<D>::kLdsBytes + 16);
-        if (e != hipSuccess) return e;
-        raised.fetch_or(bit, std::memory_order_release);
-    }
     tree_attn_mfma_kernel<D, QB><<<dim3(tiles * a.Hkv, a.splits, a.layers), 64 * 2 * (4 / QB), Geo<D>::kLdsBytes + 16, stream>>>(a, sa);
     return hipGetLastError();
 }
