@@ -27,10 +27,22 @@ if ROOT not in sys.path:
 METRIC = "verified tree tokens/s (tree-attn + verify), 70B shape, 1 GPU; % of HBM peak"
 PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
-# HBM bytes per tree-attention launch from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each
-# scaled by what the same counter reads for a 1 GiB device copy (profiles/bench_*_rocprofv3.md).
-TRAFFIC_BYTES_PER_LAUNCH = {"llama2_70b": 36344714,
-                            "llama2_70b_n32": 26385830 + 9207441}      # split kernel + combine kernel
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per tree-attention launch from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each
+    scaled by what the same counter reads for a 1 GiB device copy) summarised under profiles/, and the commit
+    they were measured at: one line per workload in profiles/hbm_traffic_per_launch.txt, rewritten whenever
+    the profiles are regenerated.  (None, None) for a workload that was not profiled."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 3 and not line.startswith("#") and parts[0] == workload:
+                    return int(parts[1]), parts[2]
+    except OSError:
+        pass
+    return None, None
 
 
 def tree_only_sweep(dy, synth, torch, np, dev) -> int:
@@ -386,7 +398,8 @@ def main() -> int:
             roofline["frac_of_measured_ceiling"] = round(gbs / ceilings["hbm_read_gbs"], 4)
     if args.batched_layers:        # one launch covers all layers: figures below stay per layer (time / layers)
         roofline["note"] = f"one launch for {cfg.layers} layers; launch_us, flops and bytes are per layer"
-    roofline.update({"traffic": None if args.batched_layers else TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+    traffic, traffic_commit = (None, None) if args.batched_layers else measured_traffic(args.workload)
+    roofline.update({"traffic": traffic, "traffic_measured_at_commit": traffic_commit,
                      "launch_us": round(launch_ms * 1e3, 2),
                      "flops_per_launch": flops_per_launch, "algorithmic_bytes_per_launch": bytes_attn_launch,
                      "achieved_tflops": round(achieved_tflops, 2)})
@@ -429,8 +442,18 @@ def main() -> int:
                           cfg.seed, seq=s)
             off += n
         t_verify = time.perf_counter() - t
+        # the same oracle on one thread, on a sample a tenth as long (figure beside the all-threads one)
+        all_threads = oracle.num_threads()
+        oracle.set_num_threads(1)
+        rows_1 = max(64, int(per_pass * max(args.cpu_seconds, 1.0) * 0.1 / max(t_rows / max(n_rows, 1) * per_pass * all_threads, 1e-6)))
+        rows_1 = min(rows_1, N0 * cfg.n_q_heads)
+        t_1 = run(rows_1)
+        oracle.set_num_threads(all_threads)
+        t_attn_step_1 = t_1 / rows_1 * (N0 * cfg.n_q_heads) * (visible / vis0) * cfg.layers
         cpu = {"value": round(n_tokens / (t_attn_step + t_verify), 3), "unit": "tokens/s",
-               "cores": oracle.num_threads(), "kind": "oracle",
+               "cores": all_threads, "kind": "oracle",
+               "one_thread_value": round(n_tokens / (t_attn_step_1 + t_verify), 4),
+               "one_thread_sample": f"{rows_1} row evaluations in {t_1:.2f} s on one thread, scaled the same way",
                "sample": f"tree attention: {n_rows} row evaluations on layer 0's tensors (of {total_rows * cfg.layers} "
                          f"(row, head, layer) rows per step) in {t_rows:.2f} s, scaled by row count; "
                          f"verification walk in full ({t_verify * 1e3:.1f} ms)"}

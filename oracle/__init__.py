@@ -50,6 +50,11 @@ def num_threads() -> int:
     return int(_L().oracle_num_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """Threads for the attention routines from now on (timing only; results do not depend on it)."""
+    _L().oracle_set_num_threads(ctypes.c_int(int(n)))
+
+
 def _p(a, ct):
     return a.ctypes.data_as(ctypes.POINTER(ct))
 

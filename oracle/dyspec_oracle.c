@@ -50,6 +50,17 @@ int oracle_num_threads(void)
 #endif
 }
 
+/* Sets the number of threads for the attention routines (timing only: results do not depend
+ * on it, every row is computed by one thread on its own). */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /* ------------------------------------------------------------------ Philox4x32-10 */
 
 static void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
