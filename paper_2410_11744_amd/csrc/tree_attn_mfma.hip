@@ -192,7 +192,10 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     const char* vt = static_cast<const char*>(a.vt) + kvt_off;
     const __bf16* q_layer = reinterpret_cast<const __bf16*>(static_cast<const char*>(a.q) + (size_t)layer * a.q_stride);
 
-    // ---- Q fragments (B operand: lane holds query n, head-dim slice 16*kk + 8*g .. +7)
+    // ---- Q fragments (B operand: lane holds query n, head-dim slice 16*kk + 8*g .. +7).  The
+    //      workgroup's 128 query rows come through LDS like a K tile (see the prologue) and are
+    //      read into these registers once.
+    static_assert(QB == 1, "the Q staging below is written for one query block per wave");
     bf16x8 qf[QB][KK];
     int rq[QB];
     const uint64_t* mrow[QB];
@@ -200,11 +203,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     for (int qb = 0; qb < QB; ++qb) {
         rq[qb] = r0 + 32 * QB * wq + 32 * qb + n;
         const int rc = min(rq[qb], rows - 1);
-        const int j = rc / G, h = kvh * G + rc % G;
-        const __bf16* qrow = q_layer + ((size_t)(node_base + j) * a.Hq + h) * D;
-        mrow[qb] = a.mask + (size_t)(node_base + j) * a.mask_words;
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) qf[qb][kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * g);
+        mrow[qb] = a.mask + (size_t)(node_base + rc / G) * a.mask_words;
     }
 
     floatx16 acc[DB][QB];                        // O^T: [32-wide head-dim block][query block]
@@ -518,6 +517,7 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     //      the tree, so the set is agreed on first, when it can shorten the walk at all.
     uint32_t* const tile_flag = reinterpret_cast<uint32_t*>(lds + L::kLdsBytes);
     auto ballot_tiles = [=]() __attribute__((always_inline)) {
+        if (wk != 0) return;                               // the wk == 1 waves hold the same rows
         uint32_t mine = 0u;
         for (int tt = 0; tt < nTt; ++tt) {
             uint64_t w = 0ull;
@@ -548,26 +548,42 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     auto first_tiles = [=](int v) __attribute__((always_inline)) -> int {
         return v < nPl ? p_begin + v : kth_tile(first_set, v - nPl);
     };
-    if constexpr (NW == 8) {
-        // position mm = 2*slot + parity
+    // The workgroup's 128 query rows go to LDS first, into V slot 1 (which no V tile needs before the
+    // middle of step 0), laid out like two K tiles: row R at R * kRowBytes, chunks swizzled as K's.
+    // A row past the end repeats the last one.
+    const uint32_t q_lds = lds0 + L::kVBase + L::kSlotBytes;
+    {
+        constexpr int QLW = (2 * kKeysPerTile / L::kRowsPerLoad) / NW;     // wave-wide loads per wave
+        const char* q_seq = reinterpret_cast<const char*>(q_layer) + (size_t)node_base * a.Hq * D * 2;
+#pragma unroll
+        for (int x = 0; x < QLW; ++x) {
+            const int X = wave * QLW + x;
+            const int R = X * L::kRowsPerLoad + ld_lrow;
+            const int rc = min(r0 + R, rows - 1);
+            const int j = rc / G, h = kvh * G + rc % G;
+            const uint32_t off = (uint32_t)(j * a.Hq + h) * (uint32_t)(D * 2) + 16u * (uint32_t)(ld_cpos ^ L::swz_k(R));
+            direct_load_16(q_seq, off, q_lds + X * 1024);
+        }
+    }
+    // K of walk positions 0..3 (position mm = 2*slot + parity, two waves per matrix) and V of
+    // positions 0 and 1.  Waves 0..3 hold what the first product needs (positions 0 and 1 of K) and
+    // issue it now; waves 4..7 hold the rest and issue it behind the next barrier, so that it queues
+    // up in the CU's address path after the urgent loads instead of among them.
+    static_assert(NW == 8, "the prologue's load plan is written for eight waves");
+    auto issue_first_loads = [=]() __attribute__((always_inline)) {
         int voff_k[4];
         lane_offsets(false, voff_k);
         issue_tile(kp, kt, voff_k, first_tiles(ld_mm), lds0 + ld_mm * L::kMatBytes + ld_x0 * 1024);
-    } else {
-        // one matrix per wave: K positions 0..3 go to waves 0..3
-        int voff_k[4];
-        lane_offsets(false, voff_k);
-        issue_tile(kp, kt, voff_k, first_tiles(wave), lds0 + wave * L::kMatBytes);
-    }
-    if (ld_is_v) issue_tile(st_prefix, st_tree, ld_voff, first_tiles(ld_par), st_dst);
+        if (ld_is_v) issue_tile(st_prefix, st_tree, ld_voff, first_tiles(ld_par), st_dst);
+    };
+    if (!ld_is_v) issue_first_loads();
     // The steady-state half step always runs all three parts; what it reads for a half that does
-    // not exist must therefore be harmless.  V of a tile that is not loaded starts as zeros (all
-    // of slot 1, and a matrix of slot 0 whose walk position does not exist) and the numerators
-    // start as zeros: 0 * 0 adds nothing to the accumulators.  K of a tile that does not exist is
-    // whatever the slot held, and the scores it gives are masked.
+    // not exist must therefore be harmless.  The numerators start as zeros, and so do numerators of
+    // masked keys; the V rows they meet must be finite: V slot 1 holds the query rows until a V tile
+    // replaces them, a matrix of slot 0 whose walk position does not exist is cleared here.  K of a
+    // tile that does not exist is whatever the slot held, and the scores it gives are masked.
     {
         const uint4 z = { 0u, 0u, 0u, 0u };
-        for (int x = tid; x < L::kSlotBytes / 16; x += 64 * NW) reinterpret_cast<uint4*>(lds + L::kVBase + L::kSlotBytes)[x] = z;
 #pragma unroll
         for (int par = 0; par < 2; ++par)
             if (first_tiles(par) >= nT)
@@ -584,9 +600,23 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
                     for (int w = 0; w < 4; ++w) pbw[bu][qb][ts][w] = 0u;
     }
     __syncthreads();
+    if (ld_is_v) issue_first_loads();
     if (squeeze) ballot_tiles();
-    wait_direct_loads();
+    // The first product needs the query rows and K of walk positions 0 and 1, which waves 0..3
+    // loaded (every wave its share of the query rows first).  Waves 4..7 went on to K of positions
+    // 2, 3 and V of positions 0, 1, needed from the middle of step 0 on: they wait for their query
+    // rows only, i.e. until just the 2 * LPW loads issued after those are still in flight.
+    {
+        const bool later_all = ld_is_v && first_tiles(ld_mm) < nT && first_tiles(ld_par) < nT;
+        if (later_all) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * LPW) : "memory");
+        else wait_direct_loads();
+    }
     __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        const int R = 32 * wq + n;
+        qf[0][kk] = *(lds_bf16x8)(uint32_t)(q_lds + R * L::kRowBytes + (((2 * kk + g) ^ L::swz_k(R)) << 4));
+    }
     const uint32_t active = squeeze ? (uint32_t)__builtin_amdgcn_readfirstlane((int)*tile_flag) : first_set;
     const int nAct = __builtin_popcount(active);
     const int nIt = (nPl + nAct + 1) / 2;                  // tiles per wave (the last odd one may not exist)
