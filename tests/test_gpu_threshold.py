@@ -76,7 +76,13 @@ def test_threshold_builder_matches_oracle(dy, nodes, V, sigma, temps, thresholds
     built, levels = dy.build_tree_threshold(dd, batch, temps, thresholds, seed)
     assert compare_threshold_trees(built, batch, d, temps, thresholds, seed) == len(nodes), \
         "an oracle decision had a margin below 1e-9: pick another seed"
-    assert levels >= 1
+    # levels expanded (the draft model calls of the paper's loop), the deepest sequence counting
+    want_levels = 0
+    for s in range(batch.n_seq):
+        a, b = int(batch.node_offset[s]), int(batch.node_offset[s + 1])
+        want_levels = max(want_levels, oracle.threshold_tree(d[a:b], b - a, float(np.float32(temps[s])), float(thresholds[s]),
+                                                             seed, seq=s).n_levels)
+    assert levels == want_levels
 
 
 def test_by_hand_uniform_three_tokens(dy):
