@@ -233,6 +233,8 @@ static dyspec_status tree_attn_common(const void* q, const void* k_prefix, const
     for (int s = 0; s < sa.n_seq; ++s) any_prefix |= sa.prefix_len[s] > 0;
     if (any_prefix && (!k_prefix || !v_prefix)) return DYSPEC_BAD_ARG;
     if (n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads != 0) return DYSPEC_BAD_SHAPE;
+    // the kernels address a sequence's query rows, and the 64 key rows of a tile, with 32-bit byte offsets
+    if ((long long)DYSPEC_MAX_NODES * n_q_heads * (head_dim > 0 ? head_dim : 1) * 4 > 0x7fffffffLL) return DYSPEC_BAD_SHAPE;
     if (!(softmax_scale > 0.0f)) return DYSPEC_BAD_ARG;
     // 16-byte pieces of every tensor are loaded at once (and moved to LDS without passing through
     // registers); mask rows are 8-byte words; the workspace holds float4 partial rows

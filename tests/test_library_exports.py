@@ -65,6 +65,8 @@ def test_misaligned_pointers_are_refused_before_any_launch():
         assert attn(**{name: A + 8}) == -1, name           # tensors and workspace: 16 bytes
     assert attn(mask=A + 4) == -1                           # mask words: 8 bytes
     assert attn(q=A + 8, dtype=binding.F32) == -1
+    # more query heads than the kernels' 32-bit row offsets reach: a shape error, not a wrong address
+    assert lib.dyspec_tree_attn(A, A, A, A, A, A, ctypes.byref(c), 4096, 2, 128, binding.BF16, 0.1, A, None, 0, None) == -2
     assert lib.dyspec_tree_attn_layers(A, A, A + 2, A, A, A, ctypes.byref(c), 3, 1 << 20, 1 << 20, 1 << 20, 8, 2, 128,
                                        binding.BF16, 0.1, A, None, 0, None) == -1
 
