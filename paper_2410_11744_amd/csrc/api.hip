@@ -123,7 +123,7 @@ size_t dyspec_tree_attn_layers_workspace_bytes(const dyspec_batch* batch, int32_
 dyspec_status dyspec_init(void)
 {
     void* scratch_address = nullptr;
-    if (prepare_tree_attn() != hipSuccess || prepare_build_tree() != hipSuccess || prepare_build_threshold() != hipSuccess ||
+    if (prepare_tree_attn() != hipSuccess || prepare_build_tree() != hipSuccess || prepare_build_threshold() != hipSuccess || prepare_verify() != hipSuccess ||
         static_scratch_address(&scratch_address) != hipSuccess)
         return DYSPEC_HIP_ERROR;
     return DYSPEC_OK;

@@ -92,6 +92,7 @@ inline hipError_t raise_dynamic_lds_once(const void* kernel, int bytes, std::ato
 hipError_t prepare_tree_attn();
 hipError_t prepare_build_tree();
 hipError_t prepare_build_threshold();
+hipError_t prepare_verify();
 
 enum : uint32_t { KIND_PATH = 0, KIND_BUILD = 1, KIND_ACCEPT = 2, KIND_RESID = 3 };
 

@@ -287,15 +287,28 @@ __global__ __launch_bounds__(kStatThreads) void softmax_stats_stream_pieces_kern
     }
 }
 
+// exp(x) for x <= 0 through the hardware's exp2 (inputs below -126/log2(e) give 0, which is what a
+// probability that small is here): one multiply and one v_exp_f32, about 1e-7 |x| of relative
+// error, against some twenty instructions of the library routine -- a thread turns 128 logits
+// into probabilities per visited node.
+__device__ __forceinline__ float exp_fast(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
+
+// LDS of the walk.  Static part: scratch of the reductions.  Dynamic part: the draft row of the
+// node being decided, as unnormalised weights exp(logit/T - max) indexed by token (what is left of
+// D after the children rejected so far is D_lds[x] * scale), then the sequence's tree links as
+// 16-bit values (tokens < 32768, nodes < 2048; -1 = none).  The target row R stays in registers.
 struct WalkShared {
     CdfScratch cdf;
     float fred[kWaves * 2];
-    int token[DYSPEC_MAX_NODES];
-    int first_child[DYSPEC_MAX_NODES];
-    int next_sibling[DYSPEC_MAX_NODES];
-    float4 stats[DYSPEC_MAX_NODES];
     float bcast[2];
 };
+// (the row's place also stages the partial sums of the final draw: at least kStageDoubles doubles)
+__host__ __device__ __forceinline__ size_t walk_row_bytes(int V)
+{
+    const size_t row = (size_t)((V + 3) & ~3) * sizeof(float), stage = (size_t)kStageDoubles * sizeof(double);
+    return row > stage ? row : stage;
+}
+static size_t walk_lds_bytes(int V, int widest) { return walk_row_bytes(V) + 3 * (size_t)((widest + 7) & ~7) * sizeof(short); }
 
 template <bool VEC, typename T>
 __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
@@ -306,61 +319,75 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
     int* __restrict__ final_token, float* __restrict__ min_margin)
 {
     __shared__ WalkShared sh;
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn[];
     const int tid = threadIdx.x;
     const int seq = blockIdx.x;
     const int base = sa.node_off[seq];
     const int N = sa.node_off[seq + 1] - base;
     const bool greedy = sa.temp_t[seq] == 0.0f;                  // target row = all mass on stats.w
     const float inv_td = 1.0f / sa.temp_d[seq], inv_tt = greedy ? 1.0f : 1.0f / sa.temp_t[seq];
+    float* const D_lds = reinterpret_cast<float*>(dyn);
+    const int Npad = (N + 7) & ~7;
+    short* const l_token = reinterpret_cast<short*>(dyn + walk_row_bytes(V));
+    short* const l_child = l_token + Npad;
+    short* const l_next = l_child + Npad;
     for (int i = tid; i < N; i += kBlock) {
-        sh.token[i] = tree.token[base + i];
-        sh.first_child[i] = tree.first_child[base + i];
-        sh.next_sibling[i] = tree.next_sibling[base + i];
-        sh.stats[i] = *reinterpret_cast<const float4*>(row_stats + 4 * (size_t)(base + i));
+        const int tk = tree.token[base + i], fc = tree.first_child[base + i], ns = tree.next_sibling[base + i];
+        l_token[i] = (short)((tk >= 0 && tk < V) ? tk : -1);     // anything else is no token: ratio 0
+        l_child[i] = (short)((fc >= 0 && fc < N) ? fc : -1);
+        l_next[i] = (short)((ns >= 0 && ns < N) ? ns : -1);
     }
     __syncthreads();
 
-    // probability of token y under row `node`: draft (.x) and target (.y)
-    auto prob_pair = [&](int node, int y) {
-        const float4 st = sh.stats[node];
-        const float d = expf(logit_to_float(draft_logits[(size_t)(base + node) * V + y]) * inv_td - st.x) / st.y;
-        const float r = greedy ? ((float)y == st.w ? 1.0f : 0.0f)
-                               : expf(logit_to_float(target_logits[(size_t)(base + node) * V + y]) * inv_tt - st.z) / st.w;
-        return make_float2(d, r);
-    };
     auto ratio_of = [](float d, float r) { return (d > 0.0f) ? r / d : (r > 0.0f ? INFINITY : 0.0f); };
 
     int cur = 0, na = 0, fin = -1;
     uint2 pk = root_key((uint32_t)seq);
     float margin = INFINITY;
     for (int steps = 0; steps < N; ++steps) {            // a path has fewer than N edges
-        int c = sh.first_child[cur];
-        const bool leaf = c < 0 || c >= N;
+        int c = l_child[cur];
+        const bool leaf = c < 0;
         int next = -1;
         uint2 pk_next = pk;
         bool rows_loaded = false;
-        float D[kMaxSeg][4], R[kMaxSeg][4];
+        float R[kMaxSeg][4];
+        // the node's statistics: one 16-byte load, on its way together with the first child's logits
+        const float4 st = *reinterpret_cast<const float4*>(row_stats + 4 * (size_t)(base + cur));
+        float scale_d = 0.0f;                             // what is left of D = D_lds * scale_d
+        // R <- softmax of the target row (registers); with want_draft, D_lds <- the draft row's weights
         auto load_rows = [&](bool want_draft) {
-            const float4 st = sh.stats[cur];
+            float X[kMaxSeg][4];
+            if (want_draft) {
+                load_row<VEC, T>(draft_logits + (size_t)(base + cur) * V, V, X);
+#pragma unroll
+                for (int j = 0; j < kMaxSeg; ++j) {
+                    const int i0 = tok_index(j, 0);
+                    if (i0 < V)                           // V is padded to a multiple of 4 in LDS; logits past V read as -inf
+                        *reinterpret_cast<float4*>(D_lds + i0) = make_float4(exp_fast(X[j][0] * inv_td - st.x), exp_fast(X[j][1] * inv_td - st.x),
+                                                                             exp_fast(X[j][2] * inv_td - st.x), exp_fast(X[j][3] * inv_td - st.x));
+                }
+                scale_d = 1.0f / st.y;
+            }
             if (!greedy) load_row<VEC, T>(target_logits + (size_t)(base + cur) * V, V, R);
-            if (want_draft) load_row<VEC, T>(draft_logits + (size_t)(base + cur) * V, V, D);
-            const float id = 1.0f / st.y, it = greedy ? 0.0f : 1.0f / st.w;
+            const float it = greedy ? 0.0f : 1.0f / st.w;
             const int top = greedy ? (int)st.w : -1;
 #pragma unroll
             for (int j = 0; j < kMaxSeg; ++j)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    R[j][e] = greedy ? (tok_index(j, e) == top ? 1.0f : 0.0f) : expf(R[j][e] * inv_tt - st.z) * it;
-                    D[j][e] = want_draft ? expf(D[j][e] * inv_td - st.x) * id : 0.0f;
-                }
+                for (int e = 0; e < 4; ++e)
+                    R[j][e] = greedy ? (tok_index(j, e) == top ? 1.0f : 0.0f) : exp_fast(R[j][e] * inv_tt - st.z) * it;
         };
         if (!leaf) {
             // ---- first child: two logits and the row statistics decide
             {
-                const int y = sh.token[c];
-                const bool y_ok = y >= 0 && y < V;
-                const float2 pr = y_ok ? prob_pair(cur, y) : make_float2(0.0f, 0.0f);
-                const float ratio = ratio_of(pr.x, pr.y);
+                const int y = l_token[c];
+                float d = 0.0f, r = 0.0f;
+                if (y >= 0) {
+                    d = exp_fast(logit_to_float(draft_logits[(size_t)(base + cur) * V + y]) * inv_td - st.x) / st.y;
+                    r = greedy ? ((float)y == st.w ? 1.0f : 0.0f)
+                               : exp_fast(logit_to_float(target_logits[(size_t)(base + cur) * V + y]) * inv_tt - st.z) / st.w;
+                }
+                const float ratio = ratio_of(d, r);
                 const uint2 pk_n = child_key(seed, pk, 0u);
                 const float u = u01(seed, pk_n, 0u, KIND_ACCEPT);
                 margin = fminf(margin, fabsf(u - ratio));
@@ -371,22 +398,24 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
             if (next < 0) {
                 load_rows(true);
                 rows_loaded = true;
+                __syncthreads();                              // D_lds is complete
                 uint32_t rank = 0;
-                for (int guard = 0; c >= 0 && c < N && guard < N; ++guard) {
-                    const int y = sh.token[c];
-                    const bool mine = y >= 0 && y < V && ((y % kSeg) >> 2) == tid;
+                for (int guard = 0; c >= 0 && guard < N; ++guard) {
+                    const int y = l_token[c];
+                    const float dy = y >= 0 ? D_lds[y] : 0.0f;        // the same word for every thread
                     if (rank > 0) {
-                        // ratio seen by this child after its earlier siblings were rejected
-                        if (mine) {
+                        // ratio seen by this child after its earlier siblings were rejected: R[y] sits in one
+                        // thread's registers
+                        if (y >= 0 && ((y % kSeg) >> 2) == tid) {
 #pragma unroll
                             for (int j = 0; j < kMaxSeg; ++j)
 #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    if (j == y / kSeg && e == (y & 3)) { sh.bcast[0] = D[j][e]; sh.bcast[1] = R[j][e]; }
+                                    if (j == y / kSeg && e == (y & 3)) sh.bcast[1] = R[j][e];
                         }
-                        if (!(y >= 0 && y < V) && tid == 0) { sh.bcast[0] = 0.0f; sh.bcast[1] = 0.0f; }
+                        if (y < 0 && tid == 0) sh.bcast[1] = 0.0f;
                         __syncthreads();
-                        const float ratio = ratio_of(sh.bcast[0], sh.bcast[1]);
+                        const float ratio = ratio_of(dy * scale_d, sh.bcast[1]);
                         const uint2 pk_n = child_key(seed, pk, rank);
                         const float u = u01(seed, pk_n, 0u, KIND_ACCEPT);
                         margin = fminf(margin, fabsf(u - ratio));
@@ -394,41 +423,45 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
                         if (u < ratio) { next = c; pk_next = pk_n; break; }
                     }
                     // reject child c: R <- norm(max(R-D,0)) with D as it stands, then y leaves D
-                    float res[2] = { 0.0f, 0.0f };          // mass of relu(R-D), mass left in D
-                    float dy_old = 0.0f;
+                    float res[2] = { 0.0f, 0.0f };          // mass of relu(R-D); weight in D_lds
 #pragma unroll
-                    for (int j = 0; j < kMaxSeg; ++j)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float d = D[j][e], r = R[j][e];
-                            if (mine && j == y / kSeg && e == (y & 3)) { dy_old = d; D[j][e] = 0.0f; }
-                            res[0] += fmaxf(r - d, 0.0f);
-                            res[1] += D[j][e];
+                    for (int j = 0; j < kMaxSeg; ++j) {
+                        const int i0 = tok_index(j, 0);
+                        if (i0 < V) {
+                            const float4 dv = *reinterpret_cast<const float4*>(D_lds + i0);
+                            res[0] += fmaxf(fmaf(-scale_d, dv.x, R[j][0]), 0.0f) + fmaxf(fmaf(-scale_d, dv.y, R[j][1]), 0.0f);
+                            res[0] += fmaxf(fmaf(-scale_d, dv.z, R[j][2]), 0.0f) + fmaxf(fmaf(-scale_d, dv.w, R[j][3]), 0.0f);
+                            res[1] += (dv.x + dv.y) + (dv.z + dv.w);
                         }
+                    }
                     block_sum<float, 2>(res, sh.fred);
                     if (res[0] > 0.0f) {                     // else R == D: keep R (no reject can reach here)
                         const float ir = 1.0f / res[0];
 #pragma unroll
-                        for (int j = 0; j < kMaxSeg; ++j)
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const float d = (mine && j == y / kSeg && e == (y & 3)) ? dy_old : D[j][e];
-                                R[j][e] = fmaxf(R[j][e] - d, 0.0f) * ir;
+                        for (int j = 0; j < kMaxSeg; ++j) {
+                            const int i0 = tok_index(j, 0);
+                            if (i0 < V) {
+                                const float4 dv = *reinterpret_cast<const float4*>(D_lds + i0);
+                                R[j][0] = fmaxf(fmaf(-scale_d, dv.x, R[j][0]), 0.0f) * ir;
+                                R[j][1] = fmaxf(fmaf(-scale_d, dv.y, R[j][1]), 0.0f) * ir;
+                                R[j][2] = fmaxf(fmaf(-scale_d, dv.z, R[j][2]), 0.0f) * ir;
+                                R[j][3] = fmaxf(fmaf(-scale_d, dv.w, R[j][3]), 0.0f) * ir;
                             }
+                        }
                     }
-                    c = sh.next_sibling[c];
+                    __syncthreads();                          // every thread has read D_lds as it stood
+                    if (tid == 0 && y >= 0) D_lds[y] = 0.0f;  // y leaves D
+                    const float left = res[1] - dy;           // weight left in D
+                    c = l_next[c];
                     ++rank;
-                    if (!(res[1] > 0.0f)) {                  // D is empty: later children are not tried
+                    if (!(left > 0.0f)) {                     // D is empty: later children are not tried
                         if (tid == 0)
-                            for (int k = 0, cc = c; cc >= 0 && cc < N && k < N; ++k, cc = sh.next_sibling[cc])
+                            for (int k = 0, cc = c; cc >= 0 && k < N; ++k, cc = l_next[cc])
                                 accept_ratio[base + cc] = -1.0f;
                         break;
                     }
-                    const float il = 1.0f / res[1];
-#pragma unroll
-                    for (int j = 0; j < kMaxSeg; ++j)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) D[j][e] *= il;
+                    scale_d = 1.0f / left;                    // D <- norm(D), kept as a factor
+                    __syncthreads();                          // the removal is visible before D_lds is read again
                 }
             }
         }
@@ -436,6 +469,7 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
             if (tid == 0) accepted_nodes[base + na] = next;
             ++na;
             cur = next; pk = pk_next;
+            __syncthreads();                                  // D_lds and the scratch are free for the next node
             continue;
         }
         // ---- the walk stops at cur: emit a token from what is left of the target row
@@ -444,7 +478,7 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
         __syncthreads();
         const double u = (double)u01(seed, pk, 0u, KIND_RESID);
         double W, wy;
-        fin = block_inverse_cdf<float>(R, u, &sh.cdf, &W, &wy);
+        fin = block_inverse_cdf<float>(R, u, &sh.cdf, reinterpret_cast<double*>(dyn), &W, &wy);   // the draft row's LDS is free now
         break;
     }
     if (tid == 0) {
@@ -452,6 +486,18 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
         final_token[seq] = fin;
         min_margin[seq] = margin;
     }
+}
+
+// the walk keeps a draft row and the tree links in dynamic LDS: raised to the largest once
+hipError_t prepare_verify()
+{
+    static std::atomic<unsigned long long> done[4] = { {0}, {0}, {0}, {0} };
+    const int bytes = (int)walk_lds_bytes(DYSPEC_MAX_VOCAB, DYSPEC_MAX_NODES);
+    hipError_t e = raise_dynamic_lds_once(reinterpret_cast<const void*>(&verify_walk_kernel<true, float>), bytes, done[0]);
+    if (e == hipSuccess) e = raise_dynamic_lds_once(reinterpret_cast<const void*>(&verify_walk_kernel<false, float>), bytes, done[1]);
+    if (e == hipSuccess) e = raise_dynamic_lds_once(reinterpret_cast<const void*>(&verify_walk_kernel<true, __bf16>), bytes, done[2]);
+    if (e == hipSuccess) e = raise_dynamic_lds_once(reinterpret_cast<const void*>(&verify_walk_kernel<false, __bf16>), bytes, done[3]);
+    return e;
 }
 
 template <typename T>
@@ -472,14 +518,19 @@ static hipError_t launch_verify_t(const T* draft_logits, const T* target_logits,
         softmax_stats_kernel<true, T><<<rows, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
     else
         softmax_stats_kernel<false, T><<<rows, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, row_stats, accept_ratio);
+    int widest = 1;
+    for (int s = 0; s < sa.n_seq; ++s) widest = max(widest, sa.node_off[s + 1] - sa.node_off[s]);
+    const size_t dyn = walk_lds_bytes(V, widest);
+    const hipError_t ep = prepare_verify();
+    if (ep != hipSuccess) return ep;
     if (V % 4 == 0)
-        verify_walk_kernel<true, T><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, tree, seed, emit_bonus,
-                                                                     row_stats, accept_ratio, accepted_nodes, n_accepted,
-                                                                     final_token, min_margin);
+        verify_walk_kernel<true, T><<<sa.n_seq, kBlock, dyn, stream>>>(draft_logits, target_logits, V, sa, tree, seed, emit_bonus,
+                                                                       row_stats, accept_ratio, accepted_nodes, n_accepted,
+                                                                       final_token, min_margin);
     else
-        verify_walk_kernel<false, T><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, target_logits, V, sa, tree, seed, emit_bonus,
-                                                                      row_stats, accept_ratio, accepted_nodes, n_accepted,
-                                                                      final_token, min_margin);
+        verify_walk_kernel<false, T><<<sa.n_seq, kBlock, dyn, stream>>>(draft_logits, target_logits, V, sa, tree, seed, emit_bonus,
+                                                                        row_stats, accept_ratio, accepted_nodes, n_accepted,
+                                                                        final_token, min_margin);
     return hipGetLastError();
 }
 

@@ -137,9 +137,45 @@ def test_bf16_prefix_split_matches_unsplit_and_oracle(dy, nodes, prefix, Hq, Hkv
     split = dy.tree_attn(*args, mask_dev, batch, scale)
     whole = dy.tree_attn(*args, mask_dev, batch, scale, use_workspace=False)
     torch.cuda.synchronize()
-    # same products, one more fp32 combine and a different bf16 rounding point
+    # same products; every split's share of a row is rounded to bf16 before the merge
     assert float((split.float() - whole.float()).abs().max()) <= 2.0 ** -6
+    # the merge sums the parts in split order whoever performs it: the same bits on every launch
+    for _ in range(3):
+        again = dy.tree_attn(*args, mask_dev, batch, scale)
+        assert torch.equal(again.view(torch.int16), split.view(torch.int16))
+    # and the arrival counters at the head of the workspace are zero again for the next call
+    from paper_2410_11744_amd import binding
+    torch.cuda.synchronize()
+    ws = binding._scratch_cache[str(args[0].device)]
+    assert int(ws[:1024].view(torch.int32).abs().max().item()) == 0
     run_and_compare(dy, nodes, prefix, Hq, Hkv, 128, "bf16", 21)
+
+
+def test_split_needs_zeroed_counters_only_once(dy):
+    """A caller's own workspace: cleared once after allocation, then used for calls of different shapes
+    and split counts in a row, never cleared again; results equal to the unsplit call's within the
+    bf16 rounding of the parts."""
+    import ctypes
+    lib = dy.load_library()
+    ws = torch.zeros(3 << 20, dtype=torch.float32, device="cuda")            # 12 MB, zero-filled once
+    for k, (nodes, prefix, Hq, Hkv) in enumerate([((32,), (4096,), 64, 8), ((128,), (1024,), 8, 8), ((40, 9), (64 * 22, 64 * 17 + 1), 4, 2),
+                                                  ((32,), (4096,), 64, 8)]):
+        batch = dy.Batch.from_sizes(nodes, prefix)
+        q, kp, vp, kt, vt, mask = make_case(nodes, prefix, Hq, Hkv, 128, "bf16", 40 + k)
+        args = [t.cuda() for t in (q, kp, vp, kt, vt)]
+        mask_dev = torch.from_numpy(mask.view(np.int64)).cuda()
+        cb = batch._c()
+        need = lib.dyspec_workspace_bytes(1, ctypes.byref(cb), 0, Hq, Hkv, 128)
+        assert 0 < need <= ws.numel() * 4
+        out = torch.empty_like(args[0])
+        st = lib.dyspec_tree_attn(*[t.data_ptr() for t in args], mask_dev.data_ptr(), ctypes.byref(cb), Hq, Hkv, 128, dy.BF16,
+                                  ctypes.c_float(1.0 / math.sqrt(128)), out.data_ptr(), ws.data_ptr(), ctypes.c_size_t(need),
+                                  torch.cuda.current_stream().cuda_stream)
+        assert st == 0
+        whole = dy.tree_attn(*args, mask_dev, batch, 1.0 / math.sqrt(128), use_workspace=False)
+        torch.cuda.synchronize()
+        assert float((out.float() - whole.float()).abs().max()) <= 2.0 ** -6
+        assert int(ws[:1024].view(torch.int32).abs().max().item()) == 0
 
 
 def test_bf16_tree_only_large_trees(dy):
