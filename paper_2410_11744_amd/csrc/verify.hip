@@ -17,7 +17,7 @@
 // the statistics pass stores (largest raw target logit, its index) in place of (max, sum-exp)
 // and the walk builds its target row from that index instead of reading the logits; every
 // other step of Algorithm 3 runs unchanged.
-#include "vocab_common.h"
+#include "lane_ops.h"
 
 namespace dyspec {
 
@@ -293,12 +293,95 @@ __global__ __launch_bounds__(kStatThreads) void softmax_stats_stream_pieces_kern
 // into probabilities per visited node.
 __device__ __forceinline__ float exp_fast(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
 
+// Inverse CDF over a register-resident row of weights (the step's last token): the smallest token
+// index y, in the order (segment, thread, element), whose cumulative weight exceeds u * W.  Sums
+// are fp64.  The threads' sixteen segment sums are staged in LDS (`stage`: kStageDoubles doubles);
+// wave w totals segments 2w and 2w+1 from there; every thread reads the sixteen totals and picks
+// the segment; each wave scans its 64 sums of that segment across lanes; the eight wave totals
+// tell every thread which wave holds the crossing, and that wave finds the owning thread with a
+// ballot; the owner walks its four weights.  Three barriers.  Every thread gets y (-1 when W == 0).
+constexpr int kStageDoubles = kMaxSeg * kBlock + kMaxSeg;
+struct DrawScratch {
+    double wave_tot[kWaves];
+    int last_live[kWaves];
+    int y;
+};
+__device__ __forceinline__ int draw_from_row(const float (&w)[kMaxSeg][4], double u, DrawScratch* sc, double* stage)
+{
+    static_assert(kMaxSeg == 2 * kWaves, "two segments per wave");
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+#pragma unroll
+    for (int j = 0; j < kMaxSeg; ++j)
+        stage[j * kBlock + tid] = ((double)w[j][0] + (double)w[j][1]) + ((double)w[j][2] + (double)w[j][3]);
+    __syncthreads();
+    double* const totals = stage + kMaxSeg * kBlock;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int j = 2 * wave + k;
+        double a = 0.0;
+#pragma unroll
+        for (int i = 0; i < kBlock / kWave; ++i) a += stage[j * kBlock + i * kWave + lane];
+        a = wave_sum_dpp(a);
+        if (lane == 0) totals[j] = a;
+    }
+    __syncthreads();
+    double tot[kMaxSeg];
+#pragma unroll
+    for (int j = 0; j < kMaxSeg; ++j) tot[j] = totals[j];
+    const SegPick pk = pick_segment(tot, u);
+    if (!(pk.W > 0.0)) return -1;                            // uniform
+    const double mine = stage[pk.js * kBlock + tid];
+    const double inc = wave_scan_dpp(mine);                  // inclusive, in lane order
+    const unsigned long long live = __ballot(mine > 0.0);
+    if (lane == kWave - 1) sc->wave_tot[wave] = inc;
+    if (lane == 0) sc->last_live[wave] = live ? wave * kWave + 63 - __builtin_clzll(live) : -1;
+    __syncthreads();
+    // the first wave whose running total is past the target; with none (rounding at the very top)
+    // the last thread that has weight
+    double before = 0.0, run = pk.cum_js;
+    int kw = -1, fixed_owner = -1;
+#pragma unroll
+    for (int k = 0; k < kWaves; ++k) {
+        const double t = sc->wave_tot[k];
+        if (kw < 0 && run + t > pk.target) { kw = k; before = run - pk.cum_js; }
+        run += t;
+        if (sc->last_live[k] >= 0) fixed_owner = sc->last_live[k];
+    }
+    if (kw >= 0) fixed_owner = -1;
+    else if (fixed_owner >= 0) kw = fixed_owner / kWave;
+    if (wave == kw) {
+        const unsigned long long hit = __ballot(mine > 0.0 && pk.cum_js + before + inc > pk.target);
+        const int ol = fixed_owner >= 0 ? fixed_owner % kWave : hit ? __builtin_ctzll(hit) : 63 - __builtin_clzll(live);
+        if (lane == ol) {
+            // this thread's four weights of the picked segment (sixteen uniform compares pick the registers)
+            float w4[4] = { 0.0f, 0.0f, 0.0f, 0.0f };
+#pragma unroll
+            for (int jj = 0; jj < kMaxSeg; ++jj)
+                if (jj == pk.js) { w4[0] = w[jj][0]; w4[1] = w[jj][1]; w4[2] = w[jj][2]; w4[3] = w[jj][3]; }
+            double c = pk.cum_js + before + (inc - mine);
+            int y = -1, ylast = -1;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                c += (double)w4[e];
+                if (w4[e] > 0.0f) ylast = tok_index(pk.js, e);
+                if (y < 0 && w4[e] > 0.0f && c > pk.target) y = tok_index(pk.js, e);
+            }
+            sc->y = y >= 0 ? y : ylast;
+        }
+    } else if (kw < 0 && tid == 0) {
+        sc->y = -1;                                          // the totals held rounding dust only
+    }
+    __syncthreads();
+    return sc->y;
+}
+
 // LDS of the walk.  Static part: scratch of the reductions.  Dynamic part: the draft row of the
 // node being decided, as unnormalised weights exp(logit/T - max) indexed by token (what is left of
 // D after the children rejected so far is D_lds[x] * scale), then the sequence's tree links as
 // 16-bit values (tokens < 32768, nodes < 2048; -1 = none).  The target row R stays in registers.
 struct WalkShared {
-    CdfScratch cdf;
+    DrawScratch draw;
     float fred[kWaves * 2];
     float bcast[2];
 };
@@ -477,8 +560,7 @@ __global__ __launch_bounds__(kBlock) void verify_walk_kernel(
         if (!rows_loaded) load_rows(false);
         __syncthreads();
         const double u = (double)u01(seed, pk, 0u, KIND_RESID);
-        double W, wy;
-        fin = block_inverse_cdf<float>(R, u, &sh.cdf, reinterpret_cast<double*>(dyn), &W, &wy);   // the draft row's LDS is free now
+        fin = draw_from_row(R, u, &sh.draw, reinterpret_cast<double*>(dyn));     // the draft row's place in LDS is free now
         break;
     }
     if (tid == 0) {

@@ -145,46 +145,4 @@ __device__ __forceinline__ int block_inverse_cdf_seg(const double (&seg_in)[kMax
     return finish_inverse_cdf(pk, mine, sc, wy_out, weight);
 }
 
-// The same over a register-resident row of weights, with the threads' segment sums staged in LDS
-// (`stage`: kStageDoubles doubles) instead of being reduced sixteen at a time in registers: wave w
-// totals segments 2w and 2w+1 from there, every thread reads the sixteen totals back.
-constexpr int kStageDoubles = kMaxSeg * kBlock + kMaxSeg;
-template <typename T>
-__device__ __forceinline__ int block_inverse_cdf(const T (&w)[kMaxSeg][4], double u, CdfScratch* sc, double* stage,
-                                                 double* W_out, double* wy_out)
-{
-    static_assert(kMaxSeg == 2 * kWaves, "two segments per wave");
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-#pragma unroll
-    for (int j = 0; j < kMaxSeg; ++j)
-        stage[j * kBlock + tid] = ((double)w[j][0] + (double)w[j][1]) + ((double)w[j][2] + (double)w[j][3]);
-    __syncthreads();
-    double* const totals = stage + kMaxSeg * kBlock;
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        const int j = 2 * wave + k;
-        double a = 0.0;
-        for (int i = lane; i < kBlock; i += kWave) a += stage[j * kBlock + i];
-        a = wave_sum(a);
-        if (lane == 0) totals[j] = a;
-    }
-    __syncthreads();
-    double tot[kMaxSeg];
-#pragma unroll
-    for (int j = 0; j < kMaxSeg; ++j) tot[j] = totals[j];
-    const SegPick pk = pick_segment(tot, u);
-    *W_out = pk.W;
-    if (!(pk.W > 0.0)) { *wy_out = 0.0; return -1; }
-    const double mine = stage[pk.js * kBlock + tid];
-    // this thread's four weights of the picked segment (the segment is the same for every thread, so
-    // sixteen uniform compares pick the four registers: the owner walks them)
-    T w4[4] = { (T)0, (T)0, (T)0, (T)0 };
-#pragma unroll
-    for (int jj = 0; jj < kMaxSeg; ++jj)
-        if (jj == pk.js) { w4[0] = w[jj][0]; w4[1] = w[jj][1]; w4[2] = w[jj][2]; w4[3] = w[jj][3]; }
-    return finish_inverse_cdf(pk, mine, sc, wy_out, [&](int, int e) {
-        return (double)(e == 0 ? w4[0] : e == 1 ? w4[1] : e == 2 ? w4[2] : w4[3]);
-    });
-}
-
 }  // namespace dyspec
