@@ -384,7 +384,7 @@ def main() -> int:
     hbm_gbs = bytes_step / (ms_per_step * 1e-3) / 1e9
     # which roof bounds the kernel at this shape: flops per algorithmic byte against the ridge
     ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
-    kernel = "tree_attn_mfma_kernel<%d, 1>" % cfg.head_dim if cfg.dtype == "bf16" else "tree_attn_kernel (fp32, per wave)"
+    kernel = "tree_attn_mfma_kernel<%d, 1>" % cfg.head_dim if cfg.dtype == "bf16" else "tree_attn_simple_kernel<float, %d>" % ((cfg.head_dim // 4 + 15) // 16)
     if cfg.dtype == "bf16" and flops_per_launch / bytes_attn_launch >= ridge:
         roofline = {"kernel": kernel, "bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4)}

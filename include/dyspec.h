@@ -46,7 +46,7 @@ enum {
 };
 
 /* Tensor element types of dyspec_tree_attn.  DYSPEC_BF16_WAVE: bf16 storage handled by the
- * one-wavefront-per-row kernel (fp32 arithmetic, any head_dim <= 256) instead of the
+ * one-workgroup-per-(row, head) kernel (fp32 arithmetic, any head_dim <= 256 that is a multiple of 4) instead of the
  * matrix-core kernel. */
 enum { DYSPEC_F32 = 0, DYSPEC_BF16 = 1, DYSPEC_BF16_WAVE = 0x101 };
 

@@ -246,9 +246,9 @@ static dyspec_status tree_attn_common(const void* q, const void* k_prefix, const
         force_simple = dtype == DYSPEC_BF16_WAVE;
         dtype = DYSPEC_BF16;
         if (!force_simple && head_dim != 64 && head_dim != 128) return DYSPEC_UNSUPPORTED;
-        if (force_simple && (head_dim < 1 || head_dim > 256)) return DYSPEC_UNSUPPORTED;
+        if (force_simple && (head_dim < 4 || head_dim > 256 || head_dim % 4)) return DYSPEC_UNSUPPORTED;
     } else if (dtype == DYSPEC_F32) {
-        if (head_dim < 1 || head_dim > 256) return DYSPEC_UNSUPPORTED;
+        if (head_dim < 4 || head_dim > 256 || head_dim % 4) return DYSPEC_UNSUPPORTED;   // rows are read 4 values at a time
     } else {
         return DYSPEC_UNSUPPORTED;
     }
@@ -265,7 +265,7 @@ static dyspec_status tree_attn_common(const void* q, const void* k_prefix, const
         return launch_tree_attn(a, sa, dtype, force_simple, workspace, workspace_bytes, stream) == hipSuccess
                    ? DYSPEC_OK : DYSPEC_HIP_ERROR;
     auto at = [](const void* p, long long off) { return p ? static_cast<const char*>(p) + off : nullptr; };
-    for (int l = 0; l < n_layers; ++l) {                                 // the per-wave kernels: one launch per layer
+    for (int l = 0; l < n_layers; ++l) {                                 // the per-row kernels: one launch per layer
         AttnArgs b = a;
         b.layers = 1;
         b.q = at(q, l * q_stride); b.out = static_cast<char*>(out) + l * q_stride;
