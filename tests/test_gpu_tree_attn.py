@@ -194,6 +194,21 @@ def test_per_wave_kernel_odd_head_dim(dy, dtype, api):
     run_and_compare(dy, (40, 9), (77, 3), 6, 3, 80, dtype, 12, api_dtype=api)
 
 
+@pytest.mark.parametrize("nodes,prefix,Hq,Hkv,d,dtype,api,seed", [
+    ((7, 130), (0, 300), 2, 1, 4, "f32", None, 40),          # one 16-byte piece per row; a sequence without prefix
+    ((65,), (1000,), 3, 3, 64, "f32", None, 41),            # several trips per wavefront, 64 keys each
+    ((33, 1), (257, 5), 4, 2, 192, "f32", None, 42),        # three pieces per lane
+    ((20, 70), (129, 64), 2, 2, 256, "f32", None, 43),      # four pieces per lane
+    ((50,), (90,), 4, 1, 252, "bf16", 0x101, 44),           # last piece of the lane missing for lanes 15 of 16
+    ((300,), (17,), 2, 2, 128, "bf16", 0x101, 45),          # more tree keys than prefix keys, five mask words
+    ((1, 1, 1), (0, 1, 3), 2, 2, 8, "f32", None, 46),       # roots only: wavefronts and groups without any key
+])
+def test_per_row_kernel_piece_counts_and_key_splits(dy, nodes, prefix, Hq, Hkv, d, dtype, api, seed):
+    """The fp32 / odd-size kernel over its four piece counts, head sizes that leave lanes without
+    a piece, walks shorter than one wavefront's run and walks of many runs."""
+    run_and_compare(dy, nodes, prefix, Hq, Hkv, d, dtype, seed, api_dtype=api)
+
+
 def test_unsupported_head_dim_is_rejected(dy):
     batch = dy.Batch.from_sizes([4], [4])
     z = lambda *sh: torch.zeros(sh, dtype=torch.bfloat16, device="cuda")

@@ -67,6 +67,9 @@ def test_misaligned_pointers_are_refused_before_any_launch():
     assert attn(q=A + 8, dtype=binding.F32) == -1
     # more query heads than the kernels' 32-bit row offsets reach: a shape error, not a wrong address
     assert lib.dyspec_tree_attn(A, A, A, A, A, A, ctypes.byref(c), 4096, 2, 128, binding.BF16, 0.1, A, None, 0, None) == -2
+    # the fp32 / odd-size kernel reads rows four values at a time
+    for hd, dt in ((66, binding.F32), (2, binding.F32), (260, binding.F32), (70, binding.BF16_WAVE)):
+        assert lib.dyspec_tree_attn(A, A, A, A, A, A, ctypes.byref(c), 8, 2, hd, dt, 0.1, A, None, 0, None) == -3, hd
     assert lib.dyspec_tree_attn_layers(A, A, A + 2, A, A, A, ctypes.byref(c), 3, 1 << 20, 1 << 20, 1 << 20, 8, 2, 128,
                                        binding.BF16, 0.1, A, None, 0, None) == -1
 
