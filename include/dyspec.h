@@ -120,11 +120,13 @@ dyspec_status dyspec_init(void);
  *   n_built       DEVICE [n_seq]: rows actually built (< N only if no slot of positive
  *                 value is left); later rows keep parent = token = -1 and their own mask bit
  *   workspace     DEVICE, dyspec_workspace_bytes(DYSPEC_WS_BUILD_TREE, ...) bytes, 8-byte
- *                 aligned, contents overwritten: the 4-token sums of every row's softmax
- *                 weights, computed for all rows at once before the serial expansion and
- *                 kept current by it.  NULL or fewer bytes: the expansion recomputes the
- *                 parent row's sums at every draw instead (same arithmetic, same tree,
- *                 several times slower).
+ *                 aligned, contents overwritten (about 4.2 KB per row): every row's
+ *                 maximum and the totals of its 16 vocabulary segments, computed for all
+ *                 rows at once before the serial expansion, and one bit per token drawn
+ *                 from the row so far; a draw then touches a 16th of the parent's row.
+ *                 NULL or fewer bytes: the expansion makes a pass over the parent's whole
+ *                 row at every draw instead (same arithmetic, same tree, several times
+ *                 slower).
  * vocab <= DYSPEC_MAX_VOCAB, N <= DYSPEC_MAX_BUILD_NODES (DYSPEC_BAD_SHAPE beyond).
  */
 dyspec_status dyspec_build_tree(const float* draft_logits, int32_t vocab,

@@ -10,11 +10,11 @@
 // token) equal to an fp64 evaluation of the algorithm except at relative margins near 1e-13.
 //
 // With a workspace the O(vocabulary) part leaves the serial loop: draft_row_sums_kernel (one
-// workgroup per row, all rows at once) stores every row's segment sums, and the builder
-// (build_tree_cached_kernel) keeps them current -- a draw changes the one sum that held the
-// drawn token and the total of its segment.  The rows' segment totals live in LDS, so a draw
-// makes one trip to global memory (each thread fetches its sum, its four logits and its
-// drawn-already bits of the picked segment together) and passes two barriers.  Without a
+// workgroup per row, all rows at once) stores every row's maximum and the totals of its kMaxSeg
+// segments, and the builder (build_tree_cached_kernel) keeps the totals current in LDS and a bit
+// per drawn token in the workspace.  A draw picks the segment from the totals, makes one trip to
+// global memory (each thread fetches its four logits and its drawn-already bits of the picked
+// segment and recomputes their four weights, a 16th of a row pass) and passes two barriers.  Without a
 // workspace the builder (build_tree_kernel) recomputes the sums of the parent's row for every
 // draw; both ways take the same decisions and build the same tree.
 #include "draft_row.h"
@@ -24,18 +24,17 @@ namespace dyspec {
 
 constexpr int kMaxSlots = 2 * DYSPEC_MAX_BUILD_NODES + 2;
 
-// Workspace of the cached form, per row (doubles): kMaxSeg * kBlock segment sums S[j][t],
-// kMaxSeg segment totals, the row maximum (already divided by the temperature), and one bit
-// per token: drawn at this position already (its weight is no longer in the sums).
+// Workspace of the cached form, per row (doubles): kMaxSeg segment totals, the row maximum
+// (already divided by the temperature), and one bit per token: drawn at this position already
+// (its weight is no longer in the totals).
 constexpr int kGoneWords = DYSPEC_MAX_VOCAB / 32;
-constexpr int kRowSumDoubles = kMaxSeg * kBlock + kMaxSeg + 8 + kGoneWords / 2;
-__host__ __device__ inline double* ws_sums(double* ws, int row) { return ws + (size_t)row * kRowSumDoubles; }
-__host__ __device__ inline double* ws_totals(double* ws, int row) { return ws_sums(ws, row) + kMaxSeg * kBlock; }
+constexpr int kRowSumDoubles = kMaxSeg + 8 + kGoneWords / 2;
+__host__ __device__ inline double* ws_totals(double* ws, int row) { return ws + (size_t)row * kRowSumDoubles; }
 __host__ __device__ inline double* ws_rowmax(double* ws, int row) { return ws_totals(ws, row) + kMaxSeg; }
 __host__ __device__ inline uint32_t* ws_gone(double* ws, int row) { return reinterpret_cast<uint32_t*>(ws_totals(ws, row) + kMaxSeg + 8); }
 
 // Data-parallel part (the draft softmax of every node, Algorithm 1's model call output):
-// one workgroup per row writes the row's segment sums, segment totals and maximum.
+// one workgroup per row writes the row's segment totals and maximum and clears its drawn bits.
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void draft_row_sums_kernel(const float* __restrict__ draft_logits, int V, SeqArgs sa,
                                                                 double* __restrict__ ws)
@@ -47,9 +46,6 @@ __global__ __launch_bounds__(kBlock) void draft_row_sums_kernel(const float* __r
     const double inv_temp = 1.0 / (double)sa.temp_d[seq];
     double m, seg[kMaxSeg];
     row_segment_sums<VEC>(draft_logits + (size_t)row * V, V, inv_temp, 0ull, fred, &m, seg);
-    double* S = ws_sums(ws, row);
-#pragma unroll
-    for (int j = 0; j < kMaxSeg; ++j) S[j * kBlock + threadIdx.x] = seg[j];
     block_sum<double, kMaxSeg>(seg, red);
     if (threadIdx.x < kMaxSeg) {
         double t = 0.0;
@@ -222,13 +218,14 @@ __global__ __launch_bounds__(kBlock) void build_tree_kernel(
 // drawn from, its parent p, the rank of the child to draw and the draw u.
 //
 // A draw takes two barriers.  Lanes read p's segment totals from LDS (one each) and pick the
-// segment with a 16-lane scan; every thread fetches, in one trip to global memory, its own sum of
-// that segment, its four logits and the word with its drawn-already bits.  While those loads
+// segment with a 16-lane scan; every thread fetches, in one trip to global memory, its four
+// logits of that segment and the word with their drawn-already bits.  While those loads
 // are in flight each wave finds the best of its other open slots (DPP maximum and a ballot).
-// The sums are scanned (barrier 1).  The waves' totals tell every thread which wave holds the
-// crossing; that wave finds the thread (the owner) with a ballot, takes the owner's logits to
-// its first four lanes, which compute the four weights, finishes the draw (token, weight), has
-// the owner store its new sum and bits and writes the segment's new total.  Meanwhile three
+// Every thread computes its four weights (drawn tokens: 0) and their sum, in the order the
+// pre-pass summed them; the sums are scanned (barrier 1).  The waves' totals tell every thread
+// which wave holds the crossing; that wave finds the thread (the owner) with a ballot, takes the
+// owner's four weights, finishes the draw (token, weight), has
+// the owner store its bits and writes the segment's new total.  Meanwhile three
 // other waves compute the path key of the new node and the draws of the two slots the draw
 // opens (functions of p and rank only) and reduce the waves' bests to the best open slot outside
 // this draw (barrier 2).  Every thread then computes the values of the two new slots, keeps them
@@ -310,16 +307,14 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         // ---- draw the token from the residual draft distribution of p
         const float* __restrict__ row = draft_logits + (size_t)(base + p) * V;
         // (ws is written by this kernel and not declared restrict or const, so these are
-        //  ordinary vector loads and stores; a sum, a bit word or a mask word is only ever re-read
+        //  ordinary vector loads and stores; a bit word or a mask word is only ever re-read
         //  by the wave that wrote it)
-        double* const S = ws_sums(ws, base + p);
         const double my_tot = row_state[p * kRowState + (lane & 15)];
         const double m = row_state[p * kRowState + kMaxSeg];
         const SegPick pk = pick_segment_lanes(my_tot, u);
         const double W = pk.W;
         if (!(W > 0.0)) break;                         // nothing left to sample under p
         const int tok_mine = pk.js * kSeg + 4 * tid;   // this thread's four tokens of the segment
-        const double mine = S[pk.js * kBlock + tid];
         uint32_t* const gone_word = ws_gone(ws, base + p) + tok_mine / 32;
         const uint32_t gone = *gone_word;
         float lg[4];
@@ -345,6 +340,19 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
             const float wu = readlane_f32(bu, wl);
             if (lane == 0) { sh.best_v[wave] = wv; sh.best_i[wave] = wi; sh.best_pr[wave] = wpr; sh.best_u[wave] = wu; }
         }
+        // ---- this thread's four weights of the segment (a drawn token has none) and their sum,
+        //      associated as the pre-pass did: the totals in LDS are sums of exactly these
+        double w4[4];
+        {
+            double z[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) z[e] = fma((double)lg[e], inv_temp, -m);
+            exp_nonpos_x4(z, w4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (tok_mine + e >= V || ((gone >> (tok_mine % 32 + e)) & 1u)) w4[e] = 0.0;
+        }
+        const double mine = (w4[0] + w4[1]) + (w4[2] + w4[3]);
         // ---- inclusive scan of the 512 sums in thread order
         const double inc = wave_scan_dpp(mine);
         if (lane == kWave - 1) sh.wave_tot[wave] = inc;
@@ -401,19 +409,10 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
             // can put the crossing on a thread without weight) the last one with weight
             const unsigned long long hit = __ballot(mine > 0.0 && pk.cum_js + incl > pk.target);
             const int ol = fixed_owner >= 0 ? fixed_owner % kWave : hit ? __builtin_ctzll(hit) : 63 - __builtin_clzll(live);
-            const float l0 = readlane_f32(lg[0], ol), l1 = readlane_f32(lg[1], ol);
-            const float l2 = readlane_f32(lg[2], ol), l3 = readlane_f32(lg[3], ol);
-            const uint32_t g = (uint32_t)__builtin_amdgcn_readlane((int)gone, ol);
             const int tok0 = pk.js * kSeg + 4 * (kw * kWave + ol);
-            // the first four lanes compute one weight each; then every lane of the wave finishes the
-            // draw: the token among the four, what is left of their sum
-            double w = 0.0;
-            if (lane < 4) {
-                const float l = lane == 0 ? l0 : lane == 1 ? l1 : lane == 2 ? l2 : l3;
-                const bool there = tok0 + lane < V && !((g >> (tok0 % 32 + lane)) & 1u);
-                if (there) w = token_weight(l, inv_temp, m);
-            }
-            const double w4v[4] = { readlane_f64(w, 0), readlane_f64(w, 1), readlane_f64(w, 2), readlane_f64(w, 3) };
+            // every lane of the wave finishes the draw with the owner's four weights: the token
+            // among the four, what is left of their sum
+            const double w4v[4] = { readlane_f64(w4[0], ol), readlane_f64(w4[1], ol), readlane_f64(w4[2], ol), readlane_f64(w4[3], ol) };
             double run = readlane_f64(pk.cum_js + (incl - mine), ol), wy = 0.0, wlast = 0.0;
             int y = -1, ylast = -1;
 #pragma unroll
@@ -428,10 +427,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
                 // the sum that held y and the total of its segment lose y's weight
                 const int ey = y - tok0;
                 const double left = ((ey == 0 ? 0.0 : w4v[0]) + (ey == 1 ? 0.0 : w4v[1])) + ((ey == 2 ? 0.0 : w4v[2]) + (ey == 3 ? 0.0 : w4v[3]));
-                if (lane == ol) {
-                    S[pk.js * kBlock + tid] = left;
-                    *gone_word = gone | (1u << (tok0 % 32 + ey));
-                }
+                if (lane == ol) *gone_word = gone | (1u << (tok0 % 32 + ey));
                 const double wsum = wave_sum_dpp(lane == ol ? left : mine);     // the wave's sums again, the owner's replaced
                 double t = (lane & 15) == kw ? wsum : wt;                       // lanes 0..7: the waves' totals now
                 t += dpp_or_zero<kDppXor1>(t);

@@ -31,6 +31,28 @@ static __device__ __attribute__((noinline)) double exp_nonpos(double z)
     return ldexp(p, (int)n);
 }
 
+// exp_nonpos of four arguments at once: the same operations per argument, interleaved so that
+// the four dependent chains overlap (every result equals exp_nonpos of its argument bit for bit)
+__device__ __forceinline__ void exp_nonpos_x4(const double (&z)[4], double (&out)[4])
+{
+    constexpr double c[13] = { 1.0 / 479001600.0, 1.0 / 39916800.0, 1.0 / 3628800.0, 1.0 / 362880.0, 1.0 / 40320.0, 1.0 / 5040.0,
+                               1.0 / 720.0, 1.0 / 120.0, 1.0 / 24.0, 1.0 / 6.0, 0.5, 1.0, 1.0 };
+    double n[4], r[4], p[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        n[e] = rint(z[e] * 1.4426950408889634074);
+        r[e] = fma(n[e], -6.93147180369123816490e-01, z[e]);
+        r[e] = fma(n[e], -1.90821492927058770002e-10, r[e]);
+        p[e] = 1.0 / 6227020800.0;
+    }
+#pragma unroll
+    for (int k = 0; k < 13; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) p[e] = fma(p[e], r[e], c[k]);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) out[e] = z[e] >= -708.0 ? ldexp(p[e], (int)n[e]) : 0.0;
+}
+
 // weight of one token of a row: exp(x / T - m), m the row maximum over T
 __device__ __forceinline__ double token_weight(float x, double inv_temp, double m)
 {

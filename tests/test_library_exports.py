@@ -31,9 +31,9 @@ def test_host_validation_without_gpu():
     b = binding.Batch.from_sizes([10, 70, 129])
     assert b.mask_words == 3
     c = b._c()
-    # the tree builder's workspace: per row 16*512 segment sums, 16 totals, the maximum (padded
-    # to 8 doubles) and 32768 drawn-token bits
-    assert lib.dyspec_workspace_bytes(0, ctypes.byref(c), 32000, 64, 8, 128) == 209 * (16 * 512 + 16 + 8 + 512) * 8
+    # the tree builder's workspace: per row 16 segment totals, the maximum (padded to 8 doubles)
+    # and 32768 drawn-token bits
+    assert lib.dyspec_workspace_bytes(0, ctypes.byref(c), 32000, 64, 8, 128) == 209 * (16 + 8 + 512) * 8
     assert lib.dyspec_workspace_bytes(1, ctypes.byref(c), 32000, 64, 8, 128) == 0
     assert lib.dyspec_workspace_bytes(2, ctypes.byref(c), 32000, 64, 8, 128) == 0
     # null pointers are refused before any launch
