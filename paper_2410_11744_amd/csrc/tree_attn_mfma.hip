@@ -173,9 +173,11 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
     const int nTp = (P + kKeysPerTile - 1) / kKeysPerTile;
     const int r_last = min(rows - 1, r0 + kRowsPerWG - 1);
     // Prefix split: this workgroup walks prefix tiles [p_begin, p_begin + nPl) and, if it is
-    // the last split, the tree tiles as well.
+    // the last split, the tree tiles as well; with a.tree_split the prefix is dealt to the other
+    // splits only and the last one is left with the tree.
     const int split = blockIdx.y, n_split = a.splits;
-    const int share = (((nTp + n_split - 1) / n_split) + 1) & ~1;      // an even number of tiles
+    const int n_pref = max(n_split - a.tree_split, 1);
+    const int share = (((nTp + n_pref - 1) / n_pref) + 1) & ~1;        // an even number of tiles
     const int p_begin = min(split * share, nTp);
     const int nPl = min(nTp - p_begin, share);
     const bool last_split = split == n_split - 1;
@@ -845,10 +847,15 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
             unsigned long long w[ZB][HW + 1];
 #pragma unroll
             for (int dz = 0; dz < ZB; ++dz) {
-                const int z = min(z0 + dz, n_split - 1);       // past the end: the last split again, weight 0 below
+                if (z0 + dz < n_split) {                       // uniform: a part past the end is not fetched
 #pragma unroll
-                for (int k = 0; k < HW; ++k) w[dz][k] = ld(z, wk * HW + k);
-                w[dz][HW] = ld(z, W2);
+                    for (int k = 0; k < HW; ++k) w[dz][k] = ld(z0 + dz, wk * HW + k);
+                    w[dz][HW] = ld(z0 + dz, W2);
+                } else {                                       // and stands in with maximum -1e30, weight 0 below
+#pragma unroll
+                    for (int k = 0; k < HW; ++k) w[dz][k] = 0ull;
+                    w[dz][HW] = (unsigned long long)__float_as_uint(-1e30f);
+                }
             }
             float Mb = M;                                      // the reference maximum moves up with the batch
 #pragma unroll
@@ -954,24 +961,50 @@ static int row_tiles(const SeqArgs& sa, int G, int* tile_off)
 // tiles of every sequence's prefix, and into at most eight parts (what the finishing workgroup
 // fetches in one trip to memory).  Measured per layer: 1024 keys over 32 workgroups run best in 4
 // parts, 2048 keys over 80 in 3, 4096 keys over 16 in 8.
-int tree_attn_splits(const SeqArgs& sa, int Hq, int Hkv, int layers)
+//
+// The split that also walks the tree ends last (a tree tile goes through the masked loop and
+// costs about two prefix tiles).  If one more workgroup per group still fits on the chip and
+// within the eight parts, the tree gets a split of its own when that shortens the longest walk
+// of the batch, counted in prefix tiles.
+AttnCut tree_attn_cut(const SeqArgs& sa, int Hq, int Hkv, int layers)
 {
     const int groups = row_tiles(sa, Hq / Hkv, nullptr) * Hkv * layers;
-    if (groups == 0) return 1;
+    if (groups == 0) return { 1, 0 };
     int min_tiles = 1 << 30;
     for (int s = 0; s < sa.n_seq; ++s) min_tiles = min(min_tiles, (sa.prefix_len[s] + kKeysPerTile - 1) / kKeysPerTile);
     const int by_work = 256 / groups, by_prefix = min_tiles / 4;
     int splits = max(1, min(min(by_work, by_prefix), 8));
+    int tree_split = 0;
+    if ((size_t)groups * sizeof(unsigned) > kAttnCounterBytes) splits = 1;     // one arrival counter per group
+    if (splits > 1) {
+        // longest walk of the batch, in prefix tiles, for `parts` workgroups per group
+        auto longest = [&](int parts, bool own) {
+            int worst = 0;
+            for (int s = 0; s < sa.n_seq; ++s) {
+                const int nTp = (sa.prefix_len[s] + kKeysPerTile - 1) / kKeysPerTile;
+                const int nTt = (sa.node_off[s + 1] - sa.node_off[s] + kKeysPerTile - 1) / kKeysPerTile;
+                const int n_pref = own ? parts - 1 : parts;
+                const int share = (((nTp + n_pref - 1) / n_pref) + 1) & ~1;
+                const int last = max(0, min(nTp - (parts - 1) * share, share));       // prefix tiles of the last split
+                worst = max(worst, own ? max(min(share, nTp), 2 * nTt) : max(min(share, nTp), last + 2 * nTt));
+            }
+            return worst;
+        };
+        const int shared = longest(splits, false);
+        if (splits + 1 <= min(by_work, 8) && longest(splits + 1, true) < shared) { ++splits; tree_split = 1; }
+        else if (splits >= 3 && longest(splits, true) < shared) tree_split = 1;
+    }
 #ifdef DYSPEC_TUNING
     if (const char* e = getenv("DYSPEC_ATTN_SPLITS")) splits = max(1, min(atoi(e), min(min_tiles / 2, 32)));
+    if (const char* e = getenv("DYSPEC_ATTN_TREE_SPLIT")) tree_split = atoi(e) != 0 && splits > 1;
+    if ((size_t)groups * sizeof(unsigned) > kAttnCounterBytes) { splits = 1; tree_split = 0; }
 #endif
-    if ((size_t)groups * sizeof(unsigned) > kAttnCounterBytes) splits = 1;     // one arrival counter per group
-    return splits;
+    return { splits, tree_split };
 }
 
 size_t tree_attn_workspace_bytes(const SeqArgs& sa, int Hq, int Hkv, int d, int layers)
 {
-    const int splits = tree_attn_splits(sa, Hq, Hkv, layers);
+    const int splits = tree_attn_cut(sa, Hq, Hkv, layers).splits;
     if (splits <= 1) return 0;
     const size_t groups = (size_t)row_tiles(sa, Hq / Hkv, nullptr) * Hkv * layers;
     return kAttnCounterBytes + groups * splits * attn_part_words(d) * sizeof(uint32_t);
@@ -981,10 +1014,11 @@ hipError_t launch_tree_attn_mfma(AttnArgs a, const SeqArgs& sa, void* workspace,
 {
     const int tiles = row_tiles(sa, a.Hq / a.Hkv, a.tile_off);
     if (tiles == 0) return hipSuccess;
-    a.splits = tree_attn_splits(sa, a.Hq, a.Hkv, a.layers);
+    const AttnCut cut = tree_attn_cut(sa, a.Hq, a.Hkv, a.layers);
+    a.splits = cut.splits; a.tree_split = cut.tree_split;
     const size_t need = tree_attn_workspace_bytes(sa, a.Hq, a.Hkv, a.d, a.layers);
     if (a.splits > 1 && (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<size_t>(workspace) & 15)))
-        a.splits = 1;                                          // no room for partial results: one workgroup walks it all
+        a.splits = 1, a.tree_split = 0;                        // no room for partial results: one workgroup walks it all
     if (a.splits > 1) {
         a.counters = static_cast<unsigned*>(workspace);
         a.part = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + kAttnCounterBytes);

@@ -121,19 +121,22 @@ def test_bf16_rising_scores_raise_the_reference(dy):
     run_and_compare(dy, (200,), (640,), 4, 4, 64, "bf16", 15, qscale=4.0, ramp=2.0)
 
 
-@pytest.mark.parametrize("nodes,prefix,Hq,Hkv", [
-    ((32,), (4096,), 64, 8),               # 70B shape, narrow tree: 16 workgroups become 128
-    ((128,), (1024 + 37,), 8, 8),          # ragged last prefix tile inside the last split
-    ((40, 9), (64 * 22, 64 * 17 + 1), 4, 2),  # two splits with shares of uneven size, ragged batch
+@pytest.mark.parametrize("nodes,prefix,Hq,Hkv,groups,parts", [
+    ((32,), (4096,), 64, 8, 16, 8),               # 70B shape, narrow tree: 16 workgroups become 128
+    ((128,), (1024 + 37,), 8, 8, 8, 4),           # ragged last prefix tile; the last split holds the tree alone already
+    ((40, 9), (64 * 22, 64 * 17 + 1), 4, 2, 4, 4),   # shares of uneven size, ragged batch
+    ((128,), (1024,), 32, 32, 32, 5),             # 7B shape: four prefix splits and one for the two tree tiles
+    ((128, 64), (1024, 640), 8, 8, 16, 3),        # ragged batch with a split for the trees: two, one tree tiles
 ])
-def test_bf16_prefix_split_matches_unsplit_and_oracle(dy, nodes, prefix, Hq, Hkv):
+def test_bf16_prefix_split_matches_unsplit_and_oracle(dy, nodes, prefix, Hq, Hkv, groups, parts):
     batch = dy.Batch.from_sizes(nodes, prefix)
     q, kp, vp, kt, vt, mask = make_case(nodes, prefix, Hq, Hkv, 128, "bf16", 21)
     scale = 1.0 / math.sqrt(128)
     mask_dev = torch.from_numpy(mask.view(np.int64)).cuda()
     args = [t.cuda() for t in (q, kp, vp, kt, vt)]
     need = dy.load_library().dyspec_workspace_bytes(1, __import__("ctypes").byref(batch._c()), 0, Hq, Hkv, 128)
-    assert need > 0, "this shape is meant to be split"
+    # arrival counters, then per (row tile, KV head) and part 4 x 64 lanes x (32 + 2) words
+    assert need == 4096 + groups * parts * 4 * 64 * 34 * 4, "the cut this case is meant to exercise"
     split = dy.tree_attn(*args, mask_dev, batch, scale)
     whole = dy.tree_attn(*args, mask_dev, batch, scale, use_workspace=False)
     torch.cuda.synchronize()
