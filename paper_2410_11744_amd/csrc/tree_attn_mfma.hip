@@ -904,25 +904,42 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         return;
     }
     if (wk == 0) {
+        // The wave's 32 finished rows go through LDS so that they leave as whole rows: in register
+        // layout a store instruction writes 16 bytes of each of 32 rows, staged it writes four rows
+        // end to end.  The staging area is the wave's own part of the merge buffer above, which only
+        // this wave has read and nobody writes again; rows are 16 bytes apart from a multiple of 256
+        // so that the 8-byte writes of a column of lanes spread over the banks.
+        static_assert(QB == 1, "one query block per wave");
+        constexpr int kPitch = D * 2 + 16;
+        static_assert(32 * kPitch <= NR * kWave * (int)sizeof(float), "the rows fit in the wave's merge area");
+        char* const stage = reinterpret_cast<char*>(xs + (size_t)wq * NR * kWave);
+        const float inv = 1.0f / l_all[0];                     // a row past the end: never read back
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            if (rq[qb] >= rows) continue;
-            const float inv = 1.0f / l_all[qb];
-            const int j = rq[qb] / G, h = kvh * G + rq[qb] % G;
-            const size_t orow_index = (size_t)(node_base + j) * a.Hq + h;
-            __bf16* orow = reinterpret_cast<__bf16*>(static_cast<char*>(a.out) + (size_t)layer * a.q_stride) + orow_index * D;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+            for (int ib = 0; ib < 4; ++ib) {
+                union { bf16x2 p[2]; uint2 v; } o;
 #pragma unroll
-                for (int ib = 0; ib < 4; ++ib) {
-                    union { bf16x2 p[2]; uint2 v; } o;
-#pragma unroll
-                    for (int ii = 0; ii < 2; ++ii) {
-                        floatx2 pr = { acc[db][qb][4 * ib + 2 * ii] * inv, acc[db][qb][4 * ib + 2 * ii + 1] * inv };
-                        o.p[ii] = __builtin_convertvector(pr, bf16x2);
-                    }
-                    *reinterpret_cast<uint2*>(orow + 32 * db + 8 * ib + 4 * g) = o.v;
+                for (int ii = 0; ii < 2; ++ii) {
+                    floatx2 pr = { acc[db][0][4 * ib + 2 * ii] * inv, acc[db][0][4 * ib + 2 * ii + 1] * inv };
+                    o.p[ii] = __builtin_convertvector(pr, bf16x2);
                 }
+                *reinterpret_cast<uint2*>(stage + n * kPitch + (32 * db + 8 * ib + 4 * g) * 2) = o.v;
+            }
+        constexpr int CPR = D * 2 / 16;                        // 16-byte chunks per row
+        char* const out_layer = static_cast<char*>(a.out) + (size_t)layer * a.q_stride;
+#pragma unroll
+        for (int t = 0; t < 32 * CPR / kWave; ++t) {
+            const int c = lane + kWave * t, rn = c / CPR, cc = c % CPR;
+            const int r = r0 + 32 * wq + rn;
+            if (r >= rows) continue;
+            const uint4 v = *reinterpret_cast<const uint4*>(stage + rn * kPitch + cc * 16);
+            const int j = r / G, h = kvh * G + r % G;
+            // whole rows, streamed: all workgroups finish together, so what stays dirty in L2 is written
+            // back after the last of them, with nothing left to overlap it
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 vv = { v.x, v.y, v.z, v.w };
+            __builtin_nontemporal_store(vv, reinterpret_cast<u32x4*>(out_layer + (((size_t)(node_base + j) * a.Hq + h) * D) * 2 + cc * 16));
         }
     }
 }
