@@ -77,11 +77,14 @@ __device__ __forceinline__ void row_segment_sums(const float* __restrict__ row, 
     *m_out = m;
 #pragma unroll
     for (int j = 0; j < kMaxSeg; ++j) {
-        double w4[4];
+        double z[4], w4[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) z[e] = fma((double)x[j][e], inv_temp, -m);
+        exp_nonpos_x4(z, w4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const bool live = tok_index(j, e) < V && !((gone >> (4 * j + e)) & 1ull);
-            w4[e] = live ? token_weight(x[j][e], inv_temp, m) : 0.0;
+            if (!live) w4[e] = 0.0;
         }
         seg[j] = (w4[0] + w4[1]) + (w4[2] + w4[3]);
     }
