@@ -887,18 +887,37 @@ __global__ __launch_bounds__(64 * 2 * (4 / QB)) void tree_attn_mfma_kernel(AttnA
         } else {
             for (int z0 = 0; z0 < n_split; z0 += 8) add_batch(std::integral_constant<int, 8>{}, z0);
         }
-        if (rq[0] >= rows) return;
-        const float inv = 1.0f / Lsum;
-        const int j = rq[0] / G, h = kvh * G + rq[0] % G;
-        __bf16* orow = reinterpret_cast<__bf16*>(static_cast<char*>(a.out) + (size_t)layer * a.q_stride) +
-                       ((size_t)(node_base + j) * a.Hq + h) * D;
+        // The rows leave as in the unsplit case below: staged in LDS (each wave its half rows, in its own
+        // half of its row block's part of the merge buffer, which nobody reads any more) and written as
+        // whole 2*D/2-byte runs with streaming stores.
+        {
+            const float inv = 1.0f / Lsum;                     // a row past the end: never read back
+            constexpr int kHalfBytes = D;                      // D/2 bf16 values
+            constexpr int kPitch = kHalfBytes + 16;
+            static_assert(2 * 32 * kPitch <= NR * kWave * (int)sizeof(float), "both halves fit in the row block's merge area");
+            char* const stage = reinterpret_cast<char*>(xs + (size_t)wq * NR * kWave) + wk * 32 * kPitch;
 #pragma unroll
-        for (int k = 0; k < HW; ++k) {
-            const int db = (wk * HW + k) / 4, ib = (wk * HW + k) % 4;
-            uint2 v;
-            v.x = pack2(o[k][0] * inv, o[k][1] * inv);
-            v.y = pack2(o[k][2] * inv, o[k][3] * inv);
-            *reinterpret_cast<uint2*>(orow + 32 * db + 8 * ib + 4 * g) = v;
+            for (int k = 0; k < HW; ++k) {
+                const int db = (wk * HW + k) / 4, ib = (wk * HW + k) % 4;
+                uint2 v;
+                v.x = pack2(o[k][0] * inv, o[k][1] * inv);
+                v.y = pack2(o[k][2] * inv, o[k][3] * inv);
+                *reinterpret_cast<uint2*>(stage + n * kPitch + (32 * db + 8 * ib + 4 * g) * 2 - wk * kHalfBytes) = v;
+            }
+            constexpr int CPH = kHalfBytes / 16;               // 16-byte chunks per half row
+            char* const out_layer = static_cast<char*>(a.out) + (size_t)layer * a.q_stride;
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+            for (int t = 0; t < 32 * CPH / kWave; ++t) {
+                const int c = lane + kWave * t, rn = c / CPH, cc = c % CPH;
+                const int r = r0 + 32 * wq + rn;
+                if (r >= rows) continue;
+                const uint4 v = *reinterpret_cast<const uint4*>(stage + rn * kPitch + cc * 16);
+                const int j = r / G, h = kvh * G + r % G;
+                const u32x4 vv = { v.x, v.y, v.z, v.w };
+                __builtin_nontemporal_store(vv, reinterpret_cast<u32x4*>(out_layer + (((size_t)(node_base + j) * a.Hq + h) * D) * 2 +
+                                                                          wk * kHalfBytes + cc * 16));
+            }
         }
         STAMP(6);
         return;
