@@ -9,7 +9,10 @@
  *    every buffer; the library allocates nothing and keeps no state between calls.
  *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
  *    stream); calls return without synchronising.  Two calls that write the same buffers
- *    race unless ordered by the stream.
+ *    race unless ordered by the stream.  Apart from dyspec_build_tree_threshold (which
+ *    waits for each level) a call enqueues kernel launches only -- no allocation, memset,
+ *    copy or wait -- so, after dyspec_init() or one plain call on the device, calls may be
+ *    recorded into a HIP graph on a capturing stream and replayed.
  *  - Errors are return codes (< 0).  Arguments are validated on the host before anything
  *    is launched; a call that returns an error has launched nothing.
  *  - Alignment of DEVICE pointers is part of that validation (DYSPEC_BAD_ARG otherwise):
