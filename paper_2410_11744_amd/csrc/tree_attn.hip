@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kSimpleWaves* kWave) void tree_attn_simple_kernel(A
     const T* kt = static_cast<const T*>(a.kt) + (size_t)node_base * kv_row + (size_t)kvh * d;
     const T* vt = static_cast<const T*>(a.vt) + (size_t)node_base * kv_row + (size_t)kvh * d;
     const T* qrow = static_cast<const T*>(a.q) + ((size_t)row * a.Hq + h) * d;
-    // mask_words <= DYSPEC_MAX_NODES / 64 = 32 < 64 lanes
+    static_assert(DYSPEC_MAX_NODES / 64 <= kWave, "a row's mask words fit one per lane");
     const uint64_t mword = lane < a.mask_words ? a.mask[(size_t)row * a.mask_words + lane] : 0ull;
     const int grp = lane >> 4, li = lane & 15;
     constexpr int kKeysInFlight = 16 / CH;   // keys per group and trip to memory
