@@ -154,6 +154,23 @@ def test_bf16_prefix_split_matches_unsplit_and_oracle(dy, nodes, prefix, Hq, Hkv
     run_and_compare(dy, nodes, prefix, Hq, Hkv, 128, "bf16", 21)
 
 
+def test_bf16_prefix_split_head_dim_64(dy):
+    """The split walk and its merged, staged rows at head_dim 64 (half rows of 64 bytes), with a ragged
+    last row tile and a tree that gets a split of its own."""
+    import ctypes
+    for nodes, prefix, Hq, Hkv, seed in (((70,), (2048 + 5,), 8, 8, 31), ((128, 33), (1024, 700), 4, 4, 32)):
+        batch = dy.Batch.from_sizes(nodes, prefix)
+        assert dy.load_library().dyspec_workspace_bytes(1, ctypes.byref(batch._c()), 0, Hq, Hkv, 64) > 0, "meant to be split"
+        run_and_compare(dy, nodes, prefix, Hq, Hkv, 64, "bf16", seed)
+        q, kp, vp, kt, vt, mask = make_case(nodes, prefix, Hq, Hkv, 64, "bf16", seed)
+        args = [t.cuda() for t in (q, kp, vp, kt, vt)]
+        mask_dev = torch.from_numpy(mask.view(np.int64)).cuda()
+        split = dy.tree_attn(*args, mask_dev, batch, 0.125)
+        whole = dy.tree_attn(*args, mask_dev, batch, 0.125, use_workspace=False)
+        torch.cuda.synchronize()
+        assert float((split.float() - whole.float()).abs().max()) <= 2.0 ** -6
+
+
 def test_split_needs_zeroed_counters_only_once(dy):
     """A caller's own workspace: cleared once after allocation, then used for calls of different shapes
     and split counts in a row, never cleared again; results equal to the unsplit call's within the
