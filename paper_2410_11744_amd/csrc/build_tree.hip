@@ -254,10 +254,13 @@ struct CachedShared {
 constexpr size_t kLdsPerWorkgroup = 160 * 1024 - 1024;
 static_assert(sizeof(CachedShared) + (size_t)DYSPEC_MAX_BUILD_NODES * kRowState * sizeof(double) <= kLdsPerWorkgroup,
               "the row states of the largest tree fit in LDS");
-constexpr int kSlotsPerThread = (kMaxSlots + kBlock - 1) / kBlock;
+// A tree of N rows opens at most 2N - 1 slots (the root's, then two per draw): SLOTS of them per thread,
+// 1 for N <= 256, 2 for N <= 512, 4 beyond.
+constexpr int slots_per_thread(int n) { return n <= kBlock / 2 ? 1 : n <= kBlock ? 2 : 4; }
+static_assert(4 * kBlock >= 2 * DYSPEC_MAX_BUILD_NODES - 1, "four slots per thread hold the largest tree's");
 static_assert(DYSPEC_MAX_BUILD_NODES <= 1024 && DYSPEC_MAX_VOCAB <= (1 << 21), "a slot's parent and rank share one word");
 
-template <bool VEC>
+template <bool VEC, int SLOTS>
 __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
     const float* __restrict__ draft_logits, int V, SeqArgs sa, uint64_t seed,
     dyspec_tree tree, float* __restrict__ est_value, uint64_t* __restrict__ anc_mask,
@@ -280,16 +283,16 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
     __syncthreads();
 
     // this thread's slots tid, tid + kBlock, ...: value (< 0: closed), parent | rank << 10, draw
-    double my_v[kSlotsPerThread];
-    int my_pr[kSlotsPerThread];
-    float my_u[kSlotsPerThread];
+    double my_v[SLOTS];
+    int my_pr[SLOTS];
+    float my_u[SLOTS];
 #pragma unroll
-    for (int k = 0; k < kSlotsPerThread; ++k) { my_v[k] = -1.0; my_pr[k] = 0; my_u[k] = 0.f; }
+    for (int k = 0; k < SLOTS; ++k) { my_v[k] = -1.0; my_pr[k] = 0; my_u[k] = 0.f; }
     if (tid == 0) { my_v[0] = 1.0; my_u[0] = u_root; }              // the root's slot
     auto set_slot = [&](int s, double v, int pr, float u) {
         if (tid == s % kBlock) {
 #pragma unroll
-            for (int k = 0; k < kSlotsPerThread; ++k)
+            for (int k = 0; k < SLOTS; ++k)
                 if (k == s / kBlock) { my_v[k] = v; my_pr[k] = pr; my_u[k] = u; }
         }
     };
@@ -331,7 +334,7 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
         {
             double bv = -1.0; int bi = 0x7fffffff, bpr = 0; float bu = 0.f;
 #pragma unroll
-            for (int k = 0; k < kSlotsPerThread; ++k)
+            for (int k = 0; k < SLOTS; ++k)
                 if (my_v[k] > bv && tid + k * kBlock != pick) { bv = my_v[k]; bi = tid + k * kBlock; bpr = my_pr[k]; bu = my_u[k]; }
             const double wv = wave_max_dpp(bv);        // largest value of the wave
             int wl;                                    // (a wave without an open slot: every lane holds -1, any will do)
@@ -488,11 +491,30 @@ __global__ __launch_bounds__(kBlock) void build_tree_cached_kernel(
 // the cached builder keeps kRowState doubles per row in dynamic LDS: raised to the largest tree once
 hipError_t prepare_build_tree()
 {
-    static std::atomic<unsigned long long> done_vec{0}, done_scalar{0};
+    static std::atomic<unsigned long long> done[6] = { {0}, {0}, {0}, {0}, {0}, {0} };
     constexpr int bytes = DYSPEC_MAX_BUILD_NODES * kRowState * (int)sizeof(double);
-    hipError_t e = raise_dynamic_lds_once(reinterpret_cast<const void*>(&build_tree_cached_kernel<true>), bytes, done_vec);
-    if (e != hipSuccess) return e;
-    return raise_dynamic_lds_once(reinterpret_cast<const void*>(&build_tree_cached_kernel<false>), bytes, done_scalar);
+    const void* const kernels[6] = {
+        reinterpret_cast<const void*>(&build_tree_cached_kernel<true, 1>), reinterpret_cast<const void*>(&build_tree_cached_kernel<true, 2>),
+        reinterpret_cast<const void*>(&build_tree_cached_kernel<true, 4>), reinterpret_cast<const void*>(&build_tree_cached_kernel<false, 1>),
+        reinterpret_cast<const void*>(&build_tree_cached_kernel<false, 2>), reinterpret_cast<const void*>(&build_tree_cached_kernel<false, 4>) };
+    for (int k = 0; k < 6; ++k) {
+        const hipError_t e = raise_dynamic_lds_once(kernels[k], bytes, done[k]);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+template <bool VEC>
+static void launch_cached(int slots, int n_seq, size_t dyn_bytes, hipStream_t stream, const float* draft_logits, int V, const SeqArgs& sa,
+                          uint64_t seed, const dyspec_tree& tree, float* est_value, uint64_t* anc_mask, int mask_words, int* n_built,
+                          double* ws)
+{
+    if (slots == 1)
+        build_tree_cached_kernel<VEC, 1><<<n_seq, kBlock, dyn_bytes, stream>>>(draft_logits, V, sa, seed, tree, est_value, anc_mask, mask_words, n_built, ws);
+    else if (slots == 2)
+        build_tree_cached_kernel<VEC, 2><<<n_seq, kBlock, dyn_bytes, stream>>>(draft_logits, V, sa, seed, tree, est_value, anc_mask, mask_words, n_built, ws);
+    else
+        build_tree_cached_kernel<VEC, 4><<<n_seq, kBlock, dyn_bytes, stream>>>(draft_logits, V, sa, seed, tree, est_value, anc_mask, mask_words, n_built, ws);
 }
 
 size_t build_tree_workspace_bytes(int total_rows) { return (size_t)total_rows * kRowSumDoubles * sizeof(double); }
@@ -512,12 +534,12 @@ hipError_t launch_build_tree(const float* draft_logits, int V, const SeqArgs& sa
         if (ea != hipSuccess) return ea;
         if (V % 4 == 0) {
             draft_row_sums_kernel<true><<<rows, kBlock, 0, stream>>>(draft_logits, V, sa, ws);
-            build_tree_cached_kernel<true><<<sa.n_seq, kBlock, dyn_bytes, stream>>>(draft_logits, V, sa, seed, tree, est_value,
-                                                                                     anc_mask, mask_words, n_built, ws);
+            launch_cached<true>(slots_per_thread(widest), sa.n_seq, dyn_bytes, stream, draft_logits, V, sa, seed, tree, est_value, anc_mask,
+                                mask_words, n_built, ws);
         } else {
             draft_row_sums_kernel<false><<<rows, kBlock, 0, stream>>>(draft_logits, V, sa, ws);
-            build_tree_cached_kernel<false><<<sa.n_seq, kBlock, dyn_bytes, stream>>>(draft_logits, V, sa, seed, tree, est_value,
-                                                                                      anc_mask, mask_words, n_built, ws);
+            launch_cached<false>(slots_per_thread(widest), sa.n_seq, dyn_bytes, stream, draft_logits, V, sa, seed, tree, est_value, anc_mask,
+                                 mask_words, n_built, ws);
         }
     } else if (V % 4 == 0) {
         build_tree_kernel<true><<<sa.n_seq, kBlock, 0, stream>>>(draft_logits, V, sa, seed, tree, est_value,
