@@ -44,5 +44,5 @@ def test_no_host_stall_over_a_thousand_dispatches():
     finally:
         gc.unfreeze()
     print(f"host time per call: median {np.median(host) * 1e6:.1f} us, max {host.max() * 1e3:.2f} ms", flush=True)
-    assert host.max() < 5e-3           # a scheduling hiccup of the box stays far below the old 35 ms stall
+    assert host.max() < 1e-3           # measured: 0.14 ms at most (the first call after a synchronisation); the old stall was 35 ms
     assert np.median(host) < 2e-4
