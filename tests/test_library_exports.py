@@ -141,3 +141,19 @@ def test_tree_attention_cut_by_shape():
         assert lib.dyspec_workspace_bytes(1, ctypes.byref(c), 0, Hq, Hkv, 128) == 4096 + groups * parts * part
     c = binding.Batch.from_sizes((512,), (4096,))._c()
     assert lib.dyspec_workspace_bytes(1, ctypes.byref(c), 0, 64, 8, 128) == 0           # 256 workgroups: no split
+
+
+def test_prepared_call_reports_the_status_of_every_issue():
+    """A prepared call is the C call with its arguments kept: each issue returns `out` or raises
+    with the library's status (here a misaligned fake address: nothing is launched, no GPU needed)."""
+    import pytest
+    from paper_2410_11744_amd import binding
+    lib = binding.load_library()
+    c = binding.Batch.from_sizes([40, 9], [100, 64])._c()
+    A = 0x7f0000001000
+    args = (A + 8, A, A, A, A, A, ctypes.byref(c), 8, 2, 128, binding.BF16, ctypes.c_float(0.1), A, None, ctypes.c_size_t(0), None)
+    call = binding.PreparedCall(lib.dyspec_tree_attn, args, (c,), "dyspec_tree_attn", "the output")
+    for _ in range(2):
+        with pytest.raises(binding.DyspecError) as e:
+            call()
+        assert e.value.status == -1
